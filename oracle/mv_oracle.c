@@ -1,0 +1,288 @@
+/*
+ * mv_oracle.c -- TEST INFRASTRUCTURE, NOT THE PRODUCT.
+ *
+ * A plain, slow, obviously-correct CPU statement of what one iteration of
+ * sparse SGD with majority voting computes between "the worker has its model
+ * difference" and "the error buffer is updated" (Algorithm 1 of the paper,
+ * the steps from error compensation to the aggregate).  Only tests, the smoke
+ * check and the benchmark's cpu_baseline leg may call this file.  It shares
+ * no code, header, table or helper with the HIP library.
+ *
+ * Precision: the paper fixes 32-bit floating point for every value (Sec. 1.2.1
+ * and Sec. 2.1, q = 32), so the arithmetic that decides a mask
+ * is done in fp32 here, with round-to-nearest-even, denormals kept, and no
+ * fused multiply-add (build with -ffp-contract=off, never -ffast-math).
+ *
+ * Every selection is the definition written out: build all (value, index)
+ * pairs, sort ALL of them with the C library's qsort under the stated total
+ * order, keep the first K.  No histograms, no partial selection, no blocking.
+ *
+ * Readings of the paper where it is silent (each one is also listed in the
+ * design notes of the repository):
+ *   - S_top ties (Sec. 2, definition of S_top; Sec. 2, vote description):
+ *     larger value first, then LOWEST INDEX first; used for the per-worker
+ *     selection and for the selection over vote counts.  The paper does not
+ *     fix a tie rule: the tie-break is "parity unpinned" by the paper and
+ *     pinned only by this build's contract.
+ *   - "highest absolute value" is the order of the fp32 bit pattern with the
+ *     sign bit cleared: -0 == +0, denormals are ordered (not flushed), +Inf is
+ *     above every finite value, NaNs above Inf by payload.
+ *   - The aggregate is a mean (Sec. 2, definition of G-tilde and the linearity
+ *     equation) although Algorithm 1's last step prints a plain sum; the sum is
+ *     available through `reduce_mean = 0`.  The sum runs over workers in order
+ *     n = 0..N-1 in fp32 and is then multiplied once by fp32 (1/N).
+ *   - The error update uses the GLOBAL mask (Algorithm 1, "e = Delta-bar minus
+ *     Delta-tilde_n"): the residual is exactly zero (+0.0) on the mask and the
+ *     compensated value elsewhere.
+ */
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#include <math.h>
+
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* ------------------------------------------------------------------ */
+/* helpers                                                             */
+/* ------------------------------------------------------------------ */
+
+static uint32_t f32_bits(float x)
+{
+    uint32_t u;
+    memcpy(&u, &x, sizeof u);
+    return u;
+}
+
+/* magnitude key: the fp32 bit pattern with the sign bit cleared */
+static uint32_t magnitude_key(float x) { return f32_bits(x) & 0x7FFFFFFFu; }
+
+typedef struct {
+    uint32_t value; /* magnitude key, or vote count */
+    uint32_t index; /* coordinate j */
+} mvo_pair;
+
+/* total order of S_top with this build's tie rule:
+ * larger value first; among equal values the lower index first */
+static int cmp_value_desc_index_asc(const void* pa, const void* pb)
+{
+    const mvo_pair* a = (const mvo_pair*)pa;
+    const mvo_pair* b = (const mvo_pair*)pb;
+    if (a->value != b->value) return (a->value > b->value) ? -1 : 1;
+    if (a->index != b->index) return (a->index < b->index) ? -1 : 1;
+    return 0;
+}
+
+static int cmp_u32_asc(const void* pa, const void* pb)
+{
+    uint32_t a = *(const uint32_t*)pa, b = *(const uint32_t*)pb;
+    return (a > b) - (a < b);
+}
+
+/* S_top over an array of non-negative integer "values" of length d:
+ * the K coordinates that come first under (value desc, index asc),
+ * written in ascending index order.  Returns 0, or -1 on bad arguments
+ * or allocation failure. */
+static int s_top_indices(const uint32_t* values, int64_t d, int64_t K, uint32_t* idx_out)
+{
+    if (d <= 0 || K < 0 || K > d) return -1;
+    mvo_pair* pairs = (mvo_pair*)malloc((size_t)d * sizeof(mvo_pair));
+    if (!pairs) return -1;
+    for (int64_t j = 0; j < d; ++j) {
+        pairs[j].value = values[j];
+        pairs[j].index = (uint32_t)j;
+    }
+    qsort(pairs, (size_t)d, sizeof(mvo_pair), cmp_value_desc_index_asc);
+    for (int64_t k = 0; k < K; ++k) idx_out[k] = pairs[k].index;
+    qsort(idx_out, (size_t)K, sizeof(uint32_t), cmp_u32_asc);
+    free(pairs);
+    return 0;
+}
+
+/* ------------------------------------------------------------------ */
+/* the steps of Algorithm 1, one function each                          */
+/* ------------------------------------------------------------------ */
+
+/* bf16 -> fp32 is exact: the 16 bits are the upper half of the fp32 pattern.
+ * (bf16 gradients are an extension of this build's workloads; the paper uses
+ * fp32 throughout.) */
+void mvo_widen_bf16(const uint16_t* g_bf16, float* g_f32, int64_t d)
+{
+    for (int64_t j = 0; j < d; ++j) {
+        uint32_t u = ((uint32_t)g_bf16[j]) << 16;
+        memcpy(&g_f32[j], &u, sizeof u);
+    }
+}
+
+/* Algorithm 1, error compensation: Delta-bar = Delta + e, one fp32 add. */
+void mvo_error_compensate(const float* delta, const float* e, float* delta_bar, int64_t d)
+{
+    for (int64_t j = 0; j < d; ++j) delta_bar[j] = delta[j] + e[j];
+}
+
+/* Algorithm 1, local mask: supp(S_top(|Delta-bar|, K)) for one worker. */
+int mvo_row_topk(const float* delta_bar, int64_t d, int64_t K, uint32_t* idx_out)
+{
+    if (d <= 0) return -1;
+    uint32_t* keys = (uint32_t*)malloc((size_t)d * sizeof(uint32_t));
+    if (!keys) return -1;
+    for (int64_t j = 0; j < d; ++j) keys[j] = magnitude_key(delta_bar[j]);
+    int rc = s_top_indices(keys, d, K, idx_out);
+    free(keys);
+    return rc;
+}
+
+/* Sec. 2, "the PS counts the votes for all the positions":
+ * votes = sum over workers of the 0/1 local masks. */
+int mvo_votes(const uint32_t* worker_idx, int32_t N, int64_t K, int64_t d, uint8_t* votes)
+{
+    if (N < 1 || N > 255) return -1;
+    memset(votes, 0, (size_t)d);
+    for (int32_t n = 0; n < N; ++n)
+        for (int64_t k = 0; k < K; ++k) {
+            uint32_t j = worker_idx[(int64_t)n * K + k];
+            if ((int64_t)j >= d) return -1;
+            votes[j] += 1;
+        }
+    return 0;
+}
+
+/* Sec. 2, mask equation, outer S_top: the K most voted coordinates. */
+int mvo_mask(const uint8_t* votes, int64_t d, int64_t K, uint32_t* mask_idx)
+{
+    if (d <= 0) return -1;
+    uint32_t* v = (uint32_t*)malloc((size_t)d * sizeof(uint32_t));
+    if (!v) return -1;
+    for (int64_t j = 0; j < d; ++j) v[j] = votes[j];
+    int rc = s_top_indices(v, d, K, mask_idx);
+    free(v);
+    return rc;
+}
+
+/* Algorithm 1, "Delta-tilde_n = M (x) Delta-bar_n" then the aggregate over
+ * workers; the 1/N is the mean of Sec. 2's G-tilde.  delta_bar is N rows of
+ * stride ld. */
+void mvo_aggregate(const float* delta_bar, int64_t ld, int32_t N,
+                   const uint32_t* mask_idx, int64_t K, int32_t reduce_mean, float* agg)
+{
+    const float inv_N = 1.0f / (float)N;
+    for (int64_t k = 0; k < K; ++k) {
+        const uint32_t j = mask_idx[k];
+        float s = delta_bar[j]; /* worker 0 */
+        for (int32_t n = 1; n < N; ++n) s = s + delta_bar[(int64_t)n * ld + j];
+        agg[k] = reduce_mean ? s * inv_N : s;
+    }
+}
+
+/* Algorithm 1, error update for one worker: e_new = Delta-bar - Delta-tilde_n,
+ * which is +0.0 on the mask and Delta-bar elsewhere. */
+void mvo_error_update(const float* delta_bar, int64_t d,
+                      const uint32_t* mask_idx, int64_t K, float* e_new)
+{
+    for (int64_t j = 0; j < d; ++j) e_new[j] = delta_bar[j];
+    for (int64_t k = 0; k < K; ++k) e_new[mask_idx[k]] = 0.0f;
+}
+
+/* ------------------------------------------------------------------ */
+/* one whole vote step                                                 */
+/* ------------------------------------------------------------------ */
+
+/*
+ * grads      : N rows, stride ld_g elements; fp32 (grad_is_bf16 = 0) or bf16
+ * err        : N rows, stride ld_e, fp32; in: e_t, out: e_{t+1}
+ * worker_idx : N x K out, each row ascending
+ * votes      : d out
+ * mask_idx   : K out, ascending
+ * agg        : K out
+ * threads    : >1 runs the row-local steps (compensation, local top-K) with
+ *              one OpenMP task per worker row; the arithmetic is unchanged.
+ * Returns 0 on success, -1 on bad arguments / allocation failure.
+ */
+int mvo_vote_step(const void* grads, int64_t ld_g, int32_t grad_is_bf16,
+                  float* err, int64_t ld_e,
+                  int32_t N, int64_t d, int64_t K, int32_t reduce_mean,
+                  uint32_t* worker_idx, uint8_t* votes, uint32_t* mask_idx, float* agg,
+                  int32_t threads)
+{
+    if (N < 1 || N > 255 || d < 1 || d > 0x7FFFFFFF || K < 1 || K > d) return -1;
+    if (ld_g < d || ld_e < d) return -1;
+    if (threads < 1) threads = 1;
+
+    float* delta_bar = (float*)malloc((size_t)N * (size_t)d * sizeof(float));
+    if (!delta_bar) return -1;
+    int failed = 0;
+
+#ifdef _OPENMP
+#pragma omp parallel for num_threads(threads) schedule(dynamic, 1)
+#endif
+    for (int32_t n = 0; n < N; ++n) {
+        float* row = delta_bar + (int64_t)n * d;
+        if (grad_is_bf16) {
+            float* wide = (float*)malloc((size_t)d * sizeof(float));
+            if (!wide) {
+                failed = 1;
+                continue;
+            }
+            mvo_widen_bf16((const uint16_t*)grads + (int64_t)n * ld_g, wide, d);
+            mvo_error_compensate(wide, err + (int64_t)n * ld_e, row, d);
+            free(wide);
+        } else {
+            mvo_error_compensate((const float*)grads + (int64_t)n * ld_g,
+                                 err + (int64_t)n * ld_e, row, d);
+        }
+        if (mvo_row_topk(row, d, K, worker_idx + (int64_t)n * K) != 0) failed = 1;
+    }
+    if (failed) {
+        free(delta_bar);
+        return -1;
+    }
+
+    if (mvo_votes(worker_idx, N, K, d, votes) != 0 || mvo_mask(votes, d, K, mask_idx) != 0) {
+        free(delta_bar);
+        return -1;
+    }
+    mvo_aggregate(delta_bar, d, N, mask_idx, K, reduce_mean, agg);
+
+#ifdef _OPENMP
+#pragma omp parallel for num_threads(threads) schedule(dynamic, 1)
+#endif
+    for (int32_t n = 0; n < N; ++n)
+        mvo_error_update(delta_bar + (int64_t)n * d, d, mask_idx, K, err + (int64_t)n * ld_e);
+
+    free(delta_bar);
+    return 0;
+}
+
+/* ------------------------------------------------------------------ */
+/* communication-load arithmetic (Sec. 2.1 and Sec. 4.4), reporting only */
+/* ------------------------------------------------------------------ */
+
+/* bits per transmitted position: log2(1/phi) rounded up to whole bits, plus
+ * the one-bit "position follows" flag and the amortised end-of-block bit
+ * (Sec. 2.1, Q_loc; Sec. 4.3.1).  phi is given as the block length 1/phi. */
+int32_t mvo_bits_per_position(double inv_phi)
+{
+    int32_t b = 0;
+    while (ldexp(1.0, b) < inv_phi) ++b; /* smallest b with 2^b >= 1/phi */
+    return b + 2;
+}
+
+/* Q_val = q * phi * d  (Sec. 2.1) */
+double mvo_q_val(double q_bits, double phi, double d) { return q_bits * phi * d; }
+
+/* Q_loc = d * phi * (log(1/phi) + 2)  (Sec. 2.1) */
+double mvo_q_loc(double phi, double d) { return d * phi * (double)mvo_bits_per_position(1.0 / phi); }
+
+/* per-parameter budgets q-bar = Q / (d H) and the compression rate
+ * 32 / (q-bar_loc + q-bar_val)  (Sec. 4.4, discussion of Table 1) */
+double mvo_compression(double qbar_loc, double qbar_val) { return 32.0 / (qbar_loc + qbar_val); }
+
+int32_t mvo_max_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}

@@ -1,0 +1,198 @@
+"""ctypes front end of the CPU oracle (oracle/mv_oracle.c).
+
+TEST INFRASTRUCTURE, NOT THE PRODUCT: only tests, the smoke check and the
+benchmark's cpu_baseline leg import this module.  It never imports the HIP
+package and the HIP package never imports it.
+
+All arrays are numpy arrays on the host.  Function names follow the steps of
+Algorithm 1 of the paper (error compensation, local top-K mask, vote count,
+global mask, aggregate, error update).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "mv_oracle.c")
+_LIB = os.path.join(_HERE, "libmv_oracle.so")
+
+# No -ffast-math, no contraction: the oracle's fp32 arithmetic must be the
+# plain IEEE operations the paper's 32-bit values imply.
+_CFLAGS = ["-O2", "-std=c11", "-fPIC", "-shared", "-ffp-contract=off", "-fopenmp", "-Wall", "-Wextra"]
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc; returns the path of the shared library."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp.%d" % os.getpid()
+        subprocess.run(["gcc", *_CFLAGS, _SRC, "-o", tmp, "-lm"], check=True)
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        L = ctypes.CDLL(build())
+        i32, i64, vp, dbl = ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p, ctypes.c_double
+        L.mvo_widen_bf16.argtypes = [vp, vp, i64]
+        L.mvo_widen_bf16.restype = None
+        L.mvo_error_compensate.argtypes = [vp, vp, vp, i64]
+        L.mvo_error_compensate.restype = None
+        L.mvo_row_topk.argtypes = [vp, i64, i64, vp]
+        L.mvo_row_topk.restype = i32
+        L.mvo_votes.argtypes = [vp, i32, i64, i64, vp]
+        L.mvo_votes.restype = i32
+        L.mvo_mask.argtypes = [vp, i64, i64, vp]
+        L.mvo_mask.restype = i32
+        L.mvo_aggregate.argtypes = [vp, i64, i32, vp, i64, i32, vp]
+        L.mvo_aggregate.restype = None
+        L.mvo_error_update.argtypes = [vp, i64, vp, i64, vp]
+        L.mvo_error_update.restype = None
+        L.mvo_vote_step.argtypes = [vp, i64, i32, vp, i64, i32, i64, i64, i32, vp, vp, vp, vp, i32]
+        L.mvo_vote_step.restype = i32
+        L.mvo_bits_per_position.argtypes = [dbl]
+        L.mvo_bits_per_position.restype = i32
+        L.mvo_q_val.argtypes = [dbl, dbl, dbl]
+        L.mvo_q_val.restype = dbl
+        L.mvo_q_loc.argtypes = [dbl, dbl]
+        L.mvo_q_loc.restype = dbl
+        L.mvo_compression.argtypes = [dbl, dbl]
+        L.mvo_compression.restype = dbl
+        L.mvo_max_threads.argtypes = []
+        L.mvo_max_threads.restype = i32
+        _lib = L
+    return _lib
+
+
+def _ptr(a: np.ndarray) -> int:
+    return a.ctypes.data
+
+
+def _c(a, dtype) -> np.ndarray:
+    a = np.ascontiguousarray(a, dtype=dtype)
+    return a
+
+
+# ---------------------------------------------------------------- steps
+
+def widen_bf16(g_bf16: np.ndarray) -> np.ndarray:
+    g = _c(g_bf16, np.uint16)
+    out = np.empty(g.shape, np.float32)
+    lib().mvo_widen_bf16(_ptr(g), _ptr(out), g.size)
+    return out
+
+
+def error_compensate(delta: np.ndarray, e: np.ndarray) -> np.ndarray:
+    delta, e = _c(delta, np.float32), _c(e, np.float32)
+    assert delta.shape == e.shape
+    out = np.empty_like(delta)
+    lib().mvo_error_compensate(_ptr(delta), _ptr(e), _ptr(out), delta.size)
+    return out
+
+
+def row_topk(delta_bar_row: np.ndarray, K: int) -> np.ndarray:
+    row = _c(delta_bar_row, np.float32)
+    assert row.ndim == 1
+    idx = np.empty(K, np.uint32)
+    rc = lib().mvo_row_topk(_ptr(row), row.size, K, _ptr(idx))
+    if rc != 0:
+        raise ValueError("mvo_row_topk rejected its arguments")
+    return idx
+
+
+def votes(worker_idx: np.ndarray, d: int) -> np.ndarray:
+    w = _c(worker_idx, np.uint32)
+    assert w.ndim == 2
+    out = np.empty(d, np.uint8)
+    rc = lib().mvo_votes(_ptr(w), w.shape[0], w.shape[1], d, _ptr(out))
+    if rc != 0:
+        raise ValueError("mvo_votes rejected its arguments")
+    return out
+
+
+def mask(votes_: np.ndarray, K: int) -> np.ndarray:
+    v = _c(votes_, np.uint8)
+    out = np.empty(K, np.uint32)
+    rc = lib().mvo_mask(_ptr(v), v.size, K, _ptr(out))
+    if rc != 0:
+        raise ValueError("mvo_mask rejected its arguments")
+    return out
+
+
+def aggregate(delta_bar: np.ndarray, mask_idx: np.ndarray, reduce_mean: bool = True) -> np.ndarray:
+    a = _c(delta_bar, np.float32)
+    m = _c(mask_idx, np.uint32)
+    assert a.ndim == 2
+    out = np.empty(m.size, np.float32)
+    lib().mvo_aggregate(_ptr(a), a.shape[1], a.shape[0], _ptr(m), m.size, int(reduce_mean), _ptr(out))
+    return out
+
+
+def error_update(delta_bar_row: np.ndarray, mask_idx: np.ndarray) -> np.ndarray:
+    a = _c(delta_bar_row, np.float32)
+    m = _c(mask_idx, np.uint32)
+    out = np.empty_like(a)
+    lib().mvo_error_update(_ptr(a), a.size, _ptr(m), m.size, _ptr(out))
+    return out
+
+
+# ---------------------------------------------------------------- whole step
+
+@dataclass
+class StepResult:
+    worker_idx: np.ndarray  # N x K uint32, rows ascending
+    votes: np.ndarray       # d uint8
+    mask_idx: np.ndarray    # K uint32 ascending
+    agg: np.ndarray         # K float32
+    err: np.ndarray         # N x d float32 (e_{t+1})
+
+
+def vote_step(grads: np.ndarray, err: np.ndarray, K: int, reduce_mean: bool = True,
+              threads: int = 1) -> StepResult:
+    """One vote step.  grads: N x d float32, or uint16 holding bf16 patterns.
+    err: N x d float32 (not modified; the new error buffer is returned)."""
+    assert grads.ndim == 2 and err.shape == grads.shape
+    is_bf16 = grads.dtype == np.uint16
+    g = _c(grads, np.uint16 if is_bf16 else np.float32)
+    e = np.array(err, dtype=np.float32, order="C", copy=True)
+    N, d = g.shape
+    widx = np.empty((N, K), np.uint32)
+    v = np.empty(d, np.uint8)
+    m = np.empty(K, np.uint32)
+    agg = np.empty(K, np.float32)
+    rc = lib().mvo_vote_step(_ptr(g), d, int(is_bf16), _ptr(e), d, N, d, K, int(reduce_mean),
+                             _ptr(widx), _ptr(v), _ptr(m), _ptr(agg), int(threads))
+    if rc != 0:
+        raise ValueError("mvo_vote_step rejected its arguments")
+    return StepResult(widx, v, m, agg, e)
+
+
+# ---------------------------------------------------------------- comm load
+
+def bits_per_position(inv_phi: float) -> int:
+    return int(lib().mvo_bits_per_position(float(inv_phi)))
+
+
+def q_val(q_bits: float, phi: float, d: float) -> float:
+    return float(lib().mvo_q_val(q_bits, phi, d))
+
+
+def q_loc(phi: float, d: float) -> float:
+    return float(lib().mvo_q_loc(phi, d))
+
+
+def compression(qbar_loc: float, qbar_val: float) -> float:
+    return float(lib().mvo_compression(qbar_loc, qbar_val))
+
+
+def max_threads() -> int:
+    return int(lib().mvo_max_threads())
