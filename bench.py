@@ -1,0 +1,223 @@
+#!/usr/bin/env python3
+"""Benchmark of the vote step (Algorithm 1, error compensation .. error update)
+on one MI355X.
+
+One "step" is one mv_vote_step() call: the whole hot path over one batch of
+synthetic gradients (N x d), inputs resident in HBM.  The error buffer is
+carried from step to step as in training; the gradients cycle over a few
+distinct pre-generated matrices.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C4]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+from concurrent.futures import ThreadPoolExecutor
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0      # MI355X published HBM3E peak
+
+
+def log(msg):
+    print("[bench] " + msg, file=sys.stderr, flush=True)
+
+
+def gen_gradients(W, w, step, pool):
+    import numpy as np
+    common = W.common_component(w, step)
+    scale = W.coordinate_scale(w)
+    out = np.empty((w.N, w.d), np.uint16 if w.grad_dtype == "bf16" else np.float32)
+
+    def one(n):
+        out[n] = W.gradient_row(w, step, n, common, scale)
+    list(pool.map(one, range(w.N)))
+    return out
+
+
+def comm_load_context(w):
+    """The paper's closed-form communication load for this (d, phi), q = 32, H = 1
+    (Sec. 2.1): context printed beside the measurement."""
+    import math
+    bits = math.ceil(math.log2(w.d / w.K) - 1e-12) + 2
+    q_loc = w.K * bits
+    q_val = 32 * w.K
+    return {"bits_per_position": bits, "Q_loc_bits": q_loc, "Q_val_bits": q_val,
+            "compression": round(32.0 * w.d / (q_loc + q_val), 1)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="C4", choices=["C1", "C2", "C3", "C4", "C5"])
+    ap.add_argument("--grad-sets", type=int, default=2, help="distinct gradient matrices cycled over")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--profile-level", type=int, default=1, choices=[0, 1, 2],
+                    help="HIP events inside the timed region: 1 = dominant kernel only, 2 = every kernel")
+    ap.add_argument("--breakdown", action="store_true",
+                    help="after the timed region, run extra untimed steps with events around every kernel")
+    args = ap.parse_args()
+
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2011_06495_amd import binding as B
+    from paper_2011_06495_amd import build as mv_build
+    from paper_2011_06495_amd import workloads as W
+
+    if not os.path.exists(B.LIB_PATH):
+        mv_build.build_lib()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    w = W.WORKLOADS[args.workload]
+    bf16 = w.grad_dtype == "bf16"
+    N, d, K = w.N, w.d, w.K
+    ld_g = (d + (7 if bf16 else 3)) // (8 if bf16 else 4) * (8 if bf16 else 4)
+    ld_e = (d + 3) // 4 * 4
+
+    # ---- inputs: generated on the host from seeds, then resident in HBM
+    t0 = time.time()
+    pool = ThreadPoolExecutor(max_workers=min(16, os.cpu_count() or 1))
+    g_host0 = None
+    g_dev = []
+    for s in range(max(1, args.grad_sets)):
+        gh = gen_gradients(W, w, s, pool)
+        if s == 0:
+            g_host0 = gh
+        t = torch.zeros((N, ld_g), dtype=torch.int16 if bf16 else torch.float32, device=dev)
+        t[:, :d].copy_(torch.from_numpy(gh.view(np.int16) if bf16 else gh))
+        g_dev.append(t)
+    log("generated %d gradient sets of %s (N=%d d=%d K=%d) in %.1f s" % (len(g_dev), w.name, N, d, K, time.time() - t0))
+
+    e_dev = torch.zeros((N, ld_e), dtype=torch.float32, device=dev)
+    widx = torch.zeros((N, K), dtype=torch.int32, device=dev)
+    votes = torch.zeros(d, dtype=torch.uint8, device=dev)
+    mask = torch.zeros(K, dtype=torch.int32, device=dev)
+    agg = torch.zeros(K, dtype=torch.float32, device=dev)
+    ctx = B.mv_begin(B.make_config(N, d, K, B.MV_BF16 if bf16 else B.MV_F32))
+    stream = torch.cuda.current_stream(dev)
+
+    def step(i):
+        B.mv_vote_step(ctx, g_dev[i % len(g_dev)], e_dev, widx, votes, mask, agg, stream=stream,
+                       ld_g=ld_g, ld_e=ld_e)
+
+    # ---- step 0 result kept for the check against the oracle
+    step(0)
+    torch.cuda.synchronize()
+    mask0 = mask.cpu().numpy().view(np.uint32).copy()
+    agg0 = agg.cpu().numpy().copy()
+    cand, tau, slow = B.mv_last_step_row_stats(ctx, N)
+    log("step 0: candidates per row min/max %d/%d, slow-path rows %d" % (min(cand), max(cand), sum(slow)))
+
+    # ---- warmup, then the timed region
+    B.mv_set_profiling(ctx, args.profile_level)
+    for i in range(args.warmup):
+        step(1 + i)
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for i in range(args.steps):
+        step(1 + args.warmup + i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+
+    names = B.kernel_names()
+    dom = names.index("mv_stream_collect")
+    dom_ms = []
+    per_kernel = {}
+    if args.profile_level > 0:
+        for back in range(min(args.steps, 64)):
+            ms = B.mv_step_kernel_ms(ctx, back)
+            dom_ms.append(ms[dom])
+            if args.profile_level == 2:
+                for nme, v in zip(names, ms):
+                    per_kernel.setdefault(nme, []).append(v)
+    _, _, slow_last = B.mv_last_step_row_stats(ctx, N)
+
+    breakdown = None
+    if args.breakdown:
+        B.mv_set_profiling(ctx, 2)
+        acc = {n: [] for n in names}
+        for i in range(10):
+            step(1000 + i)
+            torch.cuda.synchronize()
+            for nme, v in zip(names, B.mv_step_kernel_ms(ctx, 0)):
+                acc[nme].append(v)
+        breakdown = {n: round(float(np.median(v)) * 1e3, 2) for n, v in acc.items()}   # microseconds
+    B.mv_set_profiling(ctx, 0)
+
+    coords = float(N) * float(d)
+    ms_per_step = elapsed / args.steps * 1e3
+    value = coords * args.steps / elapsed
+    bytes_per_coord = 10.0 if bf16 else 12.0      # read g, read e, write e
+    roofline = None
+    if dom_ms:
+        avg_ms = float(np.mean(dom_ms))
+        achieved = bytes_per_coord * coords / (avg_ms * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "kernel": "mv_stream_collect", "achieved": round(achieved, 1),
+                    "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                    "traffic": None, "avg_kernel_ms": round(avg_ms, 4),
+                    "algorithmic_bytes_per_launch": bytes_per_coord * coords}
+    step_frac = bytes_per_coord * coords / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS
+
+    # ---- the oracle on the host, same inputs as step 0 (one full step)
+    cpu_baseline = None
+    oracle_agrees = None
+    if not args.no_cpu_baseline:
+        from oracle import mv_oracle
+        threads = max(1, min(N, mv_oracle.max_threads(), 16))
+        e0 = np.zeros((N, d), np.float32)
+        log("timing the oracle on one step of %s with %d threads ..." % (w.name, threads))
+        t1 = time.perf_counter()
+        ref = mv_oracle.vote_step(g_host0, e0, K, threads=threads)
+        t_or = time.perf_counter() - t1
+        oracle_agrees = bool(np.array_equal(ref.mask_idx, mask0) and
+                             np.array_equal(ref.agg.view(np.uint32), agg0.view(np.uint32)))
+        cpu_baseline = {"value": round(coords / t_or, 1), "unit": "coords/s", "cores": threads,
+                        "kind": "oracle", "seconds": round(t_or, 2),
+                        "sample": "one full vote step of %s (all %d rows, d=%d), step-0 inputs" % (w.name, N, d)}
+
+    B.mv_end(ctx)
+    B.mv_release(ctx)
+
+    out = {
+        "metric": "vote-step throughput (N*d coords/sec), 1 GPU",
+        "value": round(value, 1),
+        "unit": "coords/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": "%s: N=%d d=%d K=%d grads=%s, %s, error feedback carried" %
+                               (w.name, N, d, K, w.grad_dtype, w.kind),
+                   "N": N, "d": d, "K": K, "grad_sets_cycled": len(g_dev)},
+        "step_hbm_frac_algorithmic": round(step_frac, 4),
+        "roofline": roofline,
+        "cpu_baseline": cpu_baseline,
+        "oracle_agrees_on_step0": oracle_agrees,
+        "slow_path_rows_last_step": int(sum(slow_last)),
+        "paper_comm_load": comm_load_context(w),
+    }
+    if per_kernel:
+        out["kernel_us_in_timed_region"] = {n: round(float(np.mean(v)) * 1e3, 2) for n, v in per_kernel.items()}
+    if breakdown:
+        out["kernel_us_breakdown"] = breakdown
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

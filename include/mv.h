@@ -1,0 +1,157 @@
+/*
+ * mv.h -- C ABI of the majority-voting vote step for AMD MI355X (gfx950).
+ *
+ * One call of mv_vote_step() is one iteration of sparse SGD with majority
+ * voting for N workers whose vectors are held as an N x d matrix on one GPU
+ * (paper: Algorithm 1, from the error compensation to the error update):
+ *
+ *   a[n][j]      = g[n][j] + e[n][j]                      (error compensation)
+ *   worker_idx[n] = supp S_top(|a[n]|, K)                 (local mask, the vote)
+ *   votes[j]     = #{ n : j in worker_idx[n] }            (vote count, Sec. 2)
+ *   mask_idx     = supp S_top(votes, K)                   (global mask, Sec. 2 mask equation)
+ *   agg[k]       = (sum_n a[n][mask_idx[k]]) * (1/N)      (masked send + aggregate; mean of Sec. 2)
+ *   e[n][j]      = 0 if j in mask_idx else a[n][j]        (error update)
+ *
+ * S_top(x, K) marks the K entries with the highest values; the paper does not
+ * say how ties are broken.  Here ties go to the LOWEST index, both for the
+ * magnitudes of a row and for the vote counts.  "Highest absolute value" is the
+ * order of the fp32 bit pattern with the sign bit cleared (so -0 == +0,
+ * denormals are ordered and never flushed, +Inf is above all finite values).
+ *
+ * All tensor pointers are DEVICE pointers owned by the caller.  The library
+ * keeps none of them after a call returns, except cfg.workspace, which must
+ * outlive the context.  Nothing throws; every entry point returns a status.
+ */
+#ifndef MV_H
+#define MV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct mv_ctx mv_ctx; /* opaque */
+
+typedef enum {
+    MV_OK = 0,
+    MV_ERR_INVALID_ARG = 1, /* null pointer, size out of range, misalignment, bad struct_size */
+    MV_ERR_UNSUPPORTED = 2,
+    MV_ERR_ALLOC = 3,       /* device or host allocation failed */
+    MV_ERR_DEVICE = 4,      /* a HIP call failed */
+    MV_ERR_STATE = 5        /* context already ended */
+} mv_status;
+
+typedef enum { MV_F32 = 0, MV_BF16 = 1 } mv_dtype;          /* dtype of g only; e and agg are fp32 */
+typedef enum { MV_REDUCE_MEAN = 0, MV_REDUCE_SUM = 1 } mv_reduce;
+
+typedef struct {
+    uint32_t struct_size;   /* = sizeof(mv_config) */
+    int32_t  device;        /* HIP device ordinal */
+    int32_t  n_workers;     /* N, 1..255 (a vote count fits one byte) */
+    int32_t  grad_dtype;    /* mv_dtype */
+    int64_t  d;             /* coordinates per worker, 1 .. 2^31-1 */
+    int64_t  k;             /* K, 1 .. d */
+    int32_t  reduce;        /* mv_reduce; MEAN is Sec. 2's definition, SUM is Algorithm 1's last line */
+    int32_t  reserved;      /* must be 0 */
+    void*    workspace;     /* optional device scratch of >= mv_workspace_bytes(); NULL: the context allocates it */
+    size_t   workspace_bytes;
+} mv_config;
+
+/*
+ * Bytes of device scratch a context for this configuration needs.  Pure host
+ * arithmetic, no device call.  Returns 0 if the configuration is invalid.
+ */
+size_t mv_workspace_bytes(const mv_config* cfg);
+
+/*
+ * Creates a context: validates cfg on the host first (no device call is made
+ * for an invalid configuration), then allocates and zeroes the scratch.
+ * cfg.workspace, when given, must be 256-byte aligned device memory.
+ * Errors: MV_ERR_INVALID_ARG (null, struct_size, N, d, k, dtype, reduce,
+ * reserved != 0, workspace too small or misaligned), MV_ERR_ALLOC, MV_ERR_DEVICE.
+ */
+mv_status mv_begin(const mv_config* cfg, mv_ctx** out_ctx);
+
+/*
+ * One vote step (Algorithm 1, error compensation .. error update), enqueued on
+ * `stream`; returns without waiting for the GPU and allocates nothing.
+ *
+ *   grads      device, N rows of d elements (fp32 or bf16 per cfg), row stride ld_g elements
+ *   err        device, N rows of d fp32, row stride ld_e; in: e_t, out: e_{t+1} (in place)
+ *   worker_idx device, N x K uint32 out, row n = the coordinates worker n votes for,
+ *              ascending; may be NULL
+ *   votes      device, d bytes out, votes[j] in 0..N; may be NULL
+ *   mask_idx   device, K uint32 out, ascending
+ *   agg_vals   device, K fp32 out, agg_vals[k] belongs to coordinate mask_idx[k]
+ *   stream     hipStream_t, NULL = the default stream
+ *
+ * Only the first d elements of each row are read or written.  Row starts must
+ * be 16-byte aligned: base pointers 16-byte aligned, ld_g a multiple of 4
+ * (fp32) or 8 (bf16), ld_e a multiple of 4; mask_idx, agg_vals and worker_idx
+ * 4-byte aligned.  The buffers must not overlap each other.
+ *
+ * Argument errors are found on the host before anything is enqueued, so err is
+ * untouched when the call fails with MV_ERR_INVALID_ARG or MV_ERR_STATE.
+ * Calls on one context must not overlap in time (one stream at a time); distinct
+ * contexts are independent.  The result does not depend on earlier calls.
+ */
+mv_status mv_vote_step(mv_ctx* ctx,
+                       const void* grads, int64_t ld_g,
+                       float* err, int64_t ld_e,
+                       uint32_t* worker_idx,
+                       uint8_t* votes,
+                       uint32_t* mask_idx,
+                       float* agg_vals,
+                       void* stream);
+
+/*
+ * Ends the context: waits for the device, frees scratch the context allocated
+ * (never cfg.workspace).  The handle stays a valid pointer so that a later
+ * mv_vote_step / mv_end on it reports MV_ERR_STATE; mv_release frees it.
+ */
+mv_status mv_end(mv_ctx* ctx);
+
+/* Frees the handle itself (ends the context first if needed). NULL is allowed. */
+void mv_release(mv_ctx* ctx);
+
+/* Static string for a status code; never NULL, never freed. */
+const char* mv_status_string(mv_status s);
+
+/* ---- measurement hooks (not part of the method) ------------------------- */
+
+/* Number of kernels one vote step launches, and their names (static strings). */
+int32_t     mv_kernel_count(void);
+const char* mv_kernel_name(int32_t i);
+
+/*
+ * level 0: no events (default).  level 1: the step records a pair of HIP
+ * events around its dominant kernel (the streaming error-compensation pass).
+ * level 2: a pair around every kernel.
+ */
+mv_status mv_set_profiling(mv_ctx* ctx, int32_t level);
+
+/*
+ * Durations, in milliseconds, of the kernels of the step enqueued `steps_back`
+ * steps ago on this context (0 = the last one; the last 64 steps are kept),
+ * one per kernel in mv_kernel_name order, -1 for kernels that were not
+ * bracketed at the level then in force.  Waits for that step's events.  `ms`
+ * is a HOST array of n >= mv_kernel_count() floats.
+ */
+mv_status mv_step_kernel_ms(mv_ctx* ctx, int32_t steps_back, float* ms, int32_t n);
+
+/*
+ * Diagnostics of the LAST step (waits for the stream the step ran on): per
+ * worker row, how many candidates the streaming pass kept (cand_count), the
+ * magnitude bit pattern it compared against (threshold_bits) and whether the
+ * row had to take the slow exact path (slow_path: 0/1).  HOST arrays of N
+ * uint32 each; any may be NULL.
+ */
+mv_status mv_last_step_row_stats(mv_ctx* ctx, uint32_t* cand_count,
+                                 uint32_t* threshold_bits, uint32_t* slow_path);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MV_H */

@@ -1,0 +1,406 @@
+// Host side of the C ABI declared in include/mv.h: argument checks, scratch
+// layout, and the launch sequence of one vote step (Algorithm 1 of the paper,
+// error compensation .. error update).  Every step of the method runs in the
+// kernels of mv_kernels.hpp; nothing is computed on the host.
+#include "../../include/mv.h"
+#include "mv_kernels.hpp"
+
+#include <hip/hip_runtime.h>
+#include <new>
+#include <stdint.h>
+#include <string.h>
+
+namespace {
+
+enum KernelId {
+    KID_SAMPLE = 0,
+    KID_PICK,
+    KID_STREAM,
+    KID_ROW_FINISH,
+    KID_MASK_COUNT,
+    KID_MASK_EMIT,
+    KID_GATHER,
+    KID_COUNT
+};
+const char* const kKernelNames[KID_COUNT] = {"mv_sample_hist",  "mv_pick_threshold", "mv_stream_collect",
+                                             "mv_row_finish",   "mv_mask_count",     "mv_mask_emit",
+                                             "mv_gather_update"};
+
+constexpr size_t kAlign = 256;
+constexpr int kEventRing = 64;   // steps whose kernel durations stay readable
+inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+// Everything that follows from (N, d, K) alone.
+struct Plan {
+    uint32_t N, K;
+    int64_t  d;
+    uint32_t nseg;              // segments of 1024 coordinates per row
+    uint32_t stride;            // every stride-th 32-coordinate chunk is sampled
+    uint32_t n_sampled_chunks;  // per row
+    uint64_t n_sampled;         // sampled coordinates per row
+    uint32_t m_target;          // sampled coordinates that must lie at or above the threshold bin
+    uint32_t cap;               // candidate list capacity per row
+    uint32_t n_vote_blocks;
+    // scratch offsets (bytes)
+    size_t off_hist, off_tau, off_rowcnt, off_slow, off_cntge, off_seg, off_cand, off_votes, off_blockcnt;
+    size_t total_bytes;
+};
+
+bool config_valid(const mv_config* c)
+{
+    if (!c) return false;
+    if (c->struct_size != sizeof(mv_config)) return false;
+    if (c->n_workers < 1 || c->n_workers > 255) return false;
+    if (c->d < 1 || c->d > 0x7FFFFFFFll) return false;
+    if (c->k < 1 || c->k > c->d) return false;
+    if (c->grad_dtype != MV_F32 && c->grad_dtype != MV_BF16) return false;
+    if (c->reduce != MV_REDUCE_MEAN && c->reduce != MV_REDUCE_SUM) return false;
+    if (c->reserved != 0) return false;
+    if (c->device < 0) return false;
+    return true;
+}
+
+Plan make_plan(const mv_config* c)
+{
+    Plan p;
+    memset(&p, 0, sizeof p);
+    p.N = (uint32_t)c->n_workers;
+    p.K = (uint32_t)c->k;
+    p.d = c->d;
+    p.nseg = (uint32_t)((p.d + mvk::kSeg - 1) / mvk::kSeg);
+
+    // Sample about d/64 coordinates of each row, but at least ~64K when the row has them.
+    const uint64_t nchunks = (uint64_t)(p.d + mvk::kChunk - 1) / mvk::kChunk;
+    uint64_t stride = (uint64_t)p.d / ((uint64_t)mvk::kChunk * 65536u);
+    if (stride < 1) stride = 1;
+    if (stride > 64) stride = 64;
+    p.stride = (uint32_t)stride;
+    p.n_sampled_chunks = (uint32_t)((nchunks + stride - 1) / stride);
+    // all sampled chunks are full except possibly the row's last chunk
+    p.n_sampled = (uint64_t)p.n_sampled_chunks * mvk::kChunk;
+    if (((nchunks - 1) % stride) == 0) p.n_sampled -= (uint64_t)(nchunks * mvk::kChunk - (uint64_t)p.d);
+
+    // Aim at 3K coordinates above the threshold (in expectation), never fewer than
+    // 96 sampled ones, so that falling short of K is many standard deviations away.
+    const double frac = (double)p.n_sampled / (double)p.d;
+    double m = 3.0 * (double)p.K * frac;
+    if (m < 96.0) m = 96.0;
+    m += 1.0;
+    p.m_target = (m >= 4294967295.0) ? 0xFFFFFFFFu : (uint32_t)m;
+
+    uint64_t cap = 16ull * p.K;
+    if (cap < 65536) cap = 65536;
+    if (cap > (uint64_t)p.d) cap = (uint64_t)p.d;
+    p.cap = (uint32_t)cap;
+
+    p.n_vote_blocks = (uint32_t)((p.d + mvk::kVoteBlock - 1) / mvk::kVoteBlock);
+
+    size_t off = 0;
+    p.off_hist = off;     off += align_up((size_t)p.N * mvk::kHistBins * 4);
+    p.off_tau = off;      off += align_up((size_t)p.N * 4);
+    p.off_rowcnt = off;   off += align_up((size_t)p.N * 4);
+    p.off_slow = off;     off += align_up((size_t)p.N * 4);
+    p.off_cntge = off;    off += align_up(256 * 4);
+    p.off_seg = off;      off += align_up((size_t)p.N * p.nseg * 8);
+    p.off_cand = off;     off += align_up((size_t)p.N * p.cap * 8);
+    p.off_votes = off;    off += align_up(((size_t)p.d + 15) / 16 * 16);
+    p.off_blockcnt = off; off += align_up((size_t)p.n_vote_blocks * 8);
+    p.total_bytes = off;
+    return p;
+}
+
+}  // namespace
+
+struct mv_ctx {
+    mv_config  cfg;
+    Plan       plan;
+    char*      ws;          // device scratch
+    bool       owns_ws;
+    bool       ended;
+    int32_t    profiling;
+    // event pairs around kernels, a ring over the last kEventRing steps
+    hipEvent_t ev[kEventRing][KID_COUNT][2];
+    bool       ev_recorded[kEventRing][KID_COUNT];
+    uint64_t   steps_done;
+    hipStream_t last_stream;
+};
+
+namespace {
+
+template <typename T>
+T* ws_ptr(mv_ctx* c, size_t off) { return reinterpret_cast<T*>(c->ws + off); }
+
+struct DeviceGuard {
+    int  prev;
+    bool ok;
+    explicit DeviceGuard(int dev) : prev(0), ok(false)
+    {
+        if (hipGetDevice(&prev) != hipSuccess) return;
+        if (prev != dev && hipSetDevice(dev) != hipSuccess) return;
+        ok = true;
+    }
+    ~DeviceGuard() { if (ok) (void)hipSetDevice(prev); }
+};
+
+}  // namespace
+
+extern "C" {
+
+size_t mv_workspace_bytes(const mv_config* cfg)
+{
+    if (!config_valid(cfg)) return 0;
+    return make_plan(cfg).total_bytes;
+}
+
+mv_status mv_begin(const mv_config* cfg, mv_ctx** out_ctx)
+{
+    if (!out_ctx) return MV_ERR_INVALID_ARG;
+    *out_ctx = nullptr;
+    if (!config_valid(cfg)) return MV_ERR_INVALID_ARG;
+    const Plan plan = make_plan(cfg);
+    if (cfg->workspace) {
+        if (cfg->workspace_bytes < plan.total_bytes) return MV_ERR_INVALID_ARG;
+        if ((reinterpret_cast<uintptr_t>(cfg->workspace) & (kAlign - 1)) != 0) return MV_ERR_INVALID_ARG;
+    }
+
+    mv_ctx* c = new (std::nothrow) mv_ctx;
+    if (!c) return MV_ERR_ALLOC;
+    memset(c, 0, sizeof *c);
+    c->cfg = *cfg;
+    c->plan = plan;
+
+    DeviceGuard guard(cfg->device);
+    if (!guard.ok) {
+        delete c;
+        return MV_ERR_DEVICE;
+    }
+    if (cfg->workspace) {
+        c->ws = static_cast<char*>(cfg->workspace);
+        c->owns_ws = false;
+    } else {
+        void* p = nullptr;
+        if (hipMalloc(&p, plan.total_bytes) != hipSuccess) {
+            (void)hipGetLastError();
+            delete c;
+            return MV_ERR_ALLOC;
+        }
+        c->ws = static_cast<char*>(p);
+        c->owns_ws = true;
+    }
+    // The histogram and the packed vote words must start at zero; the kernels
+    // leave them at zero after every step.
+    bool ok = hipMemset(c->ws + plan.off_hist, 0, (size_t)plan.N * mvk::kHistBins * 4) == hipSuccess &&
+              hipMemset(c->ws + plan.off_votes, 0, ((size_t)plan.d + 15) / 16 * 16) == hipSuccess &&
+              hipMemset(c->ws + plan.off_tau, 0, plan.off_seg - plan.off_tau) == hipSuccess;
+    ok = ok && hipDeviceSynchronize() == hipSuccess;
+    if (!ok) {
+        (void)hipGetLastError();
+        if (c->owns_ws) (void)hipFree(c->ws);
+        delete c;
+        return MV_ERR_DEVICE;
+    }
+    *out_ctx = c;
+    return MV_OK;
+}
+
+mv_status mv_vote_step(mv_ctx* c, const void* grads, int64_t ld_g, float* err, int64_t ld_e,
+                       uint32_t* worker_idx, uint8_t* votes, uint32_t* mask_idx, float* agg_vals,
+                       void* stream_v)
+{
+    if (!c) return MV_ERR_INVALID_ARG;
+    if (c->ended) return MV_ERR_STATE;
+    if (!grads || !err || !mask_idx || !agg_vals) return MV_ERR_INVALID_ARG;
+    const Plan& p = c->plan;
+    const bool bf16 = c->cfg.grad_dtype == MV_BF16;
+    if (ld_g < p.d || ld_e < p.d) return MV_ERR_INVALID_ARG;
+    if (ld_g % (bf16 ? 8 : 4) != 0 || ld_e % 4 != 0) return MV_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(grads) & 15) || (reinterpret_cast<uintptr_t>(err) & 15))
+        return MV_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(mask_idx) & 3) || (reinterpret_cast<uintptr_t>(agg_vals) & 3) ||
+        (reinterpret_cast<uintptr_t>(worker_idx) & 3))
+        return MV_ERR_INVALID_ARG;
+
+    DeviceGuard guard(c->cfg.device);
+    if (!guard.ok) return MV_ERR_DEVICE;
+    hipStream_t st = static_cast<hipStream_t>(stream_v);
+
+    uint32_t* hist = ws_ptr<uint32_t>(c, p.off_hist);
+    uint32_t* tau = ws_ptr<uint32_t>(c, p.off_tau);
+    uint32_t* rowcnt = ws_ptr<uint32_t>(c, p.off_rowcnt);
+    uint32_t* slow = ws_ptr<uint32_t>(c, p.off_slow);
+    uint32_t* cntge = ws_ptr<uint32_t>(c, p.off_cntge);
+    mvk::u32x2* seg = ws_ptr<mvk::u32x2>(c, p.off_seg);
+    mvk::u32x2* cand = ws_ptr<mvk::u32x2>(c, p.off_cand);
+    uint32_t* votes32 = ws_ptr<uint32_t>(c, p.off_votes);
+    mvk::u32x2* blockcnt = ws_ptr<mvk::u32x2>(c, p.off_blockcnt);
+
+    const int slot = (int)(c->steps_done % kEventRing);
+    for (int i = 0; i < KID_COUNT; ++i) c->ev_recorded[slot][i] = false;
+    const int prof = c->profiling;
+    bool ev_ok = true;
+    auto wanted = [&](int kid) { return prof >= 2 || (prof == 1 && kid == KID_STREAM); };
+    auto before = [&](int kid) {
+        if (!wanted(kid)) return;
+        for (int j = 0; j < 2; ++j)   // events are created on first use
+            if (!c->ev[slot][kid][j] && hipEventCreate(&c->ev[slot][kid][j]) != hipSuccess) ev_ok = false;
+        if (ev_ok && hipEventRecord(c->ev[slot][kid][0], st) != hipSuccess) ev_ok = false;
+    };
+    auto after = [&](int kid) {
+        if (!wanted(kid) || !ev_ok) return;
+        if (hipEventRecord(c->ev[slot][kid][1], st) == hipSuccess) c->ev_recorded[slot][kid] = true;
+    };
+
+    // 1. sample histogram
+    {
+        const uint64_t nquads = (uint64_t)p.n_sampled_chunks * (mvk::kChunk / 4);
+        uint32_t bx = (uint32_t)((nquads + 255) / 256);
+        if (bx > 32) bx = 32;
+        if (bx < 1) bx = 1;
+        dim3 grid(bx, p.N);
+        before(KID_SAMPLE);
+        if (bf16)
+            hipLaunchKernelGGL(mvk::mv_sample_hist<uint16_t>, grid, dim3(256), 0, st,
+                               static_cast<const uint16_t*>(grads), ld_g, err, ld_e, p.d, p.stride,
+                               p.n_sampled_chunks, hist);
+        else
+            hipLaunchKernelGGL(mvk::mv_sample_hist<float>, grid, dim3(256), 0, st,
+                               static_cast<const float*>(grads), ld_g, err, ld_e, p.d, p.stride,
+                               p.n_sampled_chunks, hist);
+        after(KID_SAMPLE);
+    }
+    // 2. threshold estimate per row, counters reset
+    before(KID_PICK);
+    hipLaunchKernelGGL(mvk::mv_pick_threshold, dim3(p.N), dim3(mvk::kRowThreads), 0, st, hist, p.m_target,
+                       tau, rowcnt, slow, cntge);
+    after(KID_PICK);
+    // 3. streaming pass: a = g + e over e, candidates out
+    {
+        dim3 grid((p.nseg + mvk::kSegPerBlock - 1) / mvk::kSegPerBlock, p.N);
+        before(KID_STREAM);
+        if (bf16)
+            hipLaunchKernelGGL(mvk::mv_stream_collect<uint16_t>, grid, dim3(mvk::kStreamThreads), 0, st,
+                               static_cast<const uint16_t*>(grads), ld_g, err, ld_e, p.d, tau, cand, p.cap,
+                               rowcnt, seg, p.nseg);
+        else
+            hipLaunchKernelGGL(mvk::mv_stream_collect<float>, grid, dim3(mvk::kStreamThreads), 0, st,
+                               static_cast<const float*>(grads), ld_g, err, ld_e, p.d, tau, cand, p.cap,
+                               rowcnt, seg, p.nseg);
+        after(KID_STREAM);
+    }
+    // 4. exact per-row select, ordered vote lists, vote counting
+    before(KID_ROW_FINISH);
+    hipLaunchKernelGGL(mvk::mv_row_finish, dim3(p.N), dim3(mvk::kRowThreads), 0, st, err, ld_e, p.d, p.K, cand,
+                       p.cap, rowcnt, seg, p.nseg, worker_idx, votes32, cntge, slow);
+    after(KID_ROW_FINISH);
+    // 5. global mask
+    before(KID_MASK_COUNT);
+    hipLaunchKernelGGL(mvk::mv_mask_count, dim3(p.n_vote_blocks), dim3(mvk::kVoteThreads), 0, st, votes32, p.d,
+                       p.N, p.K, cntge, blockcnt, votes);
+    after(KID_MASK_COUNT);
+    before(KID_MASK_EMIT);
+    hipLaunchKernelGGL(mvk::mv_mask_emit, dim3(p.n_vote_blocks), dim3(mvk::kVoteThreads), 0, st, votes32, p.d,
+                       p.N, p.K, cntge, blockcnt, mask_idx);
+    after(KID_MASK_EMIT);
+    // 6. gather + mean + error update
+    {
+        const float inv_n = 1.0f / (float)p.N;
+        before(KID_GATHER);
+        hipLaunchKernelGGL(mvk::mv_gather_update, dim3((p.K + mvk::kGatherThreads - 1) / mvk::kGatherThreads),
+                           dim3(mvk::kGatherThreads), 0, st, err, ld_e, p.d, p.N, p.K, mask_idx, inv_n,
+                           c->cfg.reduce == MV_REDUCE_MEAN ? 1 : 0, agg_vals);
+        after(KID_GATHER);
+    }
+    c->last_stream = st;
+    c->steps_done += 1;
+    if (hipGetLastError() != hipSuccess || !ev_ok) return MV_ERR_DEVICE;
+    return MV_OK;
+}
+
+mv_status mv_end(mv_ctx* c)
+{
+    if (!c) return MV_ERR_INVALID_ARG;
+    if (c->ended) return MV_ERR_STATE;
+    c->ended = true;
+    DeviceGuard guard(c->cfg.device);
+    if (!guard.ok) return MV_ERR_DEVICE;
+    mv_status rc = MV_OK;
+    if (hipDeviceSynchronize() != hipSuccess) rc = MV_ERR_DEVICE;
+    for (int r = 0; r < kEventRing; ++r)
+        for (int i = 0; i < KID_COUNT; ++i)
+            for (int j = 0; j < 2; ++j)
+                if (c->ev[r][i][j]) (void)hipEventDestroy(c->ev[r][i][j]);
+    if (c->owns_ws && c->ws && hipFree(c->ws) != hipSuccess) rc = MV_ERR_DEVICE;
+    c->ws = nullptr;
+    return rc;
+}
+
+void mv_release(mv_ctx* c)
+{
+    if (!c) return;
+    if (!c->ended) (void)mv_end(c);
+    delete c;
+}
+
+const char* mv_status_string(mv_status s)
+{
+    switch (s) {
+        case MV_OK: return "ok";
+        case MV_ERR_INVALID_ARG: return "invalid argument";
+        case MV_ERR_UNSUPPORTED: return "unsupported";
+        case MV_ERR_ALLOC: return "allocation failed";
+        case MV_ERR_DEVICE: return "device error";
+        case MV_ERR_STATE: return "context already ended";
+    }
+    return "unknown status";
+}
+
+int32_t mv_kernel_count(void) { return KID_COUNT; }
+
+const char* mv_kernel_name(int32_t i) { return (i >= 0 && i < KID_COUNT) ? kKernelNames[i] : ""; }
+
+mv_status mv_set_profiling(mv_ctx* c, int32_t level)
+{
+    if (!c || level < 0 || level > 2) return MV_ERR_INVALID_ARG;
+    if (c->ended) return MV_ERR_STATE;
+    c->profiling = level;
+    return MV_OK;
+}
+
+mv_status mv_step_kernel_ms(mv_ctx* c, int32_t steps_back, float* ms, int32_t n)
+{
+    if (!c || !ms || n < KID_COUNT) return MV_ERR_INVALID_ARG;
+    if (c->ended) return MV_ERR_STATE;
+    if (steps_back < 0 || steps_back >= kEventRing || (uint64_t)steps_back >= c->steps_done)
+        return MV_ERR_INVALID_ARG;
+    DeviceGuard guard(c->cfg.device);
+    if (!guard.ok) return MV_ERR_DEVICE;
+    const int slot = (int)((c->steps_done - 1 - (uint64_t)steps_back) % kEventRing);
+    for (int i = 0; i < KID_COUNT; ++i) {
+        ms[i] = -1.0f;
+        if (!c->ev_recorded[slot][i]) continue;
+        if (hipEventSynchronize(c->ev[slot][i][1]) != hipSuccess) return MV_ERR_DEVICE;
+        if (hipEventElapsedTime(&ms[i], c->ev[slot][i][0], c->ev[slot][i][1]) != hipSuccess)
+            return MV_ERR_DEVICE;
+    }
+    return MV_OK;
+}
+
+mv_status mv_last_step_row_stats(mv_ctx* c, uint32_t* cand_count, uint32_t* threshold_bits, uint32_t* slow_path)
+{
+    if (!c) return MV_ERR_INVALID_ARG;
+    if (c->ended) return MV_ERR_STATE;
+    if (c->steps_done == 0) return MV_ERR_STATE;
+    DeviceGuard guard(c->cfg.device);
+    if (!guard.ok) return MV_ERR_DEVICE;
+    if (hipStreamSynchronize(c->last_stream) != hipSuccess) return MV_ERR_DEVICE;
+    const size_t nb = (size_t)c->plan.N * 4;
+    if (cand_count && hipMemcpy(cand_count, c->ws + c->plan.off_rowcnt, nb, hipMemcpyDeviceToHost) != hipSuccess)
+        return MV_ERR_DEVICE;
+    if (threshold_bits && hipMemcpy(threshold_bits, c->ws + c->plan.off_tau, nb, hipMemcpyDeviceToHost) != hipSuccess)
+        return MV_ERR_DEVICE;
+    if (slow_path && hipMemcpy(slow_path, c->ws + c->plan.off_slow, nb, hipMemcpyDeviceToHost) != hipSuccess)
+        return MV_ERR_DEVICE;
+    return MV_OK;
+}
+
+}  // extern "C"

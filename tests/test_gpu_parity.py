@@ -1,0 +1,242 @@
+"""Parity of the HIP path (through the C ABI) against the CPU oracle, element by
+element on the same seeded inputs.  Index sets, votes, mask and the error
+buffer must be bit-exact; the aggregate within 1e-6 relative (it is bit-exact,
+the worker order of the sum being fixed on both sides)."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2011_06495_amd import binding as B
+from paper_2011_06495_amd import workloads as W
+from tests.gpu_util import GpuStepper, assert_matches_oracle
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print("[case] " + msg, flush=True)
+    sys.stdout.flush()
+
+
+def run_sequence(oracle, w, steps, e0=None, threads=8, **kw):
+    """Runs `steps` consecutive vote steps on both sides with the error buffer
+    carried, comparing after every step."""
+    e_ref = W.zero_error(w) if e0 is None else e0.copy()
+    with GpuStepper(w.N, w.d, w.K, bf16=(w.grad_dtype == "bf16"), **kw) as gs:
+        gs.set_error(e_ref)
+        for t in range(steps):
+            g = W.gradients(w, t)
+            gs.set_grads(g)
+            gs.step()
+            got = gs.fetch()
+            ref = oracle.vote_step(g, e_ref, w.K, threads=threads)
+            assert_matches_oracle(got, ref, "%s step %d" % (w.name, t))
+            e_ref = ref.err
+        return gs.row_stats()
+
+
+# several tiles of every kernel and a ragged tail: d is not a multiple of 4, 16, 32, 1024 or 16384
+SMALL = {
+    "C1": W.C1.with_size(150001),
+    "C2": W.C2.with_size(300007, N=10),
+    "C3": W.C3.with_size(257003, N=16),
+    "C4": W.C4.with_size(200003, N=16, lattice_shift=6),
+    "C5": W.C5.with_size(180005, N=32),
+}
+
+
+@pytest.mark.parametrize("name", sorted(SMALL))
+def test_reduced_workloads_three_steps(oracle, name):
+    w = SMALL[name]
+    say("reduced %s N=%d d=%d K=%d" % (name, w.N, w.d, w.K))
+    run_sequence(oracle, w, 3)
+
+
+@pytest.mark.parametrize("d,K,N", [(1, 1, 1), (2, 1, 3), (5, 5, 2), (31, 7, 4), (1023, 10, 3), (1024, 1024, 2),
+                                   (1025, 3, 5), (4097, 1, 2), (16385, 100, 3), (70001, 69999, 2),
+                                   (50000, 500, 255)])
+def test_edge_shapes(oracle, d, K, N):
+    say("edge shape d=%d K=%d N=%d" % (d, K, N))
+    rng = np.random.default_rng(d * 7 + K)
+    g = rng.standard_normal((N, d)).astype(np.float32)
+    e = (rng.standard_normal((N, d)) * 0.1).astype(np.float32)
+    with GpuStepper(N, d, K) as gs:
+        gs.set_error(e)
+        gs.set_grads(g)
+        gs.step()
+        assert_matches_oracle(gs.fetch(), oracle.vote_step(g, e, K), "d=%d K=%d N=%d" % (d, K, N))
+
+
+def test_degenerate_rows_take_the_exact_slow_path(oracle):
+    """All-zero, all-equal and two-valued rows: the estimate cannot separate K
+    coordinates, the row is selected exactly from memory, lowest index first."""
+    N, d, K = 5, 140003, 137
+    say("degenerate rows N=%d d=%d K=%d" % (N, d, K))
+    rng = np.random.default_rng(1)
+    g = np.zeros((N, d), np.float32)
+    g[1] = -2.5
+    g[2] = rng.choice(np.array([1.0, -1.0, 3.0], np.float32), size=d)      # huge tie groups
+    g[3] = rng.standard_normal(d).astype(np.float32)
+    g[4, ::2] = -0.0
+    e = np.zeros_like(g)
+    with GpuStepper(N, d, K) as gs:
+        gs.set_error(e)
+        gs.set_grads(g)
+        gs.step()
+        got = gs.fetch()
+        _, _, slow = gs.row_stats()
+    ref = oracle.vote_step(g, e, K)
+    assert_matches_oracle(got, ref, "degenerate")
+    assert got.worker_idx[0].tolist() == list(range(K))
+    assert got.worker_idx[1].tolist() == list(range(K))
+    assert slow[0] == 1 and slow[1] == 1 and slow[3] == 0
+
+
+def test_denormals_and_signed_zero_are_ordered_not_flushed(oracle):
+    N, d, K = 2, 5000, 40
+    say("denormals N=%d d=%d K=%d" % (N, d, K))
+    rng = np.random.default_rng(2)
+    bits = rng.integers(1, 1 << 20, size=(N, d)).astype(np.uint32)          # denormal magnitudes
+    bits |= (rng.integers(0, 2, size=(N, d)).astype(np.uint32) << 31)
+    g = bits.view(np.float32)
+    e = np.zeros_like(g)
+    e[:, ::3] = g[:, ::3]                                                   # denormal + denormal
+    with GpuStepper(N, d, K) as gs:
+        gs.set_error(e)
+        gs.set_grads(g)
+        gs.step()
+        got = gs.fetch()
+    ref = oracle.vote_step(g, e, K)
+    assert np.count_nonzero(ref.err) > 0
+    assert_matches_oracle(got, ref, "denormals")
+
+
+def test_row_stride_larger_than_d_and_padding_untouched(oracle):
+    w = W.C2.with_size(33331, N=3)
+    say("strided rows d=%d" % w.d)
+    run_sequence(oracle, w, 2, extra_ld=5)
+
+
+def test_sum_reduction(oracle):
+    w = W.C2.with_size(40001, N=7)
+    say("sum reduction")
+    g = W.gradients(w, 0)
+    e = W.zero_error(w)
+    with GpuStepper(w.N, w.d, w.K, reduce=B.MV_REDUCE_SUM) as gs:
+        gs.set_error(e)
+        gs.set_grads(g)
+        gs.step()
+        got = gs.fetch()
+    assert_matches_oracle(got, oracle.vote_step(g, e, w.K, reduce_mean=False), "sum")
+
+
+def test_optional_outputs_and_caller_workspace(oracle):
+    w = W.C3.with_size(90001, N=6)
+    say("optional outputs / caller workspace")
+    g, e = W.gradients(w, 0), W.zero_error(w)
+    ref = oracle.vote_step(g, e, w.K)
+    for kw in (dict(want_worker_idx=False), dict(want_votes=False), dict(own_workspace=True),
+               dict(want_worker_idx=False, want_votes=False, own_workspace=True)):
+        with GpuStepper(w.N, w.d, w.K, **kw) as gs:
+            gs.set_error(e)
+            gs.set_grads(g)
+            gs.step()
+            assert_matches_oracle(gs.fetch(), ref, str(kw))
+
+
+def test_result_does_not_depend_on_context_history(oracle):
+    """A context that has run other data gives the same bits as a fresh one, and
+    the same call twice gives the same bits (atomics only order scratch)."""
+    w = W.C4.with_size(120001, N=8, lattice_shift=6)
+    say("determinism / history independence")
+    g0, g1 = W.gradients(w, 0), W.gradients(w, 1)
+    e = W.zero_error(w)
+    outs = []
+    with GpuStepper(w.N, w.d, w.K) as gs:
+        for g in (g0, g1, g0):
+            gs.set_error(e)
+            gs.set_grads(g)
+            gs.step()
+            outs.append(gs.fetch())
+    with GpuStepper(w.N, w.d, w.K) as gs:
+        gs.set_error(e)
+        gs.set_grads(g0)
+        gs.step()
+        fresh = gs.fetch()
+    for other in (outs[2], fresh):
+        assert np.array_equal(outs[0].worker_idx, other.worker_idx)
+        assert np.array_equal(outs[0].votes, other.votes)
+        assert np.array_equal(outs[0].mask_idx, other.mask_idx)
+        assert np.array_equal(outs[0].agg.view(np.uint32), other.agg.view(np.uint32))
+        assert np.array_equal(outs[0].err.view(np.uint32), other.err.view(np.uint32))
+    assert_matches_oracle(outs[0], oracle.vote_step(g0, e, w.K), "history")
+
+
+def test_resume_through_host_copy_of_error_buffer(oracle):
+    """The error buffer is the only state: 6 steps == 3 steps, E to host and into
+    a new context, 3 more steps."""
+    w = W.C3.with_size(60001, N=4, steps=6)
+    say("resume")
+    with GpuStepper(w.N, w.d, w.K) as gs:
+        gs.set_error(W.zero_error(w))
+        for t in range(6):
+            gs.set_grads(W.gradients(w, t))
+            gs.step()
+        full = gs.fetch()
+    with GpuStepper(w.N, w.d, w.K) as gs:
+        gs.set_error(W.zero_error(w))
+        for t in range(3):
+            gs.set_grads(W.gradients(w, t))
+            gs.step()
+        half = gs.fetch()
+    with GpuStepper(w.N, w.d, w.K) as gs:
+        gs.set_error(half.err)
+        for t in range(3, 6):
+            gs.set_grads(W.gradients(w, t))
+            gs.step()
+        resumed = gs.fetch()
+    assert np.array_equal(full.mask_idx, resumed.mask_idx)
+    assert np.array_equal(full.err.view(np.uint32), resumed.err.view(np.uint32))
+    assert np.array_equal(full.agg.view(np.uint32), resumed.agg.view(np.uint32))
+
+
+def test_non_default_stream(oracle):
+    w = W.C2.with_size(50001, N=4)
+    say("side stream")
+    g, e = W.gradients(w, 0), W.zero_error(w)
+    s = torch.cuda.Stream()
+    with GpuStepper(w.N, w.d, w.K) as gs:
+        gs.set_error(e)
+        gs.set_grads(g)
+        torch.cuda.synchronize()
+        gs.step(stream=s)
+        s.synchronize()
+        assert_matches_oracle(gs.fetch(), oracle.vote_step(g, e, w.K), "stream")
+
+
+def test_argument_errors_leave_error_buffer_untouched():
+    say("argument errors on a live context")
+    with GpuStepper(2, 1000, 10) as gs:
+        gs.set_error(np.ones((2, 1000), np.float32))
+        L = B.load()
+        st = L.mv_vote_step(gs.ctx, gs.g.data_ptr(), 999, gs.e.data_ptr(), gs.ld_e, 0, 0,
+                            gs.mask.data_ptr(), gs.agg.data_ptr(), 0)
+        assert st == B.MV_ERR_INVALID_ARG                       # ld < d
+        st = L.mv_vote_step(gs.ctx, gs.g.data_ptr() + 4, gs.ld_g, gs.e.data_ptr(), gs.ld_e, 0, 0,
+                            gs.mask.data_ptr(), gs.agg.data_ptr(), 0)
+        assert st == B.MV_ERR_INVALID_ARG                       # misaligned
+        st = L.mv_vote_step(gs.ctx, gs.g.data_ptr(), gs.ld_g, gs.e.data_ptr(), gs.ld_e, 0, 0,
+                            0, gs.agg.data_ptr(), 0)
+        assert st == B.MV_ERR_INVALID_ARG                       # null mask
+        torch.cuda.synchronize()
+        assert torch.all(gs.e[:, :1000] == 1.0)
+        ctx = gs.ctx
+        B.mv_end(ctx)
+        st = L.mv_vote_step(ctx, gs.g.data_ptr(), gs.ld_g, gs.e.data_ptr(), gs.ld_e, 0, 0,
+                            gs.mask.data_ptr(), gs.agg.data_ptr(), 0)
+        assert st == B.MV_ERR_STATE
+        assert L.mv_end(ctx) == B.MV_ERR_STATE
+        B.mv_release(ctx)
+        gs.ctx = 0
