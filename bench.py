@@ -155,6 +155,20 @@ def main():
         breakdown = {n: round(float(np.median(v)) * 1e3, 2) for n, v in acc.items()}   # microseconds
     B.mv_set_profiling(ctx, 0)
 
+    # ---- yardstick: a plain streaming copy of the same footprint (read n, write n bytes)
+    src = torch.empty(N * ld_e, dtype=torch.float32, device=dev).normal_()
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        B.mv_probe_copy(dst, src, stream)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record(stream)
+    for _ in range(10):
+        B.mv_probe_copy(dst, src, stream)
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    copy_gbs = 2.0 * src.numel() * 4 * 10 / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
+    del src, dst
+
     coords = float(N) * float(d)
     ms_per_step = elapsed / args.steps * 1e3
     value = coords * args.steps / elapsed
@@ -206,6 +220,7 @@ def main():
                                (w.name, N, d, K, w.grad_dtype, w.kind),
                    "N": N, "d": d, "K": K, "grad_sets_cycled": len(g_dev)},
         "step_hbm_frac_algorithmic": round(step_frac, 4),
+        "copy_probe_GBs": round(copy_gbs, 1),
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
         "oracle_agrees_on_step0": oracle_agrees,

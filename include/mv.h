@@ -151,6 +151,15 @@ mv_status mv_step_kernel_ms(mv_ctx* ctx, int32_t steps_back, float* ms, int32_t 
 mv_status mv_last_step_row_stats(mv_ctx* ctx, uint32_t* cand_count,
                                  uint32_t* threshold_bits, uint32_t* slow_path);
 
+/*
+ * Measurement aid, not part of the method: enqueues a plain streaming copy of
+ * `bytes` (a multiple of 16; dst and src 16-byte aligned DEVICE pointers, not
+ * overlapping) on `stream` of the current device.  Its achieved bandwidth is
+ * the yardstick for the streaming pass, and its known byte count calibrates the
+ * profiler's memory counters.
+ */
+mv_status mv_probe_copy(void* dst, const void* src, size_t bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

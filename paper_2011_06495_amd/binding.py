@@ -21,7 +21,7 @@ MV_REDUCE_MEAN, MV_REDUCE_SUM = 0, 1
 ABI_SYMBOLS = (
     "mv_workspace_bytes", "mv_begin", "mv_vote_step", "mv_end", "mv_release", "mv_status_string",
     "mv_kernel_count", "mv_kernel_name", "mv_set_profiling", "mv_step_kernel_ms",
-    "mv_last_step_row_stats",
+    "mv_last_step_row_stats", "mv_probe_copy",
 )
 
 
@@ -82,6 +82,8 @@ def load() -> ctypes.CDLL:
     L.mv_step_kernel_ms.restype = i32
     L.mv_last_step_row_stats.argtypes = [vp, u32p, u32p, u32p]
     L.mv_last_step_row_stats.restype = i32
+    L.mv_probe_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
+    L.mv_probe_copy.restype = i32
     _lib = L
     return L
 
@@ -167,3 +169,15 @@ def mv_last_step_row_stats(ctx: int, n_workers: int):
     if st != MV_OK:
         raise MvError(st, "mv_last_step_row_stats")
     return list(a), list(b), list(c)
+
+
+def mv_probe_copy(dst, src, stream=None) -> None:
+    """Plain streaming copy src -> dst (torch device tensors of equal byte size)."""
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream(src.device)
+    nbytes = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() == nbytes
+    st = load().mv_probe_copy(dst.data_ptr(), src.data_ptr(), nbytes, stream.cuda_stream)
+    if st != MV_OK:
+        raise MvError(st, "mv_probe_copy")

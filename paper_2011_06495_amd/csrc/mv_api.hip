@@ -16,14 +16,18 @@ enum KernelId {
     KID_SAMPLE = 0,
     KID_PICK,
     KID_STREAM,
-    KID_ROW_FINISH,
+    KID_ROW_SELECT,
+    KID_ROW_TALLY,
+    KID_SEG_SCAN,
+    KID_ROW_EMIT,
     KID_MASK_COUNT,
     KID_MASK_EMIT,
     KID_GATHER,
     KID_COUNT
 };
 const char* const kKernelNames[KID_COUNT] = {"mv_sample_hist",  "mv_pick_threshold", "mv_stream_collect",
-                                             "mv_row_finish",   "mv_mask_count",     "mv_mask_emit",
+                                             "mv_row_select",   "mv_row_tally",      "mv_seg_scan",
+                                             "mv_row_emit",     "mv_mask_count",     "mv_mask_emit",
                                              "mv_gather_update"};
 
 constexpr size_t kAlign = 256;
@@ -41,8 +45,10 @@ struct Plan {
     uint32_t m_target;          // sampled coordinates that must lie at or above the threshold bin
     uint32_t cap;               // candidate list capacity per row
     uint32_t n_vote_blocks;
+    uint32_t emit_blocks;       // workgroups per row in mv_row_emit
     // scratch offsets (bytes)
-    size_t off_hist, off_tau, off_rowcnt, off_slow, off_cntge, off_seg, off_cand, off_votes, off_blockcnt;
+    size_t off_hist, off_tau, off_rowcnt, off_slow, off_kth, off_take, off_cntge, off_seg, off_segsel,
+        off_segpre, off_cand, off_votes, off_blockcnt;
     size_t total_bytes;
 };
 
@@ -69,22 +75,24 @@ Plan make_plan(const mv_config* c)
     p.d = c->d;
     p.nseg = (uint32_t)((p.d + mvk::kSeg - 1) / mvk::kSeg);
 
-    // Sample about d/64 coordinates of each row, but at least ~64K when the row has them.
+    // Sample about d/128 coordinates of each row, but at least ~32K when the row has them.
     const uint64_t nchunks = (uint64_t)(p.d + mvk::kChunk - 1) / mvk::kChunk;
-    uint64_t stride = (uint64_t)p.d / ((uint64_t)mvk::kChunk * 65536u);
+    uint64_t want = (uint64_t)p.d / 128;
+    if (want < 32768) want = 32768;
+    uint64_t stride = nchunks / ((want + mvk::kChunk - 1) / mvk::kChunk);
     if (stride < 1) stride = 1;
-    if (stride > 64) stride = 64;
+    if (stride > 128) stride = 128;
     p.stride = (uint32_t)stride;
     p.n_sampled_chunks = (uint32_t)((nchunks + stride - 1) / stride);
     // all sampled chunks are full except possibly the row's last chunk
     p.n_sampled = (uint64_t)p.n_sampled_chunks * mvk::kChunk;
     if (((nchunks - 1) % stride) == 0) p.n_sampled -= (uint64_t)(nchunks * mvk::kChunk - (uint64_t)p.d);
 
-    // Aim at 3K coordinates above the threshold (in expectation), never fewer than
-    // 96 sampled ones, so that falling short of K is many standard deviations away.
+    // Aim at 2K coordinates above the threshold (in expectation), never fewer than
+    // 128 sampled ones, so that falling short of K is many standard deviations away.
     const double frac = (double)p.n_sampled / (double)p.d;
-    double m = 3.0 * (double)p.K * frac;
-    if (m < 96.0) m = 96.0;
+    double m = 2.0 * (double)p.K * frac;
+    if (m < 128.0) m = 128.0;
     m += 1.0;
     p.m_target = (m >= 4294967295.0) ? 0xFFFFFFFFu : (uint32_t)m;
 
@@ -94,14 +102,20 @@ Plan make_plan(const mv_config* c)
     p.cap = (uint32_t)cap;
 
     p.n_vote_blocks = (uint32_t)((p.d + mvk::kVoteBlock - 1) / mvk::kVoteBlock);
+    p.emit_blocks = (p.cap + mvk::kVoteThreads - 1) / mvk::kVoteThreads;
+    if (p.emit_blocks > 256) p.emit_blocks = 256;
 
     size_t off = 0;
     p.off_hist = off;     off += align_up((size_t)p.N * mvk::kHistBins * 4);
     p.off_tau = off;      off += align_up((size_t)p.N * 4);
     p.off_rowcnt = off;   off += align_up((size_t)p.N * 4);
     p.off_slow = off;     off += align_up((size_t)p.N * 4);
+    p.off_kth = off;      off += align_up((size_t)p.N * 4);
+    p.off_take = off;     off += align_up((size_t)p.N * 4);
     p.off_cntge = off;    off += align_up(256 * 4);
     p.off_seg = off;      off += align_up((size_t)p.N * p.nseg * 8);
+    p.off_segsel = off;   off += align_up((size_t)p.N * p.nseg * 4);
+    p.off_segpre = off;   off += align_up((size_t)p.N * p.nseg * 8);
     p.off_cand = off;     off += align_up((size_t)p.N * p.cap * 8);
     p.off_votes = off;    off += align_up(((size_t)p.d + 15) / 16 * 16);
     p.off_blockcnt = off; off += align_up((size_t)p.n_vote_blocks * 8);
@@ -229,6 +243,10 @@ mv_status mv_vote_step(mv_ctx* c, const void* grads, int64_t ld_g, float* err, i
     uint32_t* rowcnt = ws_ptr<uint32_t>(c, p.off_rowcnt);
     uint32_t* slow = ws_ptr<uint32_t>(c, p.off_slow);
     uint32_t* cntge = ws_ptr<uint32_t>(c, p.off_cntge);
+    uint32_t* kth = ws_ptr<uint32_t>(c, p.off_kth);
+    uint32_t* take = ws_ptr<uint32_t>(c, p.off_take);
+    uint32_t* segsel = ws_ptr<uint32_t>(c, p.off_segsel);
+    mvk::u32x2* segpre = ws_ptr<mvk::u32x2>(c, p.off_segpre);
     mvk::u32x2* seg = ws_ptr<mvk::u32x2>(c, p.off_seg);
     mvk::u32x2* cand = ws_ptr<mvk::u32x2>(c, p.off_cand);
     uint32_t* votes32 = ws_ptr<uint32_t>(c, p.off_votes);
@@ -253,8 +271,8 @@ mv_status mv_vote_step(mv_ctx* c, const void* grads, int64_t ld_g, float* err, i
     // 1. sample histogram
     {
         const uint64_t nquads = (uint64_t)p.n_sampled_chunks * (mvk::kChunk / 4);
-        uint32_t bx = (uint32_t)((nquads + 255) / 256);
-        if (bx > 32) bx = 32;
+        uint32_t bx = (uint32_t)((nquads + 511) / 512);
+        if (bx > 16) bx = 16;
         if (bx < 1) bx = 1;
         dim3 grid(bx, p.N);
         before(KID_SAMPLE);
@@ -280,18 +298,30 @@ mv_status mv_vote_step(mv_ctx* c, const void* grads, int64_t ld_g, float* err, i
         if (bf16)
             hipLaunchKernelGGL(mvk::mv_stream_collect<uint16_t>, grid, dim3(mvk::kStreamThreads), 0, st,
                                static_cast<const uint16_t*>(grads), ld_g, err, ld_e, p.d, tau, cand, p.cap,
-                               rowcnt, seg, p.nseg);
+                               rowcnt, seg, segsel, p.nseg);
         else
             hipLaunchKernelGGL(mvk::mv_stream_collect<float>, grid, dim3(mvk::kStreamThreads), 0, st,
                                static_cast<const float*>(grads), ld_g, err, ld_e, p.d, tau, cand, p.cap,
-                               rowcnt, seg, p.nseg);
+                               rowcnt, seg, segsel, p.nseg);
         after(KID_STREAM);
     }
     // 4. exact per-row select, ordered vote lists, vote counting
-    before(KID_ROW_FINISH);
-    hipLaunchKernelGGL(mvk::mv_row_finish, dim3(p.N), dim3(mvk::kRowThreads), 0, st, err, ld_e, p.d, p.K, cand,
-                       p.cap, rowcnt, seg, p.nseg, worker_idx, votes32, cntge, slow);
-    after(KID_ROW_FINISH);
+    before(KID_ROW_SELECT);
+    hipLaunchKernelGGL(mvk::mv_row_select, dim3(p.N), dim3(mvk::kRowThreads), 0, st, err, ld_e, p.d, p.K, cand,
+                       p.cap, rowcnt, kth, take, worker_idx, votes32, cntge, slow);
+    after(KID_ROW_SELECT);
+    before(KID_ROW_TALLY);
+    hipLaunchKernelGGL(mvk::mv_row_tally, dim3(p.emit_blocks, p.N), dim3(mvk::kVoteThreads), 0, st, cand, p.cap,
+                       rowcnt, p.nseg, kth, slow, segsel);
+    after(KID_ROW_TALLY);
+    before(KID_SEG_SCAN);
+    hipLaunchKernelGGL(mvk::mv_seg_scan, dim3((p.nseg + mvk::kRowThreads - 1) / mvk::kRowThreads, p.N),
+                       dim3(mvk::kRowThreads), 0, st, segsel, p.nseg, slow, segpre);
+    after(KID_SEG_SCAN);
+    before(KID_ROW_EMIT);
+    hipLaunchKernelGGL(mvk::mv_row_emit, dim3(p.emit_blocks, p.N), dim3(mvk::kVoteThreads), 0, st, cand, p.cap,
+                       rowcnt, seg, p.nseg, p.K, kth, take, slow, segpre, worker_idx, votes32, cntge);
+    after(KID_ROW_EMIT);
     // 5. global mask
     before(KID_MASK_COUNT);
     hipLaunchKernelGGL(mvk::mv_mask_count, dim3(p.n_vote_blocks), dim3(mvk::kVoteThreads), 0, st, votes32, p.d,
@@ -305,7 +335,8 @@ mv_status mv_vote_step(mv_ctx* c, const void* grads, int64_t ld_g, float* err, i
     {
         const float inv_n = 1.0f / (float)p.N;
         before(KID_GATHER);
-        hipLaunchKernelGGL(mvk::mv_gather_update, dim3((p.K + mvk::kGatherThreads - 1) / mvk::kGatherThreads),
+        const uint32_t kb = mvk::kGatherThreads / p.N;
+        hipLaunchKernelGGL(mvk::mv_gather_update, dim3((p.K + kb - 1) / kb),
                            dim3(mvk::kGatherThreads), 0, st, err, ld_e, p.d, p.N, p.K, mask_idx, inv_n,
                            c->cfg.reduce == MV_REDUCE_MEAN ? 1 : 0, agg_vals);
         after(KID_GATHER);
@@ -401,6 +432,20 @@ mv_status mv_last_step_row_stats(mv_ctx* c, uint32_t* cand_count, uint32_t* thre
     if (slow_path && hipMemcpy(slow_path, c->ws + c->plan.off_slow, nb, hipMemcpyDeviceToHost) != hipSuccess)
         return MV_ERR_DEVICE;
     return MV_OK;
+}
+
+mv_status mv_probe_copy(void* dst, const void* src, size_t bytes, void* stream)
+{
+    if (!dst || !src || bytes == 0 || (bytes & 15) != 0) return MV_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(dst) & 15) || (reinterpret_cast<uintptr_t>(src) & 15))
+        return MV_ERR_INVALID_ARG;
+    const uint64_t n16 = bytes / 16;
+    const uint64_t blocks = (n16 + 1023) / 1024;
+    if (blocks > 0x7FFFFFFFull) return MV_ERR_INVALID_ARG;
+    hipLaunchKernelGGL(mvk::mv_probe_copy_kernel, dim3((uint32_t)blocks), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), static_cast<const mvk::u32x4*>(src),
+                       static_cast<mvk::u32x4*>(dst), n16);
+    return hipGetLastError() == hipSuccess ? MV_OK : MV_ERR_DEVICE;
 }
 
 }  // extern "C"

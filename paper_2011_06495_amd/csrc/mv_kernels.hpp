@@ -14,12 +14,14 @@
 //                         every coordinate with |a| >= tau is appended to the
 //                         row's candidate list; each wavefront's 1024-coordinate
 //                         segment records where its run of candidates went
-//   4. mv_row_finish      per row: EXACT radix select of the K-th largest
+//   4. mv_row_select      per row: EXACT radix select of the K-th largest
 //                         magnitude among the candidates (their number is known
 //                         exactly; if it is < K or overflowed the list, the row
-//                         is selected exactly from memory instead), then the
-//                         vote is emitted in ascending coordinate order by
-//                         walking the segment table, and counted
+//                         is selected exactly from memory instead)
+//                         and the per-segment counts of taken candidates
+//      mv_row_emit        one thread per candidate: its rank in the ascending
+//                         vote list follows from the segment table, so the vote
+//                         comes out sorted without a sort; votes are counted
 //   5. mv_mask_count /    counting-sort selection of the K most voted
 //      mv_mask_emit       coordinates, ties to the lowest coordinate
 //   6. mv_gather_update   masked gather, sum over workers in order, mean, and
@@ -40,7 +42,7 @@ constexpr int      kWave           = 64;
 constexpr int      kSeg            = 1024;   // coordinates per wavefront segment in the streaming pass
 constexpr int      kStreamThreads  = 256;    // 4 segments per workgroup
 constexpr int      kSegPerBlock    = kStreamThreads / kWave;
-constexpr int      kHistBits       = 12;     // sample histogram: exponent + 4 mantissa bits
+constexpr int      kHistBits       = 13;     // sample histogram: exponent + 5 mantissa bits
 constexpr int      kHistBins       = 1 << kHistBits;
 constexpr int      kHistShift      = 31 - kHistBits;
 constexpr int      kChunk          = 32;     // sampled chunk: 32 coordinates (one 128-byte line of fp32)
@@ -230,7 +232,8 @@ template <typename GT>
 __global__ __launch_bounds__(kStreamThreads) void mv_stream_collect(
     const GT* __restrict__ g, int64_t ld_g, float* __restrict__ e, int64_t ld_e, int64_t d,
     const uint32_t* __restrict__ tau_bits, u32x2* __restrict__ cand, uint32_t cap,
-    uint32_t* __restrict__ row_count, u32x2* __restrict__ seg, uint32_t nseg)
+    uint32_t* __restrict__ row_count, u32x2* __restrict__ seg, uint32_t* __restrict__ seg_sel,
+    uint32_t nseg)
 {
     const uint32_t row = blockIdx.y;
     const uint32_t lane = lane_id();
@@ -313,58 +316,122 @@ __global__ __launch_bounds__(kStreamThreads) void mv_stream_collect(
         rec.x = run_start;
         rec.y = total;
         seg[(size_t)row * nseg + s] = rec;
+        seg_sel[(size_t)row * nseg + s] = 0;     // tallied by mv_row_select
     }
 }
 
 // ----------------------------------------------------------------------------
-// 4. per-row exact select + ordered emission + vote counting
+// 4. per-row exact select, then ordered emission of the vote + vote counting
 // ----------------------------------------------------------------------------
 
+constexpr int kSelBins = 2048;   // radix-select digit: 11, 10, 10 bits of the 31-bit key
+constexpr int kKeep    = 48;     // candidate keys a thread of mv_row_select can hold in registers
+
+__device__ __forceinline__ int      sel_shift(int pass) { return pass == 0 ? 20 : pass == 1 ? 10 : 0; }
+__device__ __forceinline__ uint32_t sel_dmask(int pass) { return pass == 0 ? 2047u : 1023u; }
+
+// Adds one key's digit to the LDS histogram.  Must be called by all lanes of
+// the wavefront together.  Gradient magnitudes share a few exponents, so most
+// lanes hit the same digit in the first pass: one lane adds the whole group's
+// count, the others add their own.
+__device__ __forceinline__ void tally_digit(uint32_t* hist, bool active, uint32_t dg, uint32_t lane)
+{
+    const uint64_t am = __ballot(active);
+    if (am != 0ull) {                                   // wave-uniform
+        const int      leader = __ffsll((long long)am) - 1;
+        const uint32_t ldg = __shfl(dg, leader, kWave);
+        const uint64_t same = __ballot(active && dg == ldg);
+        if (lane == (uint32_t)leader) atomicAdd(&hist[ldg], (uint32_t)__popcll(same));
+        if (active && dg != ldg) atomicAdd(&hist[dg], 1u);
+    }
+}
+
+// With the digit histogram of the keys that match `prefix` complete: finds the
+// digit that holds the `remaining`-th largest of them and narrows the search.
+__device__ __forceinline__ void narrow_by_digit(const uint32_t* hist, uint64_t* scan_lds, uint32_t* bcast,
+                                                int pass, uint32_t& prefix, uint32_t& known,
+                                                uint32_t& remaining)
+{
+    // thread t owns digits 2047-2t and 2046-2t (descending order over threads)
+    const int      top = kSelBins - 1 - 2 * (int)threadIdx.x;
+    const uint32_t h0 = hist[top], h1 = hist[top - 1];
+    uint64_t total;
+    const uint64_t ex = block_excl_scan64<kRowThreads>((uint64_t)h0 + h1, scan_lds, total);
+    if (ex < remaining && (uint64_t)remaining <= ex + h0 + h1) {
+        if ((uint64_t)remaining <= ex + h0) {
+            bcast[0] = (uint32_t)top;
+            bcast[1] = remaining - (uint32_t)ex;
+        } else {
+            bcast[0] = (uint32_t)(top - 1);
+            bcast[1] = remaining - (uint32_t)ex - h0;
+        }
+    }
+    __syncthreads();
+    prefix |= bcast[0] << sel_shift(pass);
+    known |= sel_dmask(pass) << sel_shift(pass);
+    remaining = bcast[1];
+    __syncthreads();
+}
+
 // Exact K-th largest of `count` keys delivered by `key_at(i)`, by an MSB-first
-// 8-bit radix select in one workgroup.  Returns the K-th largest key; `take_eq`
+// radix select (11 + 10 + 10 bits) in one workgroup of kRowThreads threads; the
+// keys are re-read in every pass.  Returns the K-th largest key; `take_eq`
 // receives how many keys EQUAL to it belong to the top K (>= 1).
 // Requires 1 <= K <= count.  All threads of the workgroup must call it.
 template <typename KeyAt>
-__device__ __forceinline__ uint32_t block_radix_select(KeyAt key_at, uint64_t count, uint32_t K,
-                                                       uint32_t* hist /*256*/, uint32_t* bcast /*2*/,
-                                                       uint32_t& take_eq)
+__device__ __forceinline__ uint32_t block_radix_select_mem(KeyAt key_at, uint64_t count, uint32_t K,
+                                                           uint32_t* hist /*kSelBins*/, uint64_t* scan_lds,
+                                                           uint32_t* bcast /*2*/, uint32_t& take_eq)
 {
+    const uint32_t lane = lane_id();
     uint32_t prefix = 0, known = 0, remaining = K;
-    for (int shift = 24; shift >= 0; shift -= 8) {
-        if (threadIdx.x < 256) hist[threadIdx.x] = 0;
-        __syncthreads();
-        for (uint64_t i = threadIdx.x; i < count; i += blockDim.x) {
-            const uint32_t k = key_at(i);
-            if ((k & known) == prefix) atomicAdd(&hist[(k >> shift) & 255u], 1u);
-        }
-        __syncthreads();
-        if (threadIdx.x < kWave) {
-            // lane l owns digits 255-4l .. 252-4l (descending)
-            const int top = 255 - 4 * (int)threadIdx.x;
-            uint32_t h[4];
-            uint32_t s = 0;
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                h[q] = hist[top - q];
-                s += h[q];
+    for (int pass = 0; pass < 3; ++pass) {
+        for (int b = threadIdx.x; b < kSelBins; b += kRowThreads) hist[b] = 0;
+        __syncthreads();
+        for (uint64_t base = 0; base < count; base += (uint64_t)kRowThreads * 8) {
+            uint32_t k[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const uint64_t i = base + (uint64_t)u * kRowThreads + threadIdx.x;
+                k[u] = (i < count) ? key_at(i) : 0u;
             }
-            const uint32_t incl = wave_incl_scan(s);
-            uint32_t acc = incl - s;
-            if (acc < remaining && remaining <= incl) {
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    if (acc < remaining && remaining <= acc + h[q]) {
-                        bcast[0] = (uint32_t)(top - q);
-                        bcast[1] = remaining - acc;
-                    }
-                    acc += h[q];
-                }
+            for (int u = 0; u < 8; ++u) {
+                const uint64_t i = base + (uint64_t)u * kRowThreads + threadIdx.x;
+                tally_digit(hist, (i < count) && ((k[u] & known) == prefix),
+                            (k[u] >> sel_shift(pass)) & sel_dmask(pass), lane);
             }
         }
         __syncthreads();
-        prefix |= bcast[0] << shift;
-        known |= 255u << shift;
-        remaining = bcast[1];
+        narrow_by_digit(hist, scan_lds, bcast, pass, prefix, known, remaining);
+    }
+    take_eq = remaining;
+    return prefix;
+}
+
+// The same select with the keys held in registers: thread t holds key number
+// q * kRowThreads + t in k[q]; entries at or beyond `count` are ignored.
+__device__ __forceinline__ uint32_t block_radix_select_regs(const uint32_t (&k)[kKeep], uint32_t count,
+                                                            uint32_t K, uint32_t* hist, uint64_t* scan_lds,
+                                                            uint32_t* bcast, uint32_t& take_eq)
+{
+    const uint32_t lane = lane_id();
+    uint32_t prefix = 0, known = 0, remaining = K;
+#pragma unroll
+    for (int pass = 0; pass < 3; ++pass) {
+        for (int b = threadIdx.x; b < kSelBins; b += kRowThreads) hist[b] = 0;
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < kKeep; ++q) {
+            if ((uint32_t)q * kRowThreads < count) {              // uniform over the workgroup
+                const uint32_t i = (uint32_t)q * kRowThreads + threadIdx.x;
+                tally_digit(hist, (i < count) && ((k[q] & known) == prefix),
+                            (k[q] >> sel_shift(pass)) & sel_dmask(pass), lane);
+            }
+        }
+        __syncthreads();
+        narrow_by_digit(hist, scan_lds, bcast, pass, prefix, known, remaining);
     }
     take_eq = remaining;
     return prefix;
@@ -381,108 +448,209 @@ __device__ __forceinline__ void cast_vote(uint32_t* __restrict__ votes32, uint32
     atomicAdd(&lvl[((old >> sh) & 255u) + 1u], 1u);
 }
 
-__global__ __launch_bounds__(kRowThreads) void mv_row_finish(
+// per-segment tally of taken candidates: magnitudes above kth in the high half,
+// ties with kth in the low half (a segment holds at most 1024 of each)
+__device__ __forceinline__ void tally_segment(uint32_t* __restrict__ seg_sel_row, uint32_t key, uint32_t idx,
+                                              uint32_t kth)
+{
+    if (key >= kth) atomicAdd(&seg_sel_row[idx / kSeg], key > kth ? 0x10000u : 1u);
+}
+
+// One workgroup per row.
+// Usual case: radix select over the row's candidate list gives the K-th largest
+// magnitude kth[row] and how many of its ties to take, take_eq[row];
+// mv_row_tally, mv_seg_scan and mv_row_emit then write the vote.
+// If the candidate count is < K or overflowed the list (for instance a row of
+// equal magnitudes), the row is instead selected exactly from memory (e already
+// holds a = g + e), and its vote is emitted here; slow_flag[row] = 1 tells the
+// next three kernels to skip the row.
+__global__ __launch_bounds__(kRowThreads) void mv_row_select(
     const float* __restrict__ e, int64_t ld_e, int64_t d, uint32_t K,
     const u32x2* __restrict__ cand, uint32_t cap, const uint32_t* __restrict__ row_count,
-    const u32x2* __restrict__ seg, uint32_t nseg,
+    uint32_t* __restrict__ kth_out, uint32_t* __restrict__ take_out,
     uint32_t* __restrict__ worker_idx, uint32_t* __restrict__ votes32,
     uint32_t* __restrict__ cnt_ge, uint32_t* __restrict__ slow_flag)
 {
-    __shared__ uint32_t hist[256];
+    __shared__ uint32_t hist[kSelBins];
     __shared__ uint32_t lvl[257];
     __shared__ uint32_t bcast[2];
     __shared__ uint64_t scan_lds[kRowThreads / kWave + 1];
 
     const uint32_t row = blockIdx.x, t = threadIdx.x;
     const uint32_t C = row_count[row];
-    uint32_t* out = worker_idx ? worker_idx + (size_t)row * K : nullptr;
-    for (int i = t; i < 257; i += kRowThreads) lvl[i] = 0;
-    // (the first __syncthreads inside block_radix_select orders this)
 
     if (C >= K && C <= cap) {
-        // ---- the usual path: everything needed is in the candidate list
         const u32x2* crow = cand + (size_t)row * cap;
-        uint32_t take_eq;
-        const uint32_t kth =
-            block_radix_select([&](uint64_t i) { return crow[i].x; }, C, K, hist, bcast, take_eq);
-
-        // thread t owns a contiguous range of segments, hence of coordinates
-        const uint32_t per = (nseg + kRowThreads - 1) / kRowThreads;
-        const uint32_t s0 = min(t * per, nseg), s1 = min(s0 + per, nseg);
-        const u32x2* srow = seg + (size_t)row * nseg;
-        uint32_t gt = 0, eq = 0;
-        for (uint32_t s = s0; s < s1; ++s) {
-            const u32x2 sr = srow[s];
-            for (uint32_t i = 0; i < sr.y; ++i) {
-                const uint32_t k = crow[sr.x + i].x;
-                gt += (k > kth);
-                eq += (k == kth);
+        uint32_t kth, take_eq;
+        if (C <= (uint32_t)kKeep * kRowThreads) {
+            // entries past C are clamped to the last candidate and ignored later
+            uint32_t k[kKeep];
+            const uint32_t last = C - 1;
+#pragma unroll
+            for (int q = 0; q < kKeep; ++q) {
+                k[q] = crow[min((uint32_t)q * kRowThreads + t, last)].x;
+                if ((q & 7) == 7) __builtin_amdgcn_sched_barrier(0);   // keep address arithmetic from piling up
             }
+            kth = block_radix_select_regs(k, C, K, hist, scan_lds, bcast, take_eq);
+        } else {
+            kth = block_radix_select_mem([&](uint64_t i) { return crow[i].x; }, C, K, hist, scan_lds,
+                                         bcast, take_eq);
+        }
+        if (t == 0) {
+            kth_out[row] = kth;
+            take_out[row] = take_eq;
+        }
+        return;
+    }
+
+    // ---- exact path from memory
+    if (t == 0) slow_flag[row] = 1;
+    for (int i = t; i < 257; i += kRowThreads) lvl[i] = 0;   // ordered by the select's first barrier
+    uint32_t* out = worker_idx ? worker_idx + (size_t)row * K : nullptr;
+    const float* arow = e + (int64_t)row * ld_e;
+    uint32_t take_eq;
+    const uint32_t kth = block_radix_select_mem(
+        [&](uint64_t i) { return __float_as_uint(arow[i]) & kAbsMask; }, (uint64_t)d, K, hist, scan_lds,
+        bcast, take_eq);
+    uint32_t gt_before = 0, eq_before = 0;
+    for (int64_t j0 = 0; j0 < d; j0 += (int64_t)kRowThreads * 4) {
+        const int64_t j = j0 + (int64_t)t * 4;
+        uint32_t k[4];
+        uint32_t gt = 0, eq = 0;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const bool valid = (j + c < d);
+            k[c] = valid ? (__float_as_uint(arow[j + c]) & kAbsMask) : 0u;
+            gt += (valid && k[c] > kth);
+            eq += (valid && k[c] == kth);
         }
         uint64_t total;
         const uint64_t ex = block_excl_scan64<kRowThreads>(pack2(gt, eq), scan_lds, total);
-        uint32_t gt_before = (uint32_t)(ex >> 32), eq_before = (uint32_t)ex;
-        for (uint32_t s = s0; s < s1; ++s) {
-            const u32x2 sr = srow[s];
-            for (uint32_t i = 0; i < sr.y; ++i) {
-                const u32x2 c = crow[sr.x + i];
-                const bool is_gt = c.x > kth, is_eq = c.x == kth;
-                if (is_gt || (is_eq && eq_before < take_eq)) {
-                    const uint32_t pos = gt_before + min(eq_before, take_eq);
-                    if (out && pos < K) out[pos] = c.y;
-                    cast_vote(votes32, c.y, lvl);
+        uint32_t g0 = gt_before + (uint32_t)(ex >> 32), e0 = eq_before + (uint32_t)ex;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            if (j + c < d) {
+                const bool is_gt = k[c] > kth, is_eq = k[c] == kth;
+                if (is_gt || (is_eq && e0 < take_eq)) {
+                    const uint32_t pos = g0 + min(e0, take_eq);
+                    if (out && pos < K) out[pos] = (uint32_t)(j + c);
+                    cast_vote(votes32, (uint32_t)(j + c), lvl);
                 }
-                gt_before += is_gt;
-                eq_before += is_eq;
+                g0 += is_gt;
+                e0 += is_eq;
             }
         }
-    } else {
-        // ---- exact path from memory: e already holds a = g + e for this row.
-        // Taken when the estimate kept fewer than K coordinates or more than
-        // the list holds (for instance a row of equal magnitudes).
-        if (t == 0) slow_flag[row] = 1;
-        const float* arow = e + (int64_t)row * ld_e;
-        uint32_t take_eq;
-        const uint32_t kth = block_radix_select(
-            [&](uint64_t i) { return __float_as_uint(arow[i]) & kAbsMask; }, (uint64_t)d, K, hist,
-            bcast, take_eq);
-        uint32_t gt_before = 0, eq_before = 0;
-        for (int64_t j0 = 0; j0 < d; j0 += (int64_t)kRowThreads * 4) {
-            const int64_t j = j0 + (int64_t)t * 4;
-            uint32_t k[4];
-            uint32_t gt = 0, eq = 0;
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                k[c] = (j + c < d) ? (__float_as_uint(arow[j + c]) & kAbsMask) : 0u;
-                const bool valid = (j + c < d);
-                gt += (valid && k[c] > kth);
-                eq += (valid && k[c] == kth);
-            }
-            uint64_t total;
-            const uint64_t ex = block_excl_scan64<kRowThreads>(pack2(gt, eq), scan_lds, total);
-            uint32_t g0 = gt_before + (uint32_t)(ex >> 32), e0 = eq_before + (uint32_t)ex;
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                if (j + c < d) {
-                    const bool is_gt = k[c] > kth, is_eq = k[c] == kth;
-                    if (is_gt || (is_eq && e0 < take_eq)) {
-                        const uint32_t pos = g0 + min(e0, take_eq);
-                        if (out && pos < K) out[pos] = (uint32_t)(j + c);
-                        cast_vote(votes32, (uint32_t)(j + c), lvl);
-                    }
-                    g0 += is_gt;
-                    e0 += is_eq;
-                }
-            }
-            gt_before += (uint32_t)(total >> 32);
-            eq_before += (uint32_t)total;
-            __syncthreads();   // scan_lds is reused by the next round
+        gt_before += (uint32_t)(total >> 32);
+        eq_before += (uint32_t)total;
+        __syncthreads();   // scan_lds is reused by the next round
+    }
+    __syncthreads();
+    for (int i = t; i < 256; i += kRowThreads) {
+        const uint32_t c = lvl[i];
+        if (c) atomicAdd(&cnt_ge[i], c);
+    }
+}
+
+// One thread per candidate: tallies, per 1024-coordinate segment, the candidates
+// above kth and tied with it (seg_sel was zeroed by the streaming pass).
+__global__ __launch_bounds__(kVoteThreads) void mv_row_tally(
+    const u32x2* __restrict__ cand, uint32_t cap, const uint32_t* __restrict__ row_count, uint32_t nseg,
+    const uint32_t* __restrict__ kth_in, const uint32_t* __restrict__ slow_flag,
+    uint32_t* __restrict__ seg_sel)
+{
+    const uint32_t row = blockIdx.y;
+    if (slow_flag[row]) return;
+    const uint32_t C = row_count[row];
+    const uint32_t kth = kth_in[row];
+    const u32x2* crow = cand + (size_t)row * cap;
+    uint32_t*    ssel = seg_sel + (size_t)row * nseg;
+    for (uint64_t i = (uint64_t)blockIdx.x * kVoteThreads + threadIdx.x; i < C;
+         i += (uint64_t)gridDim.x * kVoteThreads) {
+        const u32x2 c = crow[i];
+        tally_segment(ssel, c.x, c.y, kth);
+    }
+}
+
+// Exclusive scan of the segment tallies along each row:
+// seg_pre[row][s] = (above kth, tied with kth) summed over all segments before s.
+// A workgroup scans 1024 segments and adds up everything before its range itself.
+__global__ __launch_bounds__(kRowThreads) void mv_seg_scan(const uint32_t* __restrict__ seg_sel, uint32_t nseg,
+                                                          const uint32_t* __restrict__ slow_flag,
+                                                          u32x2* __restrict__ seg_pre)
+{
+    __shared__ uint64_t scan_lds[kRowThreads / kWave + 1];
+    const uint32_t row = blockIdx.y, t = threadIdx.x;
+    if (slow_flag[row]) return;                 // whole workgroup
+    const uint32_t* ssel = seg_sel + (size_t)row * nseg;
+    const uint32_t s0 = blockIdx.x * kRowThreads;
+    uint64_t mine = 0;
+    for (uint32_t i = t; i < s0; i += kRowThreads) {
+        const uint32_t v = ssel[i];
+        mine += pack2(v >> 16, v & 0xFFFFu);
+    }
+    uint64_t before;
+    (void)block_excl_scan64<kRowThreads>(mine, scan_lds, before);
+    __syncthreads();
+    const uint32_t s = s0 + t;
+    const uint32_t v = (s < nseg) ? ssel[s] : 0u;
+    uint64_t total;
+    const uint64_t ex = before + block_excl_scan64<kRowThreads>(pack2(v >> 16, v & 0xFFFFu), scan_lds, total);
+    if (s < nseg) {
+        u32x2 r;
+        r.x = (uint32_t)(ex >> 32);
+        r.y = (uint32_t)ex;
+        seg_pre[(size_t)row * nseg + s] = r;
+    }
+}
+
+// One thread per candidate.  A candidate at or above kth finds its rank in the
+// row's ascending vote list as (above-kth before it) + min(ties before it,
+// take_eq): the part from earlier segments comes from seg_pre, the part from its
+// own segment by walking back along its run (runs are ascending inside a
+// segment), so the list comes out sorted without a sort.  Each taken coordinate
+// also casts its vote.
+__global__ __launch_bounds__(kVoteThreads) void mv_row_emit(
+    const u32x2* __restrict__ cand, uint32_t cap, const uint32_t* __restrict__ row_count,
+    const u32x2* __restrict__ seg, uint32_t nseg, uint32_t K, const uint32_t* __restrict__ kth_in,
+    const uint32_t* __restrict__ take_in, const uint32_t* __restrict__ slow_flag,
+    const u32x2* __restrict__ seg_pre, uint32_t* __restrict__ worker_idx,
+    uint32_t* __restrict__ votes32, uint32_t* __restrict__ cnt_ge)
+{
+    __shared__ uint32_t lvl[257];
+    const uint32_t row = blockIdx.y, t = threadIdx.x;
+    if (slow_flag[row]) return;                 // whole workgroup
+    const uint32_t C = row_count[row];
+    if ((uint64_t)blockIdx.x * kVoteThreads >= C) return;   // whole workgroup
+    for (int i = t; i < 257; i += kVoteThreads) lvl[i] = 0;
+    __syncthreads();
+    const uint32_t kth = kth_in[row], take_eq = take_in[row];
+    const u32x2* crow = cand + (size_t)row * cap;
+    const u32x2* srow = seg + (size_t)row * nseg;
+    const u32x2* prow = seg_pre + (size_t)row * nseg;
+    uint32_t* out = worker_idx ? worker_idx + (size_t)row * K : nullptr;
+
+    for (uint64_t i = (uint64_t)blockIdx.x * kVoteThreads + t; i < C; i += (uint64_t)gridDim.x * kVoteThreads) {
+        const u32x2 c = crow[i];
+        if (c.x < kth) continue;
+        const uint32_t s = c.y / kSeg;
+        const u32x2 run = srow[s];
+        const u32x2 pre = prow[s];
+        uint32_t gt_before = pre.x, eq_before = pre.y;
+        for (uint32_t j = run.x; j < (uint32_t)i; ++j) {
+            const uint32_t k = crow[j].x;
+            gt_before += (k > kth);
+            eq_before += (k == kth);
+        }
+        if (c.x > kth || eq_before < take_eq) {
+            const uint32_t pos = gt_before + min(eq_before, take_eq);
+            if (out && pos < K) out[pos] = c.y;
+            cast_vote(votes32, c.y, lvl);
         }
     }
     __syncthreads();
-    for (int i = t; i < 257; i += kRowThreads) {
+    for (int i = t; i < 256; i += kVoteThreads) {
         const uint32_t c = lvl[i];
-        if (c && i < 256) atomicAdd(&cnt_ge[i], c);
+        if (c) atomicAdd(&cnt_ge[i], c);
     }
 }
 
@@ -624,25 +792,58 @@ __global__ __launch_bounds__(kVoteThreads) void mv_mask_emit(uint32_t* __restric
 // ----------------------------------------------------------------------------
 // 6. masked gather, ordered sum over workers, mean, error update
 // ----------------------------------------------------------------------------
+// A workgroup handles kb = 256 / N mask coordinates.  Thread (kl, n) reads
+// a[n][mask[k]] (held in e), stores +0.0 there (the error update: the residual
+// of a transmitted coordinate is zero), and parks the value in LDS; one thread
+// per coordinate then adds the N values in worker order 0..N-1 in fp32 and
+// applies the 1/N of the mean once.
 __global__ __launch_bounds__(kGatherThreads) void mv_gather_update(float* __restrict__ e, int64_t ld_e,
                                                                    int64_t d, uint32_t N, uint32_t K,
                                                                    const uint32_t* __restrict__ mask_idx,
                                                                    float scale, int apply_scale,
                                                                    float* __restrict__ agg)
 {
-    const uint32_t k = blockIdx.x * kGatherThreads + threadIdx.x;
-    if (k >= K) return;
-    const uint32_t j = mask_idx[k];
-    if ((int64_t)j >= d) return;   // cannot happen for a mask built by mv_mask_emit
-    float* p = e + j;
-    float s = *p;                  // worker 0
-    *p = 0.0f;
-    for (uint32_t n = 1; n < N; ++n) {
-        p += ld_e;
-        s = s + *p;                // workers in order, fp32, no contraction
-        *p = 0.0f;
+    __shared__ float tile[2 * kGatherThreads];
+    const uint32_t kb = kGatherThreads / N;          // N <= 255, so kb >= 1
+    const uint32_t t = threadIdx.x;
+    const uint32_t kl = t / N, n = t % N;
+    const uint32_t k = blockIdx.x * kb + kl;
+    const uint32_t pitch = N + 1;                     // kb * (N + 1) <= 256 + kb <= 512
+    if (kl < kb && k < K) {
+        const uint32_t j = mask_idx[k];
+        float v = 0.0f;
+        if ((int64_t)j < d) {                         // always true for a mask built by mv_mask_emit
+            float* p = e + (int64_t)n * ld_e + j;
+            v = *p;
+            *p = 0.0f;
+        }
+        tile[kl * pitch + n] = v;
     }
-    agg[k] = apply_scale ? s * scale : s;
+    __syncthreads();
+    if (t < kb) {
+        const uint32_t kk = blockIdx.x * kb + t;
+        if (kk < K) {
+            float s = tile[t * pitch];                // worker 0
+            for (uint32_t m = 1; m < N; ++m) s = s + tile[t * pitch + m];
+            agg[kk] = apply_scale ? s * scale : s;
+        }
+    }
+}
+
+// ----------------------------------------------------------------------------
+// measurement aid: a plain streaming copy (n16 units of 16 bytes), the yardstick
+// for the HBM bandwidth a kernel of this shape can reach and for scaling the
+// profiler's byte counters
+// ----------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void mv_probe_copy_kernel(const u32x4* __restrict__ src,
+                                                            u32x4* __restrict__ dst, uint64_t n16)
+{
+    const uint64_t base = (uint64_t)blockIdx.x * 1024 + threadIdx.x;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const uint64_t i = base + (uint64_t)u * 256;
+        if (i < n16) __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
+    }
 }
 
 }  // namespace mvk
