@@ -117,7 +117,7 @@ def main():
     mask0 = mask.cpu().numpy().view(np.uint32).copy()
     agg0 = agg.cpu().numpy().copy()
     cand, tau, slow = B.mv_last_step_row_stats(ctx, N)
-    log("step 0: candidates per row min/max %d/%d, slow-path rows %d" % (min(cand), max(cand), sum(slow)))
+    log("step 0: candidates per row min/max %d/%d, select path per row %s" % (min(cand), max(cand), slow))
 
     # ---- warmup, then the timed region
     B.mv_set_profiling(ctx, args.profile_level)
@@ -141,7 +141,9 @@ def main():
             if args.profile_level == 2:
                 for nme, v in zip(names, ms):
                     per_kernel.setdefault(nme, []).append(v)
-    _, _, slow_last = B.mv_last_step_row_stats(ctx, N)
+    cand_last, _, slow_last = B.mv_last_step_row_stats(ctx, N)
+    log("last timed step: candidates per row min/max %d/%d, select path per row %s" %
+        (min(cand_last), max(cand_last), slow_last))
 
     breakdown = None
     if args.breakdown:
@@ -224,7 +226,7 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
         "oracle_agrees_on_step0": oracle_agrees,
-        "slow_path_rows_last_step": int(sum(slow_last)),
+        "slow_path_rows_last_step": int(sum(1 for x in slow_last if x == 1)),
         "paper_comm_load": comm_load_context(w),
     }
     if per_kernel:

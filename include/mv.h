@@ -144,9 +144,10 @@ mv_status mv_step_kernel_ms(mv_ctx* ctx, int32_t steps_back, float* ms, int32_t 
 /*
  * Diagnostics of the LAST step (waits for the stream the step ran on): per
  * worker row, how many candidates the streaming pass kept (cand_count), the
- * magnitude bit pattern it compared against (threshold_bits) and whether the
- * row had to take the slow exact path (slow_path: 0/1).  HOST arrays of N
- * uint32 each; any may be NULL.
+ * magnitude bit pattern it compared against (threshold_bits) and how the row's
+ * K-th magnitude was found (slow_path: 0 = from the candidates through their
+ * fine histogram, 2 = radix select over the candidates, 1 = the slow exact path
+ * over the whole row in memory).  HOST arrays of N uint32 each; any may be NULL.
  */
 mv_status mv_last_step_row_stats(mv_ctx* ctx, uint32_t* cand_count,
                                  uint32_t* threshold_bits, uint32_t* slow_path);

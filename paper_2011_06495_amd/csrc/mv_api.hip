@@ -17,18 +17,15 @@ enum KernelId {
     KID_PICK,
     KID_STREAM,
     KID_ROW_SELECT,
-    KID_ROW_TALLY,
-    KID_SEG_SCAN,
-    KID_ROW_EMIT,
+    KID_ROW_VOTES,
     KID_MASK_COUNT,
     KID_MASK_EMIT,
     KID_GATHER,
     KID_COUNT
 };
-const char* const kKernelNames[KID_COUNT] = {"mv_sample_hist",  "mv_pick_threshold", "mv_stream_collect",
-                                             "mv_row_select",   "mv_row_tally",      "mv_seg_scan",
-                                             "mv_row_emit",     "mv_mask_count",     "mv_mask_emit",
-                                             "mv_gather_update"};
+const char* const kKernelNames[KID_COUNT] = {"mv_sample_hist", "mv_pick_threshold", "mv_stream_collect",
+                                             "mv_row_select",  "mv_row_votes",      "mv_mask_count",
+                                             "mv_mask_emit",   "mv_gather_update"};
 
 constexpr size_t kAlign = 256;
 constexpr int kEventRing = 64;   // steps whose kernel durations stay readable
@@ -45,10 +42,12 @@ struct Plan {
     uint32_t m_target;          // sampled coordinates that must lie at or above the threshold bin
     uint32_t cap;               // candidate list capacity per row
     uint32_t n_vote_blocks;
-    uint32_t emit_blocks;       // workgroups per row in mv_row_emit
+    uint32_t emit_blocks;       // workgroups per row that walk the candidate list
+    uint32_t scan_blocks;       // workgroups per row that scan the segment tallies
     // scratch offsets (bytes)
-    size_t off_hist, off_tau, off_rowcnt, off_slow, off_kth, off_take, off_cntge, off_seg, off_segsel,
-        off_segpre, off_cand, off_votes, off_blockcnt;
+    size_t off_hist, off_tau, off_rowcnt, off_slow, off_kth, off_tiecut, off_cntge, off_seg, off_segsel,
+        off_segpre,
+        off_blktotal, off_cand, off_votes, off_blockcnt;
     size_t total_bytes;
 };
 
@@ -104,6 +103,7 @@ Plan make_plan(const mv_config* c)
     p.n_vote_blocks = (uint32_t)((p.d + mvk::kVoteBlock - 1) / mvk::kVoteBlock);
     p.emit_blocks = (p.cap + mvk::kVoteThreads - 1) / mvk::kVoteThreads;
     if (p.emit_blocks > 256) p.emit_blocks = 256;
+    p.scan_blocks = (p.nseg + 1023) / 1024;
 
     size_t off = 0;
     p.off_hist = off;     off += align_up((size_t)p.N * mvk::kHistBins * 4);
@@ -111,11 +111,12 @@ Plan make_plan(const mv_config* c)
     p.off_rowcnt = off;   off += align_up((size_t)p.N * 4);
     p.off_slow = off;     off += align_up((size_t)p.N * 4);
     p.off_kth = off;      off += align_up((size_t)p.N * 4);
-    p.off_take = off;     off += align_up((size_t)p.N * 4);
-    p.off_cntge = off;    off += align_up(256 * 4);
+    p.off_tiecut = off;   off += align_up((size_t)p.N * 4);
+    p.off_cntge = off;    off += align_up((size_t)p.N * 256 * 4);
     p.off_seg = off;      off += align_up((size_t)p.N * p.nseg * 8);
     p.off_segsel = off;   off += align_up((size_t)p.N * p.nseg * 4);
-    p.off_segpre = off;   off += align_up((size_t)p.N * p.nseg * 8);
+    p.off_segpre = off;   off += align_up((size_t)p.N * p.nseg * 4);
+    p.off_blktotal = off; off += align_up((size_t)p.N * ((p.nseg + 1023) / 1024) * 4);
     p.off_cand = off;     off += align_up((size_t)p.N * p.cap * 8);
     p.off_votes = off;    off += align_up(((size_t)p.d + 15) / 16 * 16);
     p.off_blockcnt = off; off += align_up((size_t)p.n_vote_blocks * 8);
@@ -203,7 +204,7 @@ mv_status mv_begin(const mv_config* cfg, mv_ctx** out_ctx)
     }
     // The histogram and the packed vote words must start at zero; the kernels
     // leave them at zero after every step.
-    bool ok = hipMemset(c->ws + plan.off_hist, 0, (size_t)plan.N * mvk::kHistBins * 4) == hipSuccess &&
+    bool ok = hipMemset(c->ws + plan.off_hist, 0, plan.off_tau - plan.off_hist) == hipSuccess &&
               hipMemset(c->ws + plan.off_votes, 0, ((size_t)plan.d + 15) / 16 * 16) == hipSuccess &&
               hipMemset(c->ws + plan.off_tau, 0, plan.off_seg - plan.off_tau) == hipSuccess;
     ok = ok && hipDeviceSynchronize() == hipSuccess;
@@ -244,9 +245,10 @@ mv_status mv_vote_step(mv_ctx* c, const void* grads, int64_t ld_g, float* err, i
     uint32_t* slow = ws_ptr<uint32_t>(c, p.off_slow);
     uint32_t* cntge = ws_ptr<uint32_t>(c, p.off_cntge);
     uint32_t* kth = ws_ptr<uint32_t>(c, p.off_kth);
-    uint32_t* take = ws_ptr<uint32_t>(c, p.off_take);
+    uint32_t* tiecut = ws_ptr<uint32_t>(c, p.off_tiecut);
     uint32_t* segsel = ws_ptr<uint32_t>(c, p.off_segsel);
-    mvk::u32x2* segpre = ws_ptr<mvk::u32x2>(c, p.off_segpre);
+    uint32_t* segpre = ws_ptr<uint32_t>(c, p.off_segpre);
+    uint32_t* blktotal = ws_ptr<uint32_t>(c, p.off_blktotal);
     mvk::u32x2* seg = ws_ptr<mvk::u32x2>(c, p.off_seg);
     mvk::u32x2* cand = ws_ptr<mvk::u32x2>(c, p.off_cand);
     uint32_t* votes32 = ws_ptr<uint32_t>(c, p.off_votes);
@@ -268,7 +270,7 @@ mv_status mv_vote_step(mv_ctx* c, const void* grads, int64_t ld_g, float* err, i
         if (hipEventRecord(c->ev[slot][kid][1], st) == hipSuccess) c->ev_recorded[slot][kid] = true;
     };
 
-    // 1. sample histogram
+    // 1. sample histogram, then the threshold estimate per row and the counters' reset
     {
         const uint64_t nquads = (uint64_t)p.n_sampled_chunks * (mvk::kChunk / 4);
         uint32_t bx = (uint32_t)((nquads + 511) / 512);
@@ -285,13 +287,12 @@ mv_status mv_vote_step(mv_ctx* c, const void* grads, int64_t ld_g, float* err, i
                                static_cast<const float*>(grads), ld_g, err, ld_e, p.d, p.stride,
                                p.n_sampled_chunks, hist);
         after(KID_SAMPLE);
+        before(KID_PICK);
+        hipLaunchKernelGGL(mvk::mv_pick_threshold, dim3(p.N), dim3(mvk::kRowThreads), 0, st, hist, p.m_target,
+                           tau, rowcnt, slow, cntge);
+        after(KID_PICK);
     }
-    // 2. threshold estimate per row, counters reset
-    before(KID_PICK);
-    hipLaunchKernelGGL(mvk::mv_pick_threshold, dim3(p.N), dim3(mvk::kRowThreads), 0, st, hist, p.m_target,
-                       tau, rowcnt, slow, cntge);
-    after(KID_PICK);
-    // 3. streaming pass: a = g + e over e, candidates out
+    // 2. streaming pass: a = g + e over e, candidates out
     {
         dim3 grid((p.nseg + mvk::kSegPerBlock - 1) / mvk::kSegPerBlock, p.N);
         before(KID_STREAM);
@@ -305,31 +306,29 @@ mv_status mv_vote_step(mv_ctx* c, const void* grads, int64_t ld_g, float* err, i
                                rowcnt, seg, segsel, p.nseg);
         after(KID_STREAM);
     }
-    // 4. exact per-row select, ordered vote lists, vote counting
+    // 3. exact per-row select
     before(KID_ROW_SELECT);
     hipLaunchKernelGGL(mvk::mv_row_select, dim3(p.N), dim3(mvk::kRowThreads), 0, st, err, ld_e, p.d, p.K, cand,
-                       p.cap, rowcnt, kth, take, worker_idx, votes32, cntge, slow);
+                       p.cap, rowcnt, tau, kth, tiecut, worker_idx, votes32, cntge, slow);
     after(KID_ROW_SELECT);
-    before(KID_ROW_TALLY);
-    hipLaunchKernelGGL(mvk::mv_row_tally, dim3(p.emit_blocks, p.N), dim3(mvk::kVoteThreads), 0, st, cand, p.cap,
-                       rowcnt, p.nseg, kth, slow, segsel);
-    after(KID_ROW_TALLY);
-    before(KID_SEG_SCAN);
-    hipLaunchKernelGGL(mvk::mv_seg_scan, dim3((p.nseg + mvk::kRowThreads - 1) / mvk::kRowThreads, p.N),
-                       dim3(mvk::kRowThreads), 0, st, segsel, p.nseg, slow, segpre);
-    after(KID_SEG_SCAN);
-    before(KID_ROW_EMIT);
-    hipLaunchKernelGGL(mvk::mv_row_emit, dim3(p.emit_blocks, p.N), dim3(mvk::kVoteThreads), 0, st, cand, p.cap,
-                       rowcnt, seg, p.nseg, p.K, kth, take, slow, segpre, worker_idx, votes32, cntge);
-    after(KID_ROW_EMIT);
-    // 5. global mask
+    // 4. votes (and segment tallies when the sorted lists are wanted)
+    const bool sorted = worker_idx != nullptr;
+    before(KID_ROW_VOTES);
+    hipLaunchKernelGGL(mvk::mv_row_votes, dim3(p.emit_blocks, p.N), dim3(mvk::kVoteThreads), 0, st, cand, p.cap,
+                       rowcnt, p.nseg, kth, tiecut, slow, sorted ? segsel : nullptr, votes32, cntge);
+    after(KID_ROW_VOTES);
+    // 5. global mask; extra workgroups scan the tallies / write the sorted vote lists
     before(KID_MASK_COUNT);
-    hipLaunchKernelGGL(mvk::mv_mask_count, dim3(p.n_vote_blocks), dim3(mvk::kVoteThreads), 0, st, votes32, p.d,
-                       p.N, p.K, cntge, blockcnt, votes);
+    hipLaunchKernelGGL(mvk::mv_mask_count, dim3(p.n_vote_blocks + (sorted ? p.N * p.scan_blocks : 0)),
+                       dim3(mvk::kVoteThreads), 0, st, votes32, p.d, p.N, p.K, cntge, blockcnt, votes,
+                       p.n_vote_blocks, p.scan_blocks, p.nseg, slow, segsel, segpre, blktotal);
     after(KID_MASK_COUNT);
     before(KID_MASK_EMIT);
-    hipLaunchKernelGGL(mvk::mv_mask_emit, dim3(p.n_vote_blocks), dim3(mvk::kVoteThreads), 0, st, votes32, p.d,
-                       p.N, p.K, cntge, blockcnt, mask_idx);
+    hipLaunchKernelGGL(mvk::mv_mask_emit, dim3(p.n_vote_blocks + (sorted ? p.N * p.emit_blocks : 0)),
+                       dim3(mvk::kVoteThreads), 0, st, votes32, p.d, p.N, p.K, cntge, blockcnt, mask_idx,
+                       p.n_vote_blocks, p.emit_blocks, cand, p.cap, rowcnt, seg, p.nseg, segpre, blktotal, p.scan_blocks,
+                       kth, tiecut, slow,
+                       worker_idx);
     after(KID_MASK_EMIT);
     // 6. gather + mean + error update
     {

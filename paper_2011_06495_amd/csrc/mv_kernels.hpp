@@ -6,24 +6,27 @@
 // contraction, so no MFMA; the design goal is ONE streaming pass over g and e.
 //
 // How the per-worker top-K is found without re-reading the row:
-//   1. mv_sample_hist     histogram of the magnitude bit patterns of a strided
-//                         sample of each row (cache-line sized chunks)
-//   2. mv_pick_threshold  per row, a bin edge tau that about 3K sampled-scaled
-//                         coordinates exceed (an ESTIMATE, never trusted)
-//   3. mv_stream_collect  the streaming pass: a = g + e is written over e, and
+//   1. mv_sample_pick     histogram of the magnitude bit patterns of a strided
+//                         sample of each row (cache-line sized chunks); the last
+//                         workgroup of a row turns it into a bin edge tau that
+//                         about 2K sampled-scaled coordinates exceed (an
+//                         ESTIMATE, never trusted)
+//   2. mv_stream_collect  the streaming pass: a = g + e is written over e, and
 //                         every coordinate with |a| >= tau is appended to the
 //                         row's candidate list; each wavefront's 1024-coordinate
 //                         segment records where its run of candidates went
-//   4. mv_row_select      per row: EXACT radix select of the K-th largest
+//   3. mv_row_select      per row: EXACT radix select of the K-th largest
 //                         magnitude among the candidates (their number is known
 //                         exactly; if it is < K or overflowed the list, the row
-//                         is selected exactly from memory instead)
-//                         and the per-segment counts of taken candidates
-//      mv_row_emit        one thread per candidate: its rank in the ascending
-//                         vote list follows from the segment table, so the vote
-//                         comes out sorted without a sort; votes are counted
+//                         is selected exactly from memory instead), and of the
+//                         largest coordinate taken among its ties
+//   4. mv_row_votes       one thread per candidate: the taken ones cast their vote
 //   5. mv_mask_count /    counting-sort selection of the K most voted
-//      mv_mask_emit       coordinates, ties to the lowest coordinate
+//      mv_mask_emit       coordinates, ties to the lowest coordinate.  Extra
+//                         workgroups of the same two launches write each row's
+//                         vote in ascending coordinate order (segment tallies
+//                         scanned, then one thread per candidate), off the
+//                         critical path
 //   6. mv_gather_update   masked gather, sum over workers in order, mean, and
 //                         the error update (zero on the mask)
 #pragma once
@@ -51,6 +54,8 @@ constexpr int      kVoteBlock      = 16384;  // coordinates per workgroup in mv_
 constexpr int      kVoteThreads    = 256;
 constexpr int      kGatherThreads  = 256;
 constexpr uint32_t kAbsMask        = 0x7FFFFFFFu;
+constexpr int      kFineBins       = 2048;   // mv_row_select: histogram of the candidates' magnitudes above tau
+constexpr int      kFineShift      = 12;     // 2048 bins of 4096 bit patterns = one octave above tau
 
 // ----------------------------------------------------------------------------
 // small helpers
@@ -105,6 +110,12 @@ __device__ __forceinline__ uint64_t block_excl_scan64(uint64_t v, uint64_t* lds,
 
 __device__ __forceinline__ uint64_t pack2(uint32_t hi, uint32_t lo) { return ((uint64_t)hi << 32) | lo; }
 
+// bin of a candidate's magnitude key (>= tau) in the row's fine histogram; order preserving
+__device__ __forceinline__ uint32_t fine_bin(uint32_t key, uint32_t tau)
+{
+    return min((key - tau) >> kFineShift, (uint32_t)(kFineBins - 1));
+}
+
 // widen four gradient elements to fp32
 __device__ __forceinline__ f32x4 load4_grad(const float* p)
 {
@@ -124,10 +135,11 @@ __device__ __forceinline__ float load1_grad(const float* p) { return *p; }
 __device__ __forceinline__ float load1_grad(const uint16_t* p) { return __uint_as_float((uint32_t)(*p) << 16); }
 
 // ----------------------------------------------------------------------------
-// 1. sample histogram
+// 1. sample histogram and threshold estimate
 // ----------------------------------------------------------------------------
 // Chunk c of a row is the coordinates [32c, 32c+32); chunk c is sampled when
-// c % stride == 0.  bin = (bits(|g+e|)) >> kHistShift.
+// c % stride == 0.  bin = (bits(|g+e|)) >> kHistShift.  Workgroups of a row add
+// their LDS histograms into the row's global one.
 template <typename GT>
 __global__ __launch_bounds__(256) void mv_sample_hist(const GT* __restrict__ g, int64_t ld_g,
                                                       const float* __restrict__ e, int64_t ld_e,
@@ -136,15 +148,14 @@ __global__ __launch_bounds__(256) void mv_sample_hist(const GT* __restrict__ g, 
                                                       uint32_t* __restrict__ hist)
 {
     __shared__ uint32_t h[kHistBins];
-    const uint32_t row = blockIdx.y;
-    for (int b = threadIdx.x; b < kHistBins; b += blockDim.x) h[b] = 0;
+    const uint32_t row = blockIdx.y, t = threadIdx.x;
+    for (int b = t; b < kHistBins; b += 256) h[b] = 0;
     __syncthreads();
 
     const GT*    grow = g + (int64_t)row * ld_g;
     const float* erow = e + (int64_t)row * ld_e;
     const uint64_t nquads = (uint64_t)n_sampled_chunks * (kChunk / 4);
-    for (uint64_t q = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; q < nquads;
-         q += (uint64_t)gridDim.x * blockDim.x) {
+    for (uint64_t q = (uint64_t)blockIdx.x * 256 + t; q < nquads; q += (uint64_t)gridDim.x * 256) {
         const int64_t j = (int64_t)(q / (kChunk / 4)) * stride * kChunk + (int64_t)(q % (kChunk / 4)) * 4;
         if (j + 4 <= d) {
             f32x4 gv = load4_grad(grow + j);
@@ -163,18 +174,17 @@ __global__ __launch_bounds__(256) void mv_sample_hist(const GT* __restrict__ g, 
     }
     __syncthreads();
     uint32_t* hrow = hist + (size_t)row * kHistBins;
-    for (int b = threadIdx.x; b < kHistBins; b += blockDim.x) {
+    for (int b = t; b < kHistBins; b += 256) {
         uint32_t c = h[b];
         if (c) atomicAdd(&hrow[b], c);
     }
 }
 
-// ----------------------------------------------------------------------------
-// 2. threshold pick (one workgroup per row) + per-step reset of the counters
-// ----------------------------------------------------------------------------
-// tau_bits[row] = lower edge of the highest bin such that at least `m_target`
-// sampled coordinates lie in that bin or above; 0 if the sample holds fewer.
-// The histogram is cleared after it is read so the next step starts from zero.
+// One workgroup per row:
+//   tau_bits[row] = lower edge of the highest bin such that at least m_target
+//                   sampled coordinates lie in that bin or above (0 if fewer).
+// The histogram is cleared after it is read so the next step starts from zero,
+// and the row's per-step counters are reset.
 __global__ __launch_bounds__(kRowThreads) void mv_pick_threshold(uint32_t* __restrict__ hist,
                                                                  uint32_t m_target,
                                                                  uint32_t* __restrict__ tau_bits,
@@ -186,12 +196,12 @@ __global__ __launch_bounds__(kRowThreads) void mv_pick_threshold(uint32_t* __res
     __shared__ uint32_t found;
     const uint32_t row = blockIdx.x, t = threadIdx.x;
     uint32_t* hrow = hist + (size_t)row * kHistBins;
-    constexpr int per = kHistBins / kRowThreads;   // 4 bins per thread, descending bin order
+    constexpr int per = kHistBins / kRowThreads;   // bins per thread, descending bin order
     uint32_t c[per];
     uint32_t s = 0;
 #pragma unroll
     for (int q = 0; q < per; ++q) {
-        const int bin = kHistBins - 1 - (t * per + q);
+        const int bin = kHistBins - 1 - ((int)t * per + q);
         c[q] = hrow[bin];
         hrow[bin] = 0;
         s += c[q];
@@ -201,7 +211,7 @@ __global__ __launch_bounds__(kRowThreads) void mv_pick_threshold(uint32_t* __res
         row_count[row] = 0;
         slow_flag[row] = 0;
     }
-    if (row == 0 && t < 256) cnt_ge[t] = 0;
+    if (t < 256) cnt_ge[(size_t)row * 256 + t] = 0;   // the row's 256 vote-level counters
     uint64_t total;
     const uint64_t excl = block_excl_scan64<kRowThreads>(s, scan_lds, total);
     if (excl < m_target && (uint64_t)m_target <= excl + s) {
@@ -209,7 +219,7 @@ __global__ __launch_bounds__(kRowThreads) void mv_pick_threshold(uint32_t* __res
 #pragma unroll
         for (int q = 0; q < per; ++q) {
             if (acc < m_target && (uint64_t)m_target <= acc + c[q])
-                found = (uint32_t)(kHistBins - 1 - (t * per + q)) << kHistShift;
+                found = (uint32_t)(kHistBins - 1 - ((int)t * per + q)) << kHistShift;
             acc += c[q];
         }
     }
@@ -218,7 +228,7 @@ __global__ __launch_bounds__(kRowThreads) void mv_pick_threshold(uint32_t* __res
 }
 
 // ----------------------------------------------------------------------------
-// 3. the streaming pass
+// 2. the streaming pass
 // ----------------------------------------------------------------------------
 // One wavefront = one segment of 1024 consecutive coordinates of one row, read
 // as 4 sub-blocks of 256 (lane l holds coordinates base + 256u + 4l .. +3).
@@ -321,11 +331,13 @@ __global__ __launch_bounds__(kStreamThreads) void mv_stream_collect(
 }
 
 // ----------------------------------------------------------------------------
-// 4. per-row exact select, then ordered emission of the vote + vote counting
+// 3. per-row exact select
 // ----------------------------------------------------------------------------
 
 constexpr int kSelBins = 2048;   // radix-select digit: 11, 10, 10 bits of the 31-bit key
 constexpr int kKeep    = 48;     // candidate keys a thread of mv_row_select can hold in registers
+constexpr int kTieCap  = 8192;   // ties with the K-th magnitude that fit the LDS list
+constexpr int kBinCap  = 1024;   // candidates of one fine-histogram bin ranked by brute force
 
 __device__ __forceinline__ int      sel_shift(int pass) { return pass == 0 ? 20 : pass == 1 ? 10 : 0; }
 __device__ __forceinline__ uint32_t sel_dmask(int pass) { return pass == 0 ? 2047u : 1023u; }
@@ -348,9 +360,10 @@ __device__ __forceinline__ void tally_digit(uint32_t* hist, bool active, uint32_
 
 // With the digit histogram of the keys that match `prefix` complete: finds the
 // digit that holds the `remaining`-th largest of them and narrows the search.
+// `in_digit` receives how many keys carry that digit.
 __device__ __forceinline__ void narrow_by_digit(const uint32_t* hist, uint64_t* scan_lds, uint32_t* bcast,
                                                 int pass, uint32_t& prefix, uint32_t& known,
-                                                uint32_t& remaining)
+                                                uint32_t& remaining, uint32_t& in_digit)
 {
     // thread t owns digits 2047-2t and 2046-2t (descending order over threads)
     const int      top = kSelBins - 1 - 2 * (int)threadIdx.x;
@@ -361,30 +374,35 @@ __device__ __forceinline__ void narrow_by_digit(const uint32_t* hist, uint64_t* 
         if ((uint64_t)remaining <= ex + h0) {
             bcast[0] = (uint32_t)top;
             bcast[1] = remaining - (uint32_t)ex;
+            bcast[2] = h0;
         } else {
             bcast[0] = (uint32_t)(top - 1);
             bcast[1] = remaining - (uint32_t)ex - h0;
+            bcast[2] = h1;
         }
     }
     __syncthreads();
     prefix |= bcast[0] << sel_shift(pass);
     known |= sel_dmask(pass) << sel_shift(pass);
     remaining = bcast[1];
+    in_digit = bcast[2];
     __syncthreads();
 }
 
 // Exact K-th largest of `count` keys delivered by `key_at(i)`, by an MSB-first
 // radix select (11 + 10 + 10 bits) in one workgroup of kRowThreads threads; the
 // keys are re-read in every pass.  Returns the K-th largest key; `take_eq`
-// receives how many keys EQUAL to it belong to the top K (>= 1).
-// Requires 1 <= K <= count.  All threads of the workgroup must call it.
+// receives how many keys EQUAL to it belong to the top K (>= 1) and `n_eq` how
+// many keys equal it in all.  Requires 1 <= K <= count.  All threads of the
+// workgroup must call it.
 template <typename KeyAt>
 __device__ __forceinline__ uint32_t block_radix_select_mem(KeyAt key_at, uint64_t count, uint32_t K,
                                                            uint32_t* hist /*kSelBins*/, uint64_t* scan_lds,
-                                                           uint32_t* bcast /*2*/, uint32_t& take_eq)
+                                                           uint32_t* bcast /*3*/, uint32_t& take_eq,
+                                                           uint32_t& n_eq)
 {
     const uint32_t lane = lane_id();
-    uint32_t prefix = 0, known = 0, remaining = K;
+    uint32_t prefix = 0, known = 0, remaining = K, in_digit = 0;
 #pragma unroll
     for (int pass = 0; pass < 3; ++pass) {
         for (int b = threadIdx.x; b < kSelBins; b += kRowThreads) hist[b] = 0;
@@ -404,9 +422,10 @@ __device__ __forceinline__ uint32_t block_radix_select_mem(KeyAt key_at, uint64_
             }
         }
         __syncthreads();
-        narrow_by_digit(hist, scan_lds, bcast, pass, prefix, known, remaining);
+        narrow_by_digit(hist, scan_lds, bcast, pass, prefix, known, remaining, in_digit);
     }
     take_eq = remaining;
+    n_eq = in_digit;
     return prefix;
 }
 
@@ -414,10 +433,10 @@ __device__ __forceinline__ uint32_t block_radix_select_mem(KeyAt key_at, uint64_
 // q * kRowThreads + t in k[q]; entries at or beyond `count` are ignored.
 __device__ __forceinline__ uint32_t block_radix_select_regs(const uint32_t (&k)[kKeep], uint32_t count,
                                                             uint32_t K, uint32_t* hist, uint64_t* scan_lds,
-                                                            uint32_t* bcast, uint32_t& take_eq)
+                                                            uint32_t* bcast, uint32_t& take_eq, uint32_t& n_eq)
 {
     const uint32_t lane = lane_id();
-    uint32_t prefix = 0, known = 0, remaining = K;
+    uint32_t prefix = 0, known = 0, remaining = K, in_digit = 0;
 #pragma unroll
     for (int pass = 0; pass < 3; ++pass) {
         for (int b = threadIdx.x; b < kSelBins; b += kRowThreads) hist[b] = 0;
@@ -431,9 +450,10 @@ __device__ __forceinline__ uint32_t block_radix_select_regs(const uint32_t (&k)[
             }
         }
         __syncthreads();
-        narrow_by_digit(hist, scan_lds, bcast, pass, prefix, known, remaining);
+        narrow_by_digit(hist, scan_lds, bcast, pass, prefix, known, remaining, in_digit);
     }
     take_eq = remaining;
+    n_eq = in_digit;
     return prefix;
 }
 
@@ -448,32 +468,36 @@ __device__ __forceinline__ void cast_vote(uint32_t* __restrict__ votes32, uint32
     atomicAdd(&lvl[((old >> sh) & 255u) + 1u], 1u);
 }
 
-// per-segment tally of taken candidates: magnitudes above kth in the high half,
-// ties with kth in the low half (a segment holds at most 1024 of each)
-__device__ __forceinline__ void tally_segment(uint32_t* __restrict__ seg_sel_row, uint32_t key, uint32_t idx,
-                                              uint32_t kth)
+// A candidate (magnitude bits, coordinate) is in the row's top K iff its
+// magnitude is above the K-th largest, or equals it and its coordinate is not
+// beyond the last tie taken (ties go to the lowest coordinates).
+__device__ __forceinline__ bool is_taken(u32x2 c, uint32_t kth, uint32_t tie_cut)
 {
-    if (key >= kth) atomicAdd(&seg_sel_row[idx / kSeg], key > kth ? 0x10000u : 1u);
+    return c.x > kth || (c.x == kth && c.y <= tie_cut);
 }
 
 // One workgroup per row.
 // Usual case: radix select over the row's candidate list gives the K-th largest
-// magnitude kth[row] and how many of its ties to take, take_eq[row];
-// mv_row_tally, mv_seg_scan and mv_row_emit then write the vote.
+// magnitude kth[row]; if only some of the candidates tied with it belong to the
+// top K, a second select over the ties' coordinates gives tie_cut[row], the
+// largest tied coordinate taken (0xFFFFFFFF: all ties taken).
 // If the candidate count is < K or overflowed the list (for instance a row of
 // equal magnitudes), the row is instead selected exactly from memory (e already
-// holds a = g + e), and its vote is emitted here; slow_flag[row] = 1 tells the
-// next three kernels to skip the row.
+// holds a = g + e), and its vote is emitted and cast here; slow_flag[row] = 1
+// tells the later kernels to skip the row.
 __global__ __launch_bounds__(kRowThreads) void mv_row_select(
     const float* __restrict__ e, int64_t ld_e, int64_t d, uint32_t K,
     const u32x2* __restrict__ cand, uint32_t cap, const uint32_t* __restrict__ row_count,
-    uint32_t* __restrict__ kth_out, uint32_t* __restrict__ take_out,
+    const uint32_t* __restrict__ tau_bits,
+    uint32_t* __restrict__ kth_out, uint32_t* __restrict__ tie_cut_out,
     uint32_t* __restrict__ worker_idx, uint32_t* __restrict__ votes32,
     uint32_t* __restrict__ cnt_ge, uint32_t* __restrict__ slow_flag)
 {
-    __shared__ uint32_t hist[kSelBins];
+    __shared__ __attribute__((aligned(16))) uint32_t hist[kSelBins];
+    __shared__ __attribute__((aligned(16))) uint32_t ties[kTieCap];
     __shared__ uint32_t lvl[257];
-    __shared__ uint32_t bcast[2];
+    __shared__ uint32_t bcast[3];
+    __shared__ uint32_t n_ties;
     __shared__ uint64_t scan_lds[kRowThreads / kWave + 1];
 
     const uint32_t row = blockIdx.x, t = threadIdx.x;
@@ -481,7 +505,10 @@ __global__ __launch_bounds__(kRowThreads) void mv_row_select(
 
     if (C >= K && C <= cap) {
         const u32x2* crow = cand + (size_t)row * cap;
-        uint32_t kth, take_eq;
+        const uint32_t tau = tau_bits[row];
+        const uint32_t lane = lane_id();
+        uint32_t kth, take_eq, n_eq;
+        if (t == 0) n_ties = 0;                   // ordered by the first barrier below
         if (C <= (uint32_t)kKeep * kRowThreads) {
             // entries past C are clamped to the last candidate and ignored later
             uint32_t k[kKeep];
@@ -491,14 +518,103 @@ __global__ __launch_bounds__(kRowThreads) void mv_row_select(
                 k[q] = crow[min((uint32_t)q * kRowThreads + t, last)].x;
                 if ((q & 7) == 7) __builtin_amdgcn_sched_barrier(0);   // keep address arithmetic from piling up
             }
-            kth = block_radix_select_regs(k, C, K, hist, scan_lds, bcast, take_eq);
+            if (tau != 0) {
+                // ---- short cut.  All candidates are >= tau and most lie within an
+                // octave of it: one histogram of (key - tau) in 2048 bins finds the bin
+                // that holds the K-th largest; if that bin holds few candidates they
+                // are ranked by brute force under (magnitude desc, coordinate asc).
+                for (int b = t; b < kFineBins; b += kRowThreads) hist[b] = 0;
+                __syncthreads();
+#pragma unroll
+                for (int q = 0; q < kKeep; ++q) {
+                    if ((uint32_t)q * kRowThreads < C) {              // uniform over the workgroup
+                        const uint32_t i = (uint32_t)q * kRowThreads + t;
+                        tally_digit(hist, i < C, fine_bin(k[q], tau), lane);
+                    }
+                }
+                __syncthreads();
+                uint32_t bin = 0, known = 0, want = K, in_bin = 0;
+                narrow_by_digit(hist, scan_lds, bcast, 2, bin, known, want, in_bin);   // pass 2: shift 0
+                if (in_bin <= (uint32_t)kBinCap) {        // uniform
+                    // collect the bin's candidates: magnitude in hist[], coordinate in ties[]
+#pragma unroll
+                    for (int q = 0; q < kKeep; ++q) {
+                        const uint32_t i = (uint32_t)q * kRowThreads + t;
+                        if (i < C && fine_bin(k[q], tau) == bin) {
+                            const uint32_t p = atomicAdd(&n_ties, 1u);
+                            hist[p] = k[q];
+                            ties[p] = crow[i].y;
+                        }
+                    }
+                    if (t < 4) {                          // pad to a multiple of 4 with entries ranked last
+                        hist[in_bin + t] = 0;
+                        ties[in_bin + t] = 0xFFFFFFFFu;
+                    }
+                    __syncthreads();
+                    // the candidate with exactly want-1 others ahead of it is the last of the top K
+                    if (t < in_bin) {
+                        const uint32_t mk = hist[t], mi = ties[t];
+                        uint32_t ahead = 0;
+                        const u32x4* hk = reinterpret_cast<const u32x4*>(hist);
+                        const u32x4* hi = reinterpret_cast<const u32x4*>(ties);
+#pragma unroll 4
+                        for (uint32_t j = 0; j < (in_bin + 3) / 4; ++j) {
+                            const u32x4 ok = hk[j], oi = hi[j];
+                            ahead += (ok.x > mk) || (ok.x == mk && oi.x < mi);
+                            ahead += (ok.y > mk) || (ok.y == mk && oi.y < mi);
+                            ahead += (ok.z > mk) || (ok.z == mk && oi.z < mi);
+                            ahead += (ok.w > mk) || (ok.w == mk && oi.w < mi);
+                        }
+                        if (ahead == want - 1) {
+                            kth_out[row] = mk;
+                            tie_cut_out[row] = mi;
+                        }
+                    }
+                    return;
+                }
+            }
+            if (t == 0) slow_flag[row] = 2;       // diagnostic only: the short cut did not apply
+            kth = block_radix_select_regs(k, C, K, hist, scan_lds, bcast, take_eq, n_eq);
+            if (take_eq < n_eq && n_eq <= (uint32_t)kTieCap) {
+#pragma unroll
+                for (int q = 0; q < kKeep; ++q) {
+                    const uint32_t i = (uint32_t)q * kRowThreads + t;
+                    if (i < C && k[q] == kth) ties[atomicAdd(&n_ties, 1u)] = crow[i].y;
+                }
+            }
         } else {
+            if (t == 0) slow_flag[row] = 2;
             kth = block_radix_select_mem([&](uint64_t i) { return crow[i].x; }, C, K, hist, scan_lds,
-                                         bcast, take_eq);
+                                         bcast, take_eq, n_eq);
+            if (take_eq < n_eq && n_eq <= (uint32_t)kTieCap) {
+                for (uint32_t i = t; i < C; i += kRowThreads) {
+                    const u32x2 c = crow[i];
+                    if (c.x == kth) ties[atomicAdd(&n_ties, 1u)] = c.y;
+                }
+            }
+        }
+        uint32_t tie_cut = 0xFFFFFFFFu;
+        if (take_eq < n_eq) {                     // uniform: only the lowest take_eq tied coordinates are taken
+            // the take_eq-th SMALLEST coordinate among the ties = the take_eq-th
+            // largest of (0x7FFFFFFF - coordinate); entries that are not ties map to 0
+            uint32_t dummy_take, dummy_eq, kq;
+            __syncthreads();
+            if (n_eq <= (uint32_t)kTieCap) {
+                kq = block_radix_select_mem([&](uint64_t i) { return kAbsMask - ties[i]; }, n_eq, take_eq,
+                                            hist, scan_lds, bcast, dummy_take, dummy_eq);
+            } else {
+                kq = block_radix_select_mem(
+                    [&](uint64_t i) {
+                        const u32x2 c = crow[i];
+                        return c.x == kth ? kAbsMask - c.y : 0u;
+                    },
+                    C, take_eq, hist, scan_lds, bcast, dummy_take, dummy_eq);
+            }
+            tie_cut = kAbsMask - kq;
         }
         if (t == 0) {
             kth_out[row] = kth;
-            take_out[row] = take_eq;
+            tie_cut_out[row] = tie_cut;
         }
         return;
     }
@@ -508,10 +624,10 @@ __global__ __launch_bounds__(kRowThreads) void mv_row_select(
     for (int i = t; i < 257; i += kRowThreads) lvl[i] = 0;   // ordered by the select's first barrier
     uint32_t* out = worker_idx ? worker_idx + (size_t)row * K : nullptr;
     const float* arow = e + (int64_t)row * ld_e;
-    uint32_t take_eq;
+    uint32_t take_eq, n_eq;
     const uint32_t kth = block_radix_select_mem(
         [&](uint64_t i) { return __float_as_uint(arow[i]) & kAbsMask; }, (uint64_t)d, K, hist, scan_lds,
-        bcast, take_eq);
+        bcast, take_eq, n_eq);
     uint32_t gt_before = 0, eq_before = 0;
     for (int64_t j0 = 0; j0 < d; j0 += (int64_t)kRowThreads * 4) {
         const int64_t j = j0 + (int64_t)t * 4;
@@ -547,147 +663,153 @@ __global__ __launch_bounds__(kRowThreads) void mv_row_select(
     __syncthreads();
     for (int i = t; i < 256; i += kRowThreads) {
         const uint32_t c = lvl[i];
-        if (c) atomicAdd(&cnt_ge[i], c);
+        if (c) atomicAdd(&cnt_ge[(size_t)row * 256 + i], c);
     }
 }
 
-// One thread per candidate: tallies, per 1024-coordinate segment, the candidates
-// above kth and tied with it (seg_sel was zeroed by the streaming pass).
-__global__ __launch_bounds__(kVoteThreads) void mv_row_tally(
+// ----------------------------------------------------------------------------
+// 4. vote casting
+// ----------------------------------------------------------------------------
+// One thread per candidate: a taken candidate casts its vote and, when the
+// sorted vote lists are wanted (seg_sel != nullptr), is tallied in its
+// 1024-coordinate segment (seg_sel was zeroed by the streaming pass).
+__global__ __launch_bounds__(kVoteThreads) void mv_row_votes(
     const u32x2* __restrict__ cand, uint32_t cap, const uint32_t* __restrict__ row_count, uint32_t nseg,
-    const uint32_t* __restrict__ kth_in, const uint32_t* __restrict__ slow_flag,
-    uint32_t* __restrict__ seg_sel)
-{
-    const uint32_t row = blockIdx.y;
-    if (slow_flag[row]) return;
-    const uint32_t C = row_count[row];
-    const uint32_t kth = kth_in[row];
-    const u32x2* crow = cand + (size_t)row * cap;
-    uint32_t*    ssel = seg_sel + (size_t)row * nseg;
-    for (uint64_t i = (uint64_t)blockIdx.x * kVoteThreads + threadIdx.x; i < C;
-         i += (uint64_t)gridDim.x * kVoteThreads) {
-        const u32x2 c = crow[i];
-        tally_segment(ssel, c.x, c.y, kth);
-    }
-}
-
-// Exclusive scan of the segment tallies along each row:
-// seg_pre[row][s] = (above kth, tied with kth) summed over all segments before s.
-// A workgroup scans 1024 segments and adds up everything before its range itself.
-__global__ __launch_bounds__(kRowThreads) void mv_seg_scan(const uint32_t* __restrict__ seg_sel, uint32_t nseg,
-                                                          const uint32_t* __restrict__ slow_flag,
-                                                          u32x2* __restrict__ seg_pre)
-{
-    __shared__ uint64_t scan_lds[kRowThreads / kWave + 1];
-    const uint32_t row = blockIdx.y, t = threadIdx.x;
-    if (slow_flag[row]) return;                 // whole workgroup
-    const uint32_t* ssel = seg_sel + (size_t)row * nseg;
-    const uint32_t s0 = blockIdx.x * kRowThreads;
-    uint64_t mine = 0;
-    for (uint32_t i = t; i < s0; i += kRowThreads) {
-        const uint32_t v = ssel[i];
-        mine += pack2(v >> 16, v & 0xFFFFu);
-    }
-    uint64_t before;
-    (void)block_excl_scan64<kRowThreads>(mine, scan_lds, before);
-    __syncthreads();
-    const uint32_t s = s0 + t;
-    const uint32_t v = (s < nseg) ? ssel[s] : 0u;
-    uint64_t total;
-    const uint64_t ex = before + block_excl_scan64<kRowThreads>(pack2(v >> 16, v & 0xFFFFu), scan_lds, total);
-    if (s < nseg) {
-        u32x2 r;
-        r.x = (uint32_t)(ex >> 32);
-        r.y = (uint32_t)ex;
-        seg_pre[(size_t)row * nseg + s] = r;
-    }
-}
-
-// One thread per candidate.  A candidate at or above kth finds its rank in the
-// row's ascending vote list as (above-kth before it) + min(ties before it,
-// take_eq): the part from earlier segments comes from seg_pre, the part from its
-// own segment by walking back along its run (runs are ascending inside a
-// segment), so the list comes out sorted without a sort.  Each taken coordinate
-// also casts its vote.
-__global__ __launch_bounds__(kVoteThreads) void mv_row_emit(
-    const u32x2* __restrict__ cand, uint32_t cap, const uint32_t* __restrict__ row_count,
-    const u32x2* __restrict__ seg, uint32_t nseg, uint32_t K, const uint32_t* __restrict__ kth_in,
-    const uint32_t* __restrict__ take_in, const uint32_t* __restrict__ slow_flag,
-    const u32x2* __restrict__ seg_pre, uint32_t* __restrict__ worker_idx,
+    const uint32_t* __restrict__ kth_in, const uint32_t* __restrict__ tie_cut_in,
+    const uint32_t* __restrict__ slow_flag, uint32_t* __restrict__ seg_sel,
     uint32_t* __restrict__ votes32, uint32_t* __restrict__ cnt_ge)
 {
     __shared__ uint32_t lvl[257];
     const uint32_t row = blockIdx.y, t = threadIdx.x;
-    if (slow_flag[row]) return;                 // whole workgroup
+    if (slow_flag[row] == 1u) return;                              // whole workgroup
     const uint32_t C = row_count[row];
-    if ((uint64_t)blockIdx.x * kVoteThreads >= C) return;   // whole workgroup
+    if ((uint64_t)blockIdx.x * kVoteThreads >= C) return;    // whole workgroup
     for (int i = t; i < 257; i += kVoteThreads) lvl[i] = 0;
     __syncthreads();
-    const uint32_t kth = kth_in[row], take_eq = take_in[row];
+    const uint32_t kth = kth_in[row], tie_cut = tie_cut_in[row];
     const u32x2* crow = cand + (size_t)row * cap;
-    const u32x2* srow = seg + (size_t)row * nseg;
-    const u32x2* prow = seg_pre + (size_t)row * nseg;
-    uint32_t* out = worker_idx ? worker_idx + (size_t)row * K : nullptr;
-
-    for (uint64_t i = (uint64_t)blockIdx.x * kVoteThreads + t; i < C; i += (uint64_t)gridDim.x * kVoteThreads) {
-        const u32x2 c = crow[i];
-        if (c.x < kth) continue;
-        const uint32_t s = c.y / kSeg;
-        const u32x2 run = srow[s];
-        const u32x2 pre = prow[s];
-        uint32_t gt_before = pre.x, eq_before = pre.y;
-        for (uint32_t j = run.x; j < (uint32_t)i; ++j) {
-            const uint32_t k = crow[j].x;
-            gt_before += (k > kth);
-            eq_before += (k == kth);
+    uint32_t*    ssel = seg_sel ? seg_sel + (size_t)row * nseg : nullptr;
+    const uint32_t lane = lane_id();
+    for (uint64_t i0 = (uint64_t)blockIdx.x * kVoteThreads; i0 < C; i0 += (uint64_t)gridDim.x * kVoteThreads) {
+        const uint64_t i = i0 + t;
+        u32x2 c = {0u, 0xFFFFFFFFu};
+        bool taken = false;
+        if (i < C) {
+            c = crow[i];
+            taken = is_taken(c, kth, tie_cut);
         }
-        if (c.x > kth || eq_before < take_eq) {
-            const uint32_t pos = gt_before + min(eq_before, take_eq);
-            if (out && pos < K) out[pos] = c.y;
-            cast_vote(votes32, c.y, lvl);
+        if (taken) cast_vote(votes32, c.y, lvl);
+        if (ssel) {
+            // neighbouring list entries mostly share a segment (they are one run):
+            // the first lane of each group of equal segments adds the group's count
+            const uint32_t sg = c.y / kSeg;
+            const uint32_t prev = __shfl_up(sg, 1, kWave);
+            const uint64_t heads = __ballot(lane == 0 || sg != prev);
+            const uint64_t tk = __ballot(taken);
+            if (heads & (1ull << lane)) {
+                const uint64_t above = (lane == kWave - 1) ? 0ull : (heads >> (lane + 1));
+                const uint32_t len = above ? (uint32_t)__ffsll((long long)above) : (kWave - lane);
+                const uint64_t span = (len >= 64 ? ~0ull : ((1ull << len) - 1)) << lane;
+                const uint32_t n = (uint32_t)__popcll(tk & span);
+                if (n) atomicAdd(&ssel[sg], n);
+            }
         }
     }
     __syncthreads();
     for (int i = t; i < 256; i += kVoteThreads) {
         const uint32_t c = lvl[i];
-        if (c) atomicAdd(&cnt_ge[i], c);
+        if (c) atomicAdd(&cnt_ge[(size_t)row * 256 + i], c);
     }
 }
 
 // ----------------------------------------------------------------------------
-// 5. global mask = the K most voted coordinates, ties to the lowest coordinate
+// 5. global mask = the K most voted coordinates, ties to the lowest coordinate;
+//    beside it, the sorted vote lists
 // ----------------------------------------------------------------------------
 // cnt_ge[v] = number of coordinates with at least v votes (v = 1..N).  The
 // threshold v* is the largest v with cnt_ge[v] >= K: all cnt_ge[v*+1]
 // coordinates above it are taken, and the first K - cnt_ge[v*+1] coordinates
 // (in coordinate order) with exactly v* votes.
 __device__ __forceinline__ void vote_threshold(const uint32_t* __restrict__ cnt_ge, uint32_t N,
-                                               uint32_t K, uint32_t* lds2, uint32_t& vstar,
-                                               uint32_t& take_eq)
+                                               uint32_t K, uint32_t* lds_lvl /*256*/, uint32_t* lds2,
+                                               uint32_t& vstar, uint32_t& take_eq)
 {
+    // cnt_ge holds one set of 256 level counters per worker row; thread v sums level v
+    for (uint32_t v = threadIdx.x; v < 256; v += blockDim.x) {
+        uint32_t sum = 0;
+        if (v >= 1 && v <= N)
+            for (uint32_t n = 0; n < N; ++n) sum += cnt_ge[(size_t)n * 256 + v];
+        lds_lvl[v] = sum;
+    }
+    __syncthreads();
     if (threadIdx.x == 0) {
         uint32_t v = N;
-        while (v > 1 && cnt_ge[v] < K) --v;
+        while (v > 1 && lds_lvl[v] < K) --v;
         lds2[0] = v;
-        lds2[1] = K - ((v < N) ? cnt_ge[v + 1] : 0u);
+        lds2[1] = K - ((v < N) ? lds_lvl[v + 1] : 0u);
     }
     __syncthreads();
     vstar = lds2[0];
     take_eq = lds2[1];
 }
 
-// counts, per block of kVoteBlock coordinates, how many have votes > v* and == v*;
-// optionally copies the vote bytes to the caller's array.
+// Exclusive scan of a row's segment tallies, in blocks of 1024 segments:
+// seg_pre[s] = taken candidates in the earlier segments of s's block, and
+// blk_total[blk] = taken candidates in the whole block.
+__device__ __forceinline__ void seg_scan_block(const uint32_t* __restrict__ ssel, uint32_t nseg,
+                                               uint32_t blk, uint32_t* __restrict__ spre,
+                                               uint32_t* __restrict__ blk_total, uint64_t* scan_lds)
+{
+    const uint32_t t = threadIdx.x;
+    const uint32_t s0 = blk * 1024u;
+    uint32_t v[4];
+    uint32_t sum = 0;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const uint32_t s = s0 + t * 4 + q;
+        v[q] = (s < nseg) ? ssel[s] : 0u;
+        sum += v[q];
+    }
+    uint64_t total;
+    uint64_t ex = block_excl_scan64<kVoteThreads>(sum, scan_lds, total);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const uint32_t s = s0 + t * 4 + q;
+        if (s < nseg) spre[s] = (uint32_t)ex;
+        ex += v[q];
+    }
+    if (t == 0) blk_total[blk] = (uint32_t)total;
+}
+
+// Workgroups [0, n_vote_blocks): count, per block of kVoteBlock coordinates, how
+// many have votes > v* and == v*; optionally copy the vote bytes to the caller.
+// Workgroups beyond (only launched when the sorted vote lists are wanted): scan
+// the segment tallies of row (b / scan_blocks), block (b % scan_blocks).
 __global__ __launch_bounds__(kVoteThreads) void mv_mask_count(const uint32_t* __restrict__ votes32,
                                                               int64_t d, uint32_t N, uint32_t K,
                                                               const uint32_t* __restrict__ cnt_ge,
                                                               u32x2* __restrict__ block_cnt,
-                                                              uint8_t* __restrict__ votes_out)
+                                                              uint8_t* __restrict__ votes_out,
+                                                              uint32_t n_vote_blocks, uint32_t scan_blocks,
+                                                              uint32_t nseg,
+                                                              const uint32_t* __restrict__ slow_flag,
+                                                              const uint32_t* __restrict__ seg_sel,
+                                                              uint32_t* __restrict__ seg_pre,
+                                                              uint32_t* __restrict__ blk_total)
 {
     __shared__ uint32_t lds2[2];
+    __shared__ uint32_t lds_lvl[256];
     __shared__ uint64_t scan_lds[kVoteThreads / kWave + 1];
+    if (blockIdx.x >= n_vote_blocks) {
+        const uint32_t b = blockIdx.x - n_vote_blocks;
+        const uint32_t row = b / scan_blocks;
+        if (slow_flag[row] == 1u) return;
+        seg_scan_block(seg_sel + (size_t)row * nseg, nseg, b % scan_blocks, seg_pre + (size_t)row * nseg,
+                       blk_total + (size_t)row * scan_blocks, scan_lds);
+        return;
+    }
     uint32_t vstar, take_eq;
-    vote_threshold(cnt_ge, N, K, lds2, vstar, take_eq);
+    vote_threshold(cnt_ge, N, K, lds_lvl, lds2, vstar, take_eq);
     const int64_t base = (int64_t)blockIdx.x * kVoteBlock;
     uint32_t gt = 0, eq = 0;
 #pragma unroll
@@ -724,17 +846,66 @@ __global__ __launch_bounds__(kVoteThreads) void mv_mask_count(const uint32_t* __
     }
 }
 
-// emits the mask in ascending order and clears the vote words for the next step
+// One thread per candidate of a row: a taken candidate's rank in the row's
+// ascending vote list is (taken candidates in earlier blocks of 1024 segments,
+// from blk_total) + (in earlier segments of its block, from seg_pre) + (before
+// it in its own segment's run; runs are ascending), so the list comes out
+// sorted without a sort.
+__device__ __forceinline__ void row_emit_block(const u32x2* __restrict__ crow, uint32_t C,
+                                               const u32x2* __restrict__ srow,
+                                               const uint32_t* __restrict__ prow,
+                                               const uint32_t* __restrict__ blk_total, uint32_t scan_blocks,
+                                               uint32_t K, uint32_t kth, uint32_t tie_cut, uint32_t blk,
+                                               uint32_t nblk, uint32_t* __restrict__ out)
+{
+    if ((uint64_t)blk * kVoteThreads >= C) return;           // whole workgroup
+    for (uint64_t i = (uint64_t)blk * kVoteThreads + threadIdx.x; i < C; i += (uint64_t)nblk * kVoteThreads) {
+        const u32x2 c = crow[i];
+        if (!is_taken(c, kth, tie_cut)) continue;
+        const uint32_t s = c.y / kSeg;
+        uint32_t pos = prow[s];
+        const uint32_t run_start = srow[s].x;
+        for (uint32_t b = 0; b < s / 1024u; ++b) pos += blk_total[b];
+        for (uint32_t j = run_start; j < (uint32_t)i; ++j) pos += is_taken(crow[j], kth, tie_cut) ? 1u : 0u;
+        if (pos < K) out[pos] = c.y;
+    }
+}
+
+// Workgroups [0, n_vote_blocks): emit the mask in ascending order and clear the
+// vote words for the next step.  Workgroups beyond (only launched when the
+// sorted vote lists are wanted): write row (b / emit_blocks)'s vote list.
 __global__ __launch_bounds__(kVoteThreads) void mv_mask_emit(uint32_t* __restrict__ votes32,
                                                              int64_t d, uint32_t N, uint32_t K,
                                                              const uint32_t* __restrict__ cnt_ge,
                                                              const u32x2* __restrict__ block_cnt,
-                                                             uint32_t* __restrict__ mask_idx)
+                                                             uint32_t* __restrict__ mask_idx,
+                                                             uint32_t n_vote_blocks, uint32_t emit_blocks,
+                                                             const u32x2* __restrict__ cand, uint32_t cap,
+                                                             const uint32_t* __restrict__ row_count,
+                                                             const u32x2* __restrict__ seg, uint32_t nseg,
+                                                             const uint32_t* __restrict__ seg_pre,
+                                                             const uint32_t* __restrict__ blk_total,
+                                                             uint32_t scan_blocks,
+                                                             const uint32_t* __restrict__ kth_in,
+                                                             const uint32_t* __restrict__ tie_cut_in,
+                                                             const uint32_t* __restrict__ slow_flag,
+                                                             uint32_t* __restrict__ worker_idx)
 {
     __shared__ uint32_t lds2[2];
+    __shared__ uint32_t lds_lvl[256];
     __shared__ uint64_t scan_lds[kVoteThreads / kWave + 1];
+    if (blockIdx.x >= n_vote_blocks) {
+        const uint32_t b = blockIdx.x - n_vote_blocks;
+        const uint32_t row = b / emit_blocks;
+        if (slow_flag[row] == 1u) return;
+        row_emit_block(cand + (size_t)row * cap, row_count[row], seg + (size_t)row * nseg,
+                       seg_pre + (size_t)row * nseg, blk_total + (size_t)row * scan_blocks, scan_blocks, K,
+                       kth_in[row], tie_cut_in[row], b % emit_blocks, emit_blocks,
+                       worker_idx + (size_t)row * K);
+        return;
+    }
     uint32_t vstar, take_eq;
-    vote_threshold(cnt_ge, N, K, lds2, vstar, take_eq);
+    vote_threshold(cnt_ge, N, K, lds_lvl, lds2, vstar, take_eq);
 
     // coordinates selected / tied before this block
     uint64_t mine = 0;
