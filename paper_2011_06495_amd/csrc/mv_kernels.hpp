@@ -43,7 +43,7 @@ typedef uint16_t u16x4 __attribute__((ext_vector_type(4)));
 
 constexpr int      kWave           = 64;
 constexpr int      kSeg            = 1024;   // coordinates per wavefront segment in the streaming pass
-constexpr int      kStreamThreads  = 256;    // 4 segments per workgroup
+constexpr int      kStreamThreads  = 512;    // 8 segments per workgroup
 constexpr int      kSegPerBlock    = kStreamThreads / kWave;
 constexpr int      kHistBits       = 13;     // sample histogram: exponent + 5 mantissa bits
 constexpr int      kHistBins       = 1 << kHistBits;
@@ -231,13 +231,18 @@ __global__ __launch_bounds__(kRowThreads) void mv_pick_threshold(uint32_t* __res
 // 2. the streaming pass
 // ----------------------------------------------------------------------------
 // One wavefront = one segment of 1024 consecutive coordinates of one row, read
-// as 4 sub-blocks of 256 (lane l holds coordinates base + 256u + 4l .. +3).
+// as 4 sub-blocks of 256 (lane l holds coordinates base + 256u + 4l .. +3); a
+// workgroup of 8 wavefronts covers 8 consecutive segments.
 // a = g + e overwrites e.  Coordinates with (bits(a) & 0x7FFFFFFF) >= tau are
 // appended to the row's candidate list as (magnitude bits, coordinate), in
 // ascending coordinate order inside the wavefront's run; seg[row][s] =
 // (start of the run, its length).  Runs land in the list in any order; the
-// table makes the order recoverable.  Entries beyond `cap` are dropped, the
-// counter keeps counting (the overflow is detected from it).
+// table makes the order recoverable.  The workgroup reserves list space for
+// all its runs with ONE atomic on the row's counter (returning atomics on one
+// cache line complete only every few nanoseconds chip-wide, so one per
+// wavefront would bound the whole pass when candidates are spread evenly).
+// Entries beyond `cap` are dropped, the counter keeps counting (the overflow is
+// detected from it).
 template <typename GT>
 __global__ __launch_bounds__(kStreamThreads) void mv_stream_collect(
     const GT* __restrict__ g, int64_t ld_g, float* __restrict__ e, int64_t ld_e, int64_t d,
@@ -245,10 +250,12 @@ __global__ __launch_bounds__(kStreamThreads) void mv_stream_collect(
     uint32_t* __restrict__ row_count, u32x2* __restrict__ seg, uint32_t* __restrict__ seg_sel,
     uint32_t nseg)
 {
+    __shared__ uint32_t wave_total[kSegPerBlock];
+    __shared__ uint32_t block_base;
     const uint32_t row = blockIdx.y;
-    const uint32_t lane = lane_id();
-    const uint32_t s = blockIdx.x * kSegPerBlock + threadIdx.x / kWave;
-    if (s >= nseg) return;                       // whole wavefront
+    const uint32_t lane = lane_id(), wave = threadIdx.x / kWave;
+    const uint32_t s = blockIdx.x * kSegPerBlock + wave;
+    const bool live = s < nseg;                  // whole wavefront; dead ones only keep the barriers company
     const int64_t base = (int64_t)s * kSeg;
     const GT* grow = g + (int64_t)row * ld_g;
     float*    erow = e + (int64_t)row * ld_e;
@@ -256,7 +263,7 @@ __global__ __launch_bounds__(kStreamThreads) void mv_stream_collect(
 
     uint32_t key[16];
     uint32_t flags = 0;
-    if (base + kSeg <= d) {
+    if (live && base + kSeg <= d) {
         f32x4 gv[4], ev[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
@@ -276,7 +283,7 @@ __global__ __launch_bounds__(kStreamThreads) void mv_stream_collect(
         }
 #pragma unroll
         for (int i = 0; i < 16; ++i) flags |= (key[i] >= tau ? 1u : 0u) << i;
-    } else {
+    } else if (live) {
         // last segment of the row: element-wise, nothing past d is read or written
 #pragma unroll
         for (int u = 0; u < 4; ++u)
@@ -294,9 +301,11 @@ __global__ __launch_bounds__(kStreamThreads) void mv_stream_collect(
             }
     }
 
-    uint32_t total = 0, run_start = 0;
-    if (__ballot(flags != 0) != 0ull) {          // wave-uniform
-        uint32_t rank[4];
+    // rank of each kept coordinate inside the wavefront's run
+    uint32_t total = 0;
+    uint32_t rank[4] = {0, 0, 0, 0};
+    const bool any = __ballot(flags != 0) != 0ull;       // wave-uniform
+    if (any) {
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const uint32_t c = __popc((flags >> (4 * u)) & 15u);
@@ -304,8 +313,23 @@ __global__ __launch_bounds__(kStreamThreads) void mv_stream_collect(
             rank[u] = total + incl - c;
             total += __shfl(incl, kWave - 1, kWave);
         }
-        if (lane == 0) run_start = atomicAdd(&row_count[row], total);
-        run_start = __shfl(run_start, 0, kWave);
+    }
+    // one reservation for the workgroup's 8 runs
+    if (lane == 0) wave_total[wave] = total;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t sum = 0;
+#pragma unroll
+        for (int w = 0; w < kSegPerBlock; ++w) {
+            const uint32_t t = wave_total[w];
+            wave_total[w] = sum;
+            sum += t;
+        }
+        block_base = sum ? atomicAdd(&row_count[row], sum) : 0u;
+    }
+    __syncthreads();
+    const uint32_t run_start = block_base + wave_total[wave];
+    if (any) {
         u32x2* crow = cand + (size_t)row * cap;
 #pragma unroll
         for (int u = 0; u < 4; ++u)
@@ -321,12 +345,12 @@ __global__ __launch_bounds__(kStreamThreads) void mv_stream_collect(
                     }
                 }
     }
-    if (lane == 0) {
+    if (live && lane == 0) {
         u32x2 rec;
         rec.x = run_start;
         rec.y = total;
         seg[(size_t)row * nseg + s] = rec;
-        seg_sel[(size_t)row * nseg + s] = 0;     // tallied by mv_row_select
+        seg_sel[(size_t)row * nseg + s] = 0;     // tallied by mv_row_votes
     }
 }
 
