@@ -177,13 +177,23 @@ def gradient_row(w: Workload, step: int, n: int, common: Optional[np.ndarray] = 
     return g
 
 
-def gradients(w: Workload, step: int) -> np.ndarray:
-    """N x d gradient matrix of one step (float32, or uint16 holding bf16)."""
+def gradients(w: Workload, step: int, threads: int = 1) -> np.ndarray:
+    """N x d gradient matrix of one step (float32, or uint16 holding bf16).
+    threads > 1 draws the rows concurrently (same bytes: every row has its own stream)."""
     common = common_component(w, step)
     scale = coordinate_scale(w)
     out = np.empty((w.N, w.d), np.uint16 if w.grad_dtype == "bf16" else np.float32)
-    for n in range(w.N):
+
+    def one(n: int) -> None:
         out[n] = gradient_row(w, step, n, common, scale)
+
+    if threads > 1:
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(max_workers=threads) as pool:
+            list(pool.map(one, range(w.N)))
+    else:
+        for n in range(w.N):
+            one(n)
     return out
 
 

@@ -1,0 +1,78 @@
+"""Parity at the benchmark's full sizes, in the launch configuration bench.py
+times (all outputs requested, error buffer carried on the device from step to
+step).  The oracle runs the whole step on the host (row-parallel, same
+arithmetic) and every output is compared element by element."""
+import sys
+import time
+
+import numpy as np
+import pytest
+
+from paper_2011_06495_amd import workloads as W
+from tests.gpu_util import GpuStepper, assert_matches_oracle
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print("[case] " + msg, flush=True)
+    sys.stdout.flush()
+
+
+def run_full(oracle, w, steps, check_ties=False):
+    threads = min(16, oracle.max_threads())
+    e_ref = W.zero_error(w)
+    paths = []
+    with GpuStepper(w.N, w.d, w.K, bf16=(w.grad_dtype == "bf16")) as gs:
+        gs.set_error(e_ref)
+        for t in range(steps):
+            t0 = time.time()
+            g = W.gradients(w, t, threads=threads)
+            gs.set_grads(g)
+            gs.step()
+            got = gs.fetch()
+            ref = oracle.vote_step(g, e_ref, w.K, threads=threads)
+            assert_matches_oracle(got, ref, "%s full size, step %d" % (w.name, t))
+            cand, _, path = gs.row_stats()
+            paths.append(path)
+            if check_ties:
+                # the lattice workload must exercise both tie-breaks at full size
+                a = (g + e_ref) if g.dtype == np.float32 else None
+                keys = np.abs(a).view(np.uint32)
+                for n in range(w.N):
+                    kmin = keys[n][ref.worker_idx[n]].min()
+                    n_tied = int(np.count_nonzero(keys[n] == kmin))
+                    n_taken = int(np.count_nonzero(keys[n][ref.worker_idx[n]] == kmin))
+                    assert n_tied > n_taken >= 1, "row %d: boundary tie group not split" % n
+                vmin = ref.votes[ref.mask_idx].min()
+                assert np.count_nonzero(ref.votes == vmin) > np.count_nonzero(ref.votes[ref.mask_idx] == vmin)
+            e_ref = ref.err
+            say("%s step %d ok (%.1f s), candidates/row %d..%d, slow rows %d" %
+                (w.name, t, time.time() - t0, min(cand), max(cand), sum(1 for p in path if p == 1)))
+    return paths
+
+
+@pytest.mark.timeout(900)
+def test_c1_full(oracle):
+    run_full(oracle, W.C1, 1)
+
+
+@pytest.mark.timeout(900)
+def test_c2_full(oracle):
+    run_full(oracle, W.C2, 1)
+
+
+@pytest.mark.timeout(1200)
+def test_c3_full_heavy_tails_many_steps(oracle):
+    run_full(oracle, W.C3, 20)
+
+
+@pytest.mark.timeout(1200)
+def test_c4_full_lattice_ties_five_steps(oracle):
+    paths = run_full(oracle, W.C4, 5, check_ties=True)
+    assert all(p != 1 for step in paths for p in step), "the headline workload must not take the slow path"
+
+
+@pytest.mark.timeout(1200)
+def test_c5_full_bf16(oracle):
+    run_full(oracle, W.C5, 10)
