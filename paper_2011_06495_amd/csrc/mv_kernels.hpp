@@ -359,7 +359,8 @@ __global__ __launch_bounds__(kStreamThreads) void mv_stream_collect(
 // ----------------------------------------------------------------------------
 
 constexpr int kSelBins = 2048;   // radix-select digit: 11, 10, 10 bits of the 31-bit key
-constexpr int kKeep    = 48;     // candidate keys a thread of mv_row_select can hold in registers
+constexpr int kKeyBins = 4096;   // exact magnitudes inside one fine-histogram bin (1 << kFineShift)
+constexpr int kKeep    = 32;     // candidate keys a thread of mv_row_select can hold in registers
 constexpr int kTieCap  = 8192;   // ties with the K-th magnitude that fit the LDS list
 constexpr int kBinCap  = 1024;   // candidates of one fine-histogram bin ranked by brute force
 
@@ -382,55 +383,70 @@ __device__ __forceinline__ void tally_digit(uint32_t* hist, bool active, uint32_
     }
 }
 
-// With the digit histogram of the keys that match `prefix` complete: finds the
-// digit that holds the `remaining`-th largest of them and narrows the search.
-// `in_digit` receives how many keys carry that digit.
-__device__ __forceinline__ void narrow_by_digit(const uint32_t* hist, uint64_t* scan_lds, uint32_t* bcast,
-                                                int pass, uint32_t& prefix, uint32_t& known,
-                                                uint32_t& remaining, uint32_t& in_digit)
+// With a histogram of BINS bins complete (bins ordered like the keys): finds the
+// bin that holds the `want`-th largest entry.  `bin` receives it, `want_in_bin`
+// the rank inside the bin counted from its top (>= 1), `in_bin` the bin's count.
+// Requires 1 <= want <= total count.  All kRowThreads threads must call it.
+template <int BINS>
+__device__ __forceinline__ void find_rank_bin(const uint32_t* hist, uint64_t* scan_lds, uint32_t* bcast,
+                                              uint32_t want, uint32_t& bin, uint32_t& want_in_bin,
+                                              uint32_t& in_bin)
 {
-    // thread t owns digits 2047-2t and 2046-2t (descending order over threads)
-    const int      top = kSelBins - 1 - 2 * (int)threadIdx.x;
-    const uint32_t h0 = hist[top], h1 = hist[top - 1];
+    constexpr int per = BINS / kRowThreads;       // bins per thread, descending bin order over threads
+    uint32_t h[per];
+    uint32_t s = 0;
+#pragma unroll
+    for (int q = 0; q < per; ++q) {
+        h[q] = hist[BINS - 1 - ((int)threadIdx.x * per + q)];
+        s += h[q];
+    }
     uint64_t total;
-    const uint64_t ex = block_excl_scan64<kRowThreads>((uint64_t)h0 + h1, scan_lds, total);
-    if (ex < remaining && (uint64_t)remaining <= ex + h0 + h1) {
-        if ((uint64_t)remaining <= ex + h0) {
-            bcast[0] = (uint32_t)top;
-            bcast[1] = remaining - (uint32_t)ex;
-            bcast[2] = h0;
-        } else {
-            bcast[0] = (uint32_t)(top - 1);
-            bcast[1] = remaining - (uint32_t)ex - h0;
-            bcast[2] = h1;
+    const uint64_t ex = block_excl_scan64<kRowThreads>(s, scan_lds, total);
+    if (ex < want && (uint64_t)want <= ex + s) {
+        uint64_t acc = ex;
+#pragma unroll
+        for (int q = 0; q < per; ++q) {
+            if (acc < want && (uint64_t)want <= acc + h[q]) {
+                bcast[0] = (uint32_t)(BINS - 1 - ((int)threadIdx.x * per + q));
+                bcast[1] = want - (uint32_t)acc;
+                bcast[2] = h[q];
+            }
+            acc += h[q];
         }
     }
     __syncthreads();
-    prefix |= bcast[0] << sel_shift(pass);
-    known |= sel_dmask(pass) << sel_shift(pass);
-    remaining = bcast[1];
-    in_digit = bcast[2];
+    bin = bcast[0];
+    want_in_bin = bcast[1];
+    in_bin = bcast[2];
     __syncthreads();
 }
 
-// Exact K-th largest of `count` keys delivered by `key_at(i)`, by an MSB-first
-// radix select (11 + 10 + 10 bits) in one workgroup of kRowThreads threads; the
-// keys are re-read in every pass.  Returns the K-th largest key; `take_eq`
-// receives how many keys EQUAL to it belong to the top K (>= 1) and `n_eq` how
-// many keys equal it in all.  Requires 1 <= K <= count.  All threads of the
-// workgroup must call it.
-template <typename KeyAt>
-__device__ __forceinline__ uint32_t block_radix_select_mem(KeyAt key_at, uint64_t count, uint32_t K,
-                                                           uint32_t* hist /*kSelBins*/, uint64_t* scan_lds,
-                                                           uint32_t* bcast /*3*/, uint32_t& take_eq,
-                                                           uint32_t& n_eq)
-{
-    const uint32_t lane = lane_id();
-    uint32_t prefix = 0, known = 0, remaining = K, in_digit = 0;
+// Key sources for the selects below.  each(f) calls f(key, i, valid) the same
+// number of times in every lane of the workgroup (so f may use wave-wide
+// operations); i is the key's position in the source, valid says whether it
+// exists.
+struct KeysInRegs {                     // thread t holds key number q * kRowThreads + t in k[q]
+    const uint32_t (&k)[kKeep];
+    uint32_t count;
+    template <typename F>
+    __device__ __forceinline__ void each(F f) const
+    {
 #pragma unroll
-    for (int pass = 0; pass < 3; ++pass) {
-        for (int b = threadIdx.x; b < kSelBins; b += kRowThreads) hist[b] = 0;
-        __syncthreads();
+        for (int q = 0; q < kKeep; ++q) {
+            if ((uint32_t)q * kRowThreads < count) {              // uniform over the workgroup
+                const uint32_t i = (uint32_t)q * kRowThreads + threadIdx.x;
+                f(k[q], (uint64_t)i, i < count);
+            }
+        }
+    }
+};
+template <typename KeyAt>
+struct KeysInMemory {                   // re-read on every pass
+    KeyAt    key_at;
+    uint64_t count;
+    template <typename F>
+    __device__ __forceinline__ void each(F f) const
+    {
         for (uint64_t base = 0; base < count; base += (uint64_t)kRowThreads * 8) {
             uint32_t k[8];
 #pragma unroll
@@ -441,23 +457,20 @@ __device__ __forceinline__ uint32_t block_radix_select_mem(KeyAt key_at, uint64_
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
                 const uint64_t i = base + (uint64_t)u * kRowThreads + threadIdx.x;
-                tally_digit(hist, (i < count) && ((k[u] & known) == prefix),
-                            (k[u] >> sel_shift(pass)) & sel_dmask(pass), lane);
+                f(k[u], i, i < count);
             }
         }
-        __syncthreads();
-        narrow_by_digit(hist, scan_lds, bcast, pass, prefix, known, remaining, in_digit);
     }
-    take_eq = remaining;
-    n_eq = in_digit;
-    return prefix;
-}
+};
 
-// The same select with the keys held in registers: thread t holds key number
-// q * kRowThreads + t in k[q]; entries at or beyond `count` are ignored.
-__device__ __forceinline__ uint32_t block_radix_select_regs(const uint32_t (&k)[kKeep], uint32_t count,
-                                                            uint32_t K, uint32_t* hist, uint64_t* scan_lds,
-                                                            uint32_t* bcast, uint32_t& take_eq, uint32_t& n_eq)
+// Exact K-th largest of the source's keys by an MSB-first radix select
+// (11 + 10 + 10 bits) in one workgroup of kRowThreads threads.  Returns the K-th
+// largest key; `take_eq` receives how many keys EQUAL to it belong to the top K
+// (>= 1) and `n_eq` how many keys equal it in all.  Requires 1 <= K <= count.
+template <typename Keys>
+__device__ __forceinline__ uint32_t block_radix_select(const Keys& keys, uint32_t K, uint32_t* hist,
+                                                       uint64_t* scan_lds, uint32_t* bcast,
+                                                       uint32_t& take_eq, uint32_t& n_eq)
 {
     const uint32_t lane = lane_id();
     uint32_t prefix = 0, known = 0, remaining = K, in_digit = 0;
@@ -465,16 +478,14 @@ __device__ __forceinline__ uint32_t block_radix_select_regs(const uint32_t (&k)[
     for (int pass = 0; pass < 3; ++pass) {
         for (int b = threadIdx.x; b < kSelBins; b += kRowThreads) hist[b] = 0;
         __syncthreads();
-#pragma unroll
-        for (int q = 0; q < kKeep; ++q) {
-            if ((uint32_t)q * kRowThreads < count) {              // uniform over the workgroup
-                const uint32_t i = (uint32_t)q * kRowThreads + threadIdx.x;
-                tally_digit(hist, (i < count) && ((k[q] & known) == prefix),
-                            (k[q] >> sel_shift(pass)) & sel_dmask(pass), lane);
-            }
-        }
+        keys.each([&](uint32_t k, uint64_t, bool valid) {
+            tally_digit(hist, valid && ((k & known) == prefix), (k >> sel_shift(pass)) & sel_dmask(pass), lane);
+        });
         __syncthreads();
-        narrow_by_digit(hist, scan_lds, bcast, pass, prefix, known, remaining, in_digit);
+        uint32_t digit;
+        find_rank_bin<kSelBins>(hist, scan_lds, bcast, remaining, digit, remaining, in_digit);
+        prefix |= digit << sel_shift(pass);
+        known |= sel_dmask(pass) << sel_shift(pass);
     }
     take_eq = remaining;
     n_eq = in_digit;
@@ -500,11 +511,155 @@ __device__ __forceinline__ bool is_taken(u32x2 c, uint32_t kth, uint32_t tie_cut
     return c.x > kth || (c.x == kth && c.y <= tie_cut);
 }
 
+// LDS of mv_row_select
+struct SelectLds {
+    __attribute__((aligned(16))) uint32_t hist[kKeyBins];   // histograms; then magnitudes of a bin's members
+    __attribute__((aligned(16))) uint32_t ties[kTieCap];    // coordinates of a bin's members / of the ties
+    uint32_t lvl[257];
+    uint32_t bcast[3];
+    uint32_t n_list;
+    uint64_t scan[kRowThreads / kWave + 1];
+};
+
+// The take-th SMALLEST of the n coordinates in lds.ties[0..n): ranked by counting
+// when few, else by a radix select on (0x7FFFFFFF - coordinate).
+__device__ __forceinline__ uint32_t smallest_coordinate(SelectLds& lds, uint32_t n, uint32_t take)
+{
+    if (n <= (uint32_t)kRowThreads) {
+        if (threadIdx.x < 4) lds.ties[n + threadIdx.x] = 0xFFFFFFFFu;   // pad to a multiple of 4, ranked last
+        __syncthreads();
+        if (threadIdx.x < n) {
+            const uint32_t mine = lds.ties[threadIdx.x];
+            const u32x4* tv = reinterpret_cast<const u32x4*>(lds.ties);
+            uint32_t below = 0;
+#pragma unroll 4
+            for (uint32_t j = 0; j < (n + 3) / 4; ++j) {
+                const u32x4 o = tv[j];
+                below += (o.x < mine) + (o.y < mine) + (o.z < mine) + (o.w < mine);
+            }
+            if (below == take - 1) lds.bcast[0] = mine;
+        }
+        __syncthreads();
+        const uint32_t r = lds.bcast[0];
+        __syncthreads();
+        return r;
+    }
+    uint32_t t_eq, n_eq;
+    const uint32_t* ties = lds.ties;
+    auto at = [ties](uint64_t i) { return kAbsMask - ties[i]; };
+    const KeysInMemory<decltype(at)> src{at, n};
+    return kAbsMask - block_radix_select(src, take, lds.hist, lds.scan, lds.bcast, t_eq, n_eq);
+}
+
+// K-th largest magnitude of a row's candidate list and the tie cut.  `keys`
+// delivers the candidates' magnitudes (position i = position in the list crow).
+// Returns through kth / tie_cut; `path` = 0 when the fine histogram sufficed,
+// 2 when the radix select over all candidates had to run.
+template <typename Keys>
+__device__ __forceinline__ void select_among_candidates(const Keys& keys, const u32x2* __restrict__ crow,
+                                                        uint32_t C, uint32_t K, uint32_t tau, SelectLds& lds,
+                                                        uint32_t& kth, uint32_t& tie_cut, uint32_t& path)
+{
+    const uint32_t lane = lane_id(), t = threadIdx.x;
+    uint32_t take_eq = 0, n_eq = 0;
+    bool have_kth = false;
+    path = 0;
+    if (t == 0) lds.n_list = 0;                   // ordered by the first barrier below
+    if (tau != 0) {
+        // All candidates are >= tau and most lie within an octave of it: one
+        // histogram of (key - tau) in 2048 bins finds the bin of the K-th largest.
+        for (int b = t; b < kFineBins; b += kRowThreads) lds.hist[b] = 0;
+        __syncthreads();
+        keys.each([&](uint32_t k, uint64_t, bool valid) { tally_digit(lds.hist, valid, fine_bin(k, tau), lane); });
+        __syncthreads();
+        uint32_t bin, want, in_bin;
+        find_rank_bin<kFineBins>(lds.hist, lds.scan, lds.bcast, K, bin, want, in_bin);
+        if (in_bin <= (uint32_t)kBinCap) {        // uniform
+            // few candidates in that bin: collect them (magnitude in hist[], coordinate
+            // in ties[]) and rank them by brute force under (magnitude desc, coordinate
+            // asc); the one with exactly want-1 others ahead is the last of the top K
+            keys.each([&](uint32_t k, uint64_t i, bool valid) {
+                if (valid && fine_bin(k, tau) == bin) {
+                    const uint32_t p = atomicAdd(&lds.n_list, 1u);
+                    lds.hist[p] = k;
+                    lds.ties[p] = crow[i].y;
+                }
+            });
+            if (t < 4) {                          // pad to a multiple of 4 with entries ranked last
+                lds.hist[in_bin + t] = 0;
+                lds.ties[in_bin + t] = 0xFFFFFFFFu;
+            }
+            __syncthreads();
+            if (t < in_bin) {
+                const uint32_t mk = lds.hist[t], mi = lds.ties[t];
+                const u32x4* hk = reinterpret_cast<const u32x4*>(lds.hist);
+                const u32x4* hi = reinterpret_cast<const u32x4*>(lds.ties);
+                uint32_t ahead = 0;
+#pragma unroll 4
+                for (uint32_t j = 0; j < (in_bin + 3) / 4; ++j) {
+                    const u32x4 ok = hk[j], oi = hi[j];
+                    ahead += (ok.x > mk) || (ok.x == mk && oi.x < mi);
+                    ahead += (ok.y > mk) || (ok.y == mk && oi.y < mi);
+                    ahead += (ok.z > mk) || (ok.z == mk && oi.z < mi);
+                    ahead += (ok.w > mk) || (ok.w == mk && oi.w < mi);
+                }
+                if (ahead == want - 1) {
+                    lds.bcast[0] = mk;
+                    lds.bcast[1] = mi;
+                }
+            }
+            __syncthreads();
+            kth = lds.bcast[0];
+            tie_cut = lds.bcast[1];
+            return;
+        }
+        if (bin < (uint32_t)(kFineBins - 1)) {
+            // a crowded bin (many equal magnitudes): it spans exactly 4096 key values,
+            // so a second histogram over the exact keys inside it finds the K-th largest
+            const uint32_t bin_lo = tau + (bin << kFineShift);
+            for (int b = t; b < kKeyBins; b += kRowThreads) lds.hist[b] = 0;
+            __syncthreads();
+            keys.each([&](uint32_t k, uint64_t, bool valid) {
+                tally_digit(lds.hist, valid && fine_bin(k, tau) == bin, (k - bin_lo) & (uint32_t)(kKeyBins - 1), lane);
+            });
+            __syncthreads();
+            uint32_t sub;
+            find_rank_bin<kKeyBins>(lds.hist, lds.scan, lds.bcast, want, sub, take_eq, n_eq);
+            kth = bin_lo + sub;
+            have_kth = true;
+        }
+    }
+    if (!have_kth) {
+        path = 2;
+        kth = block_radix_select(keys, K, lds.hist, lds.scan, lds.bcast, take_eq, n_eq);
+    }
+    // ties with the K-th magnitude: all taken, or only the take_eq lowest coordinates
+    tie_cut = 0xFFFFFFFFu;
+    if (take_eq < n_eq) {                         // uniform
+        if (n_eq <= (uint32_t)kTieCap) {
+            keys.each([&](uint32_t k, uint64_t i, bool valid) {
+                if (valid && k == kth) lds.ties[atomicAdd(&lds.n_list, 1u)] = crow[i].y;
+            });
+            __syncthreads();
+            tie_cut = smallest_coordinate(lds, n_eq, take_eq);
+        } else {
+            // more ties than the LDS list holds: select over the whole candidate list in
+            // memory, entries that are not ties mapped below every tie
+            uint32_t t_eq, t_n;
+            auto at = [crow, kth](uint64_t i) {
+                const u32x2 c = crow[i];
+                return c.x == kth ? kAbsMask - c.y : 0u;
+            };
+            const KeysInMemory<decltype(at)> src{at, C};
+            tie_cut = kAbsMask - block_radix_select(src, take_eq, lds.hist, lds.scan, lds.bcast, t_eq, t_n);
+        }
+    }
+}
+
 // One workgroup per row.
-// Usual case: radix select over the row's candidate list gives the K-th largest
-// magnitude kth[row]; if only some of the candidates tied with it belong to the
-// top K, a second select over the ties' coordinates gives tie_cut[row], the
-// largest tied coordinate taken (0xFFFFFFFF: all ties taken).
+// Usual case: an exact select over the row's candidate list gives the K-th
+// largest magnitude kth[row] and tie_cut[row], the largest coordinate taken
+// among the candidates tied with it (0xFFFFFFFF: all ties taken).
 // If the candidate count is < K or overflowed the list (for instance a row of
 // equal magnitudes), the row is instead selected exactly from memory (e already
 // holds a = g + e), and its vote is emitted and cast here; slow_flag[row] = 1
@@ -517,22 +672,14 @@ __global__ __launch_bounds__(kRowThreads) void mv_row_select(
     uint32_t* __restrict__ worker_idx, uint32_t* __restrict__ votes32,
     uint32_t* __restrict__ cnt_ge, uint32_t* __restrict__ slow_flag)
 {
-    __shared__ __attribute__((aligned(16))) uint32_t hist[kSelBins];
-    __shared__ __attribute__((aligned(16))) uint32_t ties[kTieCap];
-    __shared__ uint32_t lvl[257];
-    __shared__ uint32_t bcast[3];
-    __shared__ uint32_t n_ties;
-    __shared__ uint64_t scan_lds[kRowThreads / kWave + 1];
-
+    __shared__ SelectLds lds;
     const uint32_t row = blockIdx.x, t = threadIdx.x;
     const uint32_t C = row_count[row];
 
     if (C >= K && C <= cap) {
         const u32x2* crow = cand + (size_t)row * cap;
         const uint32_t tau = tau_bits[row];
-        const uint32_t lane = lane_id();
-        uint32_t kth, take_eq, n_eq;
-        if (t == 0) n_ties = 0;                   // ordered by the first barrier below
+        uint32_t kth, tie_cut, path;
         if (C <= (uint32_t)kKeep * kRowThreads) {
             // entries past C are clamped to the last candidate and ignored later
             uint32_t k[kKeep];
@@ -542,116 +689,30 @@ __global__ __launch_bounds__(kRowThreads) void mv_row_select(
                 k[q] = crow[min((uint32_t)q * kRowThreads + t, last)].x;
                 if ((q & 7) == 7) __builtin_amdgcn_sched_barrier(0);   // keep address arithmetic from piling up
             }
-            if (tau != 0) {
-                // ---- short cut.  All candidates are >= tau and most lie within an
-                // octave of it: one histogram of (key - tau) in 2048 bins finds the bin
-                // that holds the K-th largest; if that bin holds few candidates they
-                // are ranked by brute force under (magnitude desc, coordinate asc).
-                for (int b = t; b < kFineBins; b += kRowThreads) hist[b] = 0;
-                __syncthreads();
-#pragma unroll
-                for (int q = 0; q < kKeep; ++q) {
-                    if ((uint32_t)q * kRowThreads < C) {              // uniform over the workgroup
-                        const uint32_t i = (uint32_t)q * kRowThreads + t;
-                        tally_digit(hist, i < C, fine_bin(k[q], tau), lane);
-                    }
-                }
-                __syncthreads();
-                uint32_t bin = 0, known = 0, want = K, in_bin = 0;
-                narrow_by_digit(hist, scan_lds, bcast, 2, bin, known, want, in_bin);   // pass 2: shift 0
-                if (in_bin <= (uint32_t)kBinCap) {        // uniform
-                    // collect the bin's candidates: magnitude in hist[], coordinate in ties[]
-#pragma unroll
-                    for (int q = 0; q < kKeep; ++q) {
-                        const uint32_t i = (uint32_t)q * kRowThreads + t;
-                        if (i < C && fine_bin(k[q], tau) == bin) {
-                            const uint32_t p = atomicAdd(&n_ties, 1u);
-                            hist[p] = k[q];
-                            ties[p] = crow[i].y;
-                        }
-                    }
-                    if (t < 4) {                          // pad to a multiple of 4 with entries ranked last
-                        hist[in_bin + t] = 0;
-                        ties[in_bin + t] = 0xFFFFFFFFu;
-                    }
-                    __syncthreads();
-                    // the candidate with exactly want-1 others ahead of it is the last of the top K
-                    if (t < in_bin) {
-                        const uint32_t mk = hist[t], mi = ties[t];
-                        uint32_t ahead = 0;
-                        const u32x4* hk = reinterpret_cast<const u32x4*>(hist);
-                        const u32x4* hi = reinterpret_cast<const u32x4*>(ties);
-#pragma unroll 4
-                        for (uint32_t j = 0; j < (in_bin + 3) / 4; ++j) {
-                            const u32x4 ok = hk[j], oi = hi[j];
-                            ahead += (ok.x > mk) || (ok.x == mk && oi.x < mi);
-                            ahead += (ok.y > mk) || (ok.y == mk && oi.y < mi);
-                            ahead += (ok.z > mk) || (ok.z == mk && oi.z < mi);
-                            ahead += (ok.w > mk) || (ok.w == mk && oi.w < mi);
-                        }
-                        if (ahead == want - 1) {
-                            kth_out[row] = mk;
-                            tie_cut_out[row] = mi;
-                        }
-                    }
-                    return;
-                }
-            }
-            if (t == 0) slow_flag[row] = 2;       // diagnostic only: the short cut did not apply
-            kth = block_radix_select_regs(k, C, K, hist, scan_lds, bcast, take_eq, n_eq);
-            if (take_eq < n_eq && n_eq <= (uint32_t)kTieCap) {
-#pragma unroll
-                for (int q = 0; q < kKeep; ++q) {
-                    const uint32_t i = (uint32_t)q * kRowThreads + t;
-                    if (i < C && k[q] == kth) ties[atomicAdd(&n_ties, 1u)] = crow[i].y;
-                }
-            }
+            const KeysInRegs src{k, C};
+            select_among_candidates(src, crow, C, K, tau, lds, kth, tie_cut, path);
         } else {
-            if (t == 0) slow_flag[row] = 2;
-            kth = block_radix_select_mem([&](uint64_t i) { return crow[i].x; }, C, K, hist, scan_lds,
-                                         bcast, take_eq, n_eq);
-            if (take_eq < n_eq && n_eq <= (uint32_t)kTieCap) {
-                for (uint32_t i = t; i < C; i += kRowThreads) {
-                    const u32x2 c = crow[i];
-                    if (c.x == kth) ties[atomicAdd(&n_ties, 1u)] = c.y;
-                }
-            }
-        }
-        uint32_t tie_cut = 0xFFFFFFFFu;
-        if (take_eq < n_eq) {                     // uniform: only the lowest take_eq tied coordinates are taken
-            // the take_eq-th SMALLEST coordinate among the ties = the take_eq-th
-            // largest of (0x7FFFFFFF - coordinate); entries that are not ties map to 0
-            uint32_t dummy_take, dummy_eq, kq;
-            __syncthreads();
-            if (n_eq <= (uint32_t)kTieCap) {
-                kq = block_radix_select_mem([&](uint64_t i) { return kAbsMask - ties[i]; }, n_eq, take_eq,
-                                            hist, scan_lds, bcast, dummy_take, dummy_eq);
-            } else {
-                kq = block_radix_select_mem(
-                    [&](uint64_t i) {
-                        const u32x2 c = crow[i];
-                        return c.x == kth ? kAbsMask - c.y : 0u;
-                    },
-                    C, take_eq, hist, scan_lds, bcast, dummy_take, dummy_eq);
-            }
-            tie_cut = kAbsMask - kq;
+            auto at = [crow](uint64_t i) { return crow[i].x; };
+            const KeysInMemory<decltype(at)> src{at, C};
+            select_among_candidates(src, crow, C, K, tau, lds, kth, tie_cut, path);
         }
         if (t == 0) {
             kth_out[row] = kth;
             tie_cut_out[row] = tie_cut;
+            if (path) slow_flag[row] = path;      // diagnostic only
         }
         return;
     }
 
     // ---- exact path from memory
     if (t == 0) slow_flag[row] = 1;
-    for (int i = t; i < 257; i += kRowThreads) lvl[i] = 0;   // ordered by the select's first barrier
+    for (int i = t; i < 257; i += kRowThreads) lds.lvl[i] = 0;   // ordered by the select's first barrier
     uint32_t* out = worker_idx ? worker_idx + (size_t)row * K : nullptr;
     const float* arow = e + (int64_t)row * ld_e;
     uint32_t take_eq, n_eq;
-    const uint32_t kth = block_radix_select_mem(
-        [&](uint64_t i) { return __float_as_uint(arow[i]) & kAbsMask; }, (uint64_t)d, K, hist, scan_lds,
-        bcast, take_eq, n_eq);
+    auto at = [arow](uint64_t i) { return __float_as_uint(arow[i]) & kAbsMask; };
+    const KeysInMemory<decltype(at)> src{at, (uint64_t)d};
+    const uint32_t kth = block_radix_select(src, K, lds.hist, lds.scan, lds.bcast, take_eq, n_eq);
     uint32_t gt_before = 0, eq_before = 0;
     for (int64_t j0 = 0; j0 < d; j0 += (int64_t)kRowThreads * 4) {
         const int64_t j = j0 + (int64_t)t * 4;
@@ -665,7 +726,7 @@ __global__ __launch_bounds__(kRowThreads) void mv_row_select(
             eq += (valid && k[c] == kth);
         }
         uint64_t total;
-        const uint64_t ex = block_excl_scan64<kRowThreads>(pack2(gt, eq), scan_lds, total);
+        const uint64_t ex = block_excl_scan64<kRowThreads>(pack2(gt, eq), lds.scan, total);
         uint32_t g0 = gt_before + (uint32_t)(ex >> 32), e0 = eq_before + (uint32_t)ex;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
@@ -674,7 +735,7 @@ __global__ __launch_bounds__(kRowThreads) void mv_row_select(
                 if (is_gt || (is_eq && e0 < take_eq)) {
                     const uint32_t pos = g0 + min(e0, take_eq);
                     if (out && pos < K) out[pos] = (uint32_t)(j + c);
-                    cast_vote(votes32, (uint32_t)(j + c), lvl);
+                    cast_vote(votes32, (uint32_t)(j + c), lds.lvl);
                 }
                 g0 += is_gt;
                 e0 += is_eq;
@@ -682,11 +743,11 @@ __global__ __launch_bounds__(kRowThreads) void mv_row_select(
         }
         gt_before += (uint32_t)(total >> 32);
         eq_before += (uint32_t)total;
-        __syncthreads();   // scan_lds is reused by the next round
+        __syncthreads();   // lds.scan is reused by the next round
     }
     __syncthreads();
     for (int i = t; i < 256; i += kRowThreads) {
-        const uint32_t c = lvl[i];
+        const uint32_t c = lds.lvl[i];
         if (c) atomicAdd(&cnt_ge[(size_t)row * 256 + i], c);
     }
 }

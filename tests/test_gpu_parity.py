@@ -240,3 +240,56 @@ def test_argument_errors_leave_error_buffer_untouched():
         assert L.mv_end(ctx) == B.MV_ERR_STATE
         B.mv_release(ctx)
         gs.ctx = 0
+
+
+def _levels_row(rng, d, groups, noise=1e-3):
+    """A row of small noise with groups of (count, lo, hi) magnitudes planted at random places."""
+    row = (rng.standard_normal(d) * noise).astype(np.float32)
+    pos = rng.permutation(d)
+    at = 0
+    for count, lo, hi in groups:
+        vals = rng.uniform(lo, hi, size=count).astype(np.float32) if hi > lo else np.full(count, lo, np.float32)
+        row[pos[at:at + count]] = vals * rng.choice(np.array([-1.0, 1.0], np.float32), size=count)
+        at += count
+    return row
+
+
+@pytest.mark.parametrize("case", ["ties_in_lds_by_counting", "ties_in_lds_by_radix", "ties_beyond_lds",
+                                  "kth_far_above_threshold", "more_candidates_than_registers"])
+def test_every_route_of_the_row_select(oracle, case):
+    """Rows built to drive mv_row_select down each of its routes: crowded
+    histogram bins (equal magnitudes), tie groups small / large / larger than the
+    LDS list, a K-th magnitude more than an octave above the estimate, and a
+    candidate list longer than the register file holds."""
+    rng = np.random.default_rng(hash(case) % 1000)
+    N, d, K = 3, 300007, 3000
+    if case == "ties_in_lds_by_counting":
+        groups = [(2600, 2.0, 3.0), (900, 1.0, 1.0)]            # 900 ties, 400 taken
+    elif case == "ties_in_lds_by_radix":
+        groups = [(2000, 2.0, 3.0), (5000, 1.0, 1.0)]           # 5000 ties, 1000 taken
+    elif case == "ties_beyond_lds":
+        groups = [(2000, 2.0, 3.0), (20000, 1.0, 1.0)]          # 20000 ties, 1000 taken
+    elif case == "kth_far_above_threshold":
+        groups = [(3500, 8.0, 16.0), (2600, 1.0, 1.1)]          # > K coordinates beyond 2 tau
+    else:
+        N, d, K = 2, 400003, 20000                              # about 2K = 40000 candidates per row
+        groups = []
+    say("select route %s N=%d d=%d K=%d" % (case, N, d, K))
+    if groups:
+        g = np.stack([_levels_row(rng, d, groups) for _ in range(N)])
+    else:
+        g = rng.standard_normal((N, d)).astype(np.float32)
+    e = np.zeros_like(g)
+    with GpuStepper(N, d, K) as gs:
+        gs.set_error(e)
+        gs.set_grads(g)
+        gs.step()
+        got = gs.fetch()
+        cand, _, path = gs.row_stats()
+    say("  candidates %s path %s" % (cand, path))
+    assert_matches_oracle(got, oracle.vote_step(g, e, K), case)
+    assert all(p != 1 for p in path), "these rows are meant for the candidate-list routes"
+    if case == "kth_far_above_threshold":
+        assert all(p == 2 for p in path)
+    if case == "more_candidates_than_registers":
+        assert min(cand) > 32768
