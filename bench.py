@@ -61,6 +61,8 @@ def main():
     ap.add_argument("--workload", default="C4", choices=["C1", "C2", "C3", "C4", "C5"])
     ap.add_argument("--grad-sets", type=int, default=2, help="distinct gradient matrices cycled over")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-worker-idx", action="store_true",
+                    help="do not request the per-worker sorted vote lists (optional output)")
     ap.add_argument("--profile-level", type=int, default=1, choices=[0, 1, 2],
                     help="HIP events inside the timed region: 1 = dominant kernel only, 2 = every kernel")
     ap.add_argument("--breakdown", action="store_true",
@@ -103,7 +105,7 @@ def main():
     log("generated %d gradient sets of %s (N=%d d=%d K=%d) in %.1f s" % (len(g_dev), w.name, N, d, K, time.time() - t0))
 
     e_dev = torch.zeros((N, ld_e), dtype=torch.float32, device=dev)
-    widx = torch.zeros((N, K), dtype=torch.int32, device=dev)
+    widx = None if args.no_worker_idx else torch.zeros((N, K), dtype=torch.int32, device=dev)
     votes = torch.zeros(d, dtype=torch.uint8, device=dev)
     mask = torch.zeros(K, dtype=torch.int32, device=dev)
     agg = torch.zeros(K, dtype=torch.float32, device=dev)
@@ -223,7 +225,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": "%s: N=%d d=%d K=%d grads=%s, %s, error feedback carried" %
                                (w.name, N, d, K, w.grad_dtype, w.kind),
-                   "N": N, "d": d, "K": K, "grad_sets_cycled": len(g_dev)},
+                   "N": N, "d": d, "K": K, "grad_sets_cycled": len(g_dev),
+                   "outputs": "mask_idx, agg_vals, votes" + ("" if args.no_worker_idx else ", worker_idx")},
         "step_hbm_frac_algorithmic": round(step_frac, 4),
         "copy_probe_GBs": round(copy_gbs, 1),
         "roofline": roofline,

@@ -47,7 +47,7 @@ struct Plan {
     // scratch offsets (bytes)
     size_t off_hist, off_tau, off_rowcnt, off_slow, off_kth, off_tiecut, off_cntge, off_seg, off_segsel,
         off_segpre,
-        off_blktotal, off_cand, off_votes, off_blockcnt;
+        off_blktotal, off_votethr, off_cand, off_votes, off_blockcnt;
     size_t total_bytes;
 };
 
@@ -113,6 +113,7 @@ Plan make_plan(const mv_config* c)
     p.off_kth = off;      off += align_up((size_t)p.N * 4);
     p.off_tiecut = off;   off += align_up((size_t)p.N * 4);
     p.off_cntge = off;    off += align_up((size_t)p.N * 256 * 4);
+    p.off_votethr = off;  off += align_up(2 * 4);
     p.off_seg = off;      off += align_up((size_t)p.N * p.nseg * 8);
     p.off_segsel = off;   off += align_up((size_t)p.N * p.nseg * 4);
     p.off_segpre = off;   off += align_up((size_t)p.N * p.nseg * 4);
@@ -249,6 +250,7 @@ mv_status mv_vote_step(mv_ctx* c, const void* grads, int64_t ld_g, float* err, i
     uint32_t* segsel = ws_ptr<uint32_t>(c, p.off_segsel);
     uint32_t* segpre = ws_ptr<uint32_t>(c, p.off_segpre);
     uint32_t* blktotal = ws_ptr<uint32_t>(c, p.off_blktotal);
+    uint32_t* votethr = ws_ptr<uint32_t>(c, p.off_votethr);
     mvk::u32x2* seg = ws_ptr<mvk::u32x2>(c, p.off_seg);
     mvk::u32x2* cand = ws_ptr<mvk::u32x2>(c, p.off_cand);
     uint32_t* votes32 = ws_ptr<uint32_t>(c, p.off_votes);
@@ -321,11 +323,11 @@ mv_status mv_vote_step(mv_ctx* c, const void* grads, int64_t ld_g, float* err, i
     before(KID_MASK_COUNT);
     hipLaunchKernelGGL(mvk::mv_mask_count, dim3(p.n_vote_blocks + (sorted ? p.N * p.scan_blocks : 0)),
                        dim3(mvk::kVoteThreads), 0, st, votes32, p.d, p.N, p.K, cntge, blockcnt, votes,
-                       p.n_vote_blocks, p.scan_blocks, p.nseg, slow, segsel, segpre, blktotal);
+                       p.n_vote_blocks, p.scan_blocks, p.nseg, slow, segsel, segpre, blktotal, votethr);
     after(KID_MASK_COUNT);
     before(KID_MASK_EMIT);
     hipLaunchKernelGGL(mvk::mv_mask_emit, dim3(p.n_vote_blocks + (sorted ? p.N * p.emit_blocks : 0)),
-                       dim3(mvk::kVoteThreads), 0, st, votes32, p.d, p.N, p.K, cntge, blockcnt, mask_idx,
+                       dim3(mvk::kVoteThreads), 0, st, votes32, p.d, p.K, votethr, blockcnt, mask_idx,
                        p.n_vote_blocks, p.emit_blocks, cand, p.cap, rowcnt, seg, p.nseg, segpre, blktotal, p.scan_blocks,
                        kth, tiecut, slow,
                        worker_idx);

@@ -53,6 +53,7 @@ constexpr int      kRowThreads     = 1024;   // mv_pick_threshold / mv_row_finis
 constexpr int      kVoteBlock      = 16384;  // coordinates per workgroup in mv_mask_count / mv_mask_emit
 constexpr int      kVoteThreads    = 256;
 constexpr int      kGatherThreads  = 256;
+constexpr int      kMaxScanBlocks  = 2048;   // blocks of 1024 segments in a row of up to 2^31 coordinates
 constexpr uint32_t kAbsMask        = 0x7FFFFFFFu;
 constexpr int      kFineBins       = 2048;   // mv_row_select: histogram of the candidates' magnitudes above tau
 constexpr int      kFineShift      = 12;     // 2048 bins of 4096 bit patterns = one octave above tau
@@ -819,12 +820,23 @@ __device__ __forceinline__ void vote_threshold(const uint32_t* __restrict__ cnt_
                                                uint32_t K, uint32_t* lds_lvl /*256*/, uint32_t* lds2,
                                                uint32_t& vstar, uint32_t& take_eq)
 {
-    // cnt_ge holds one set of 256 level counters per worker row; thread v sums level v
-    for (uint32_t v = threadIdx.x; v < 256; v += blockDim.x) {
-        uint32_t sum = 0;
-        if (v >= 1 && v <= N)
-            for (uint32_t n = 0; n < N; ++n) sum += cnt_ge[(size_t)n * 256 + v];
-        lds_lvl[v] = sum;
+    // cnt_ge holds one set of 256 level counters per worker row; add the rows up
+    // (levels 1..N matter), all loads of a thread in flight together
+    for (uint32_t v = threadIdx.x; v < 256; v += blockDim.x) lds_lvl[v] = 0;
+    __syncthreads();
+    const uint32_t per_row = N + 1, n_vals = N * per_row;
+    for (uint32_t i0 = threadIdx.x; i0 < n_vals; i0 += blockDim.x * 4) {
+        uint32_t c[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint32_t i = i0 + u * blockDim.x;
+            c[u] = (i < n_vals) ? cnt_ge[(size_t)(i / per_row) * 256 + (i % per_row)] : 0u;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint32_t i = i0 + u * blockDim.x;
+            if (i < n_vals && c[u]) atomicAdd(&lds_lvl[i % per_row], c[u]);
+        }
     }
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -880,7 +892,8 @@ __global__ __launch_bounds__(kVoteThreads) void mv_mask_count(const uint32_t* __
                                                               const uint32_t* __restrict__ slow_flag,
                                                               const uint32_t* __restrict__ seg_sel,
                                                               uint32_t* __restrict__ seg_pre,
-                                                              uint32_t* __restrict__ blk_total)
+                                                              uint32_t* __restrict__ blk_total,
+                                                              uint32_t* __restrict__ vote_thr)
 {
     __shared__ uint32_t lds2[2];
     __shared__ uint32_t lds_lvl[256];
@@ -893,16 +906,24 @@ __global__ __launch_bounds__(kVoteThreads) void mv_mask_count(const uint32_t* __
                        blk_total + (size_t)row * scan_blocks, scan_lds);
         return;
     }
+    // the block's vote words first: their latency overlaps the threshold's loads
+    constexpr int kIt = kVoteBlock / (kVoteThreads * 16);
+    const int64_t base = (int64_t)blockIdx.x * kVoteBlock;
+    u32x4 w[kIt];
+#pragma unroll
+    for (int it = 0; it < kIt; ++it) {
+        const int64_t j = base + ((int64_t)it * kVoteThreads + threadIdx.x) * 16;
+        const u32x4 z = {0u, 0u, 0u, 0u};
+        w[it] = (j < d) ? *reinterpret_cast<const u32x4*>(votes32 + (j >> 2)) : z;   // padded to 16 bytes with zeros
+    }
     uint32_t vstar, take_eq;
     vote_threshold(cnt_ge, N, K, lds_lvl, lds2, vstar, take_eq);
-    const int64_t base = (int64_t)blockIdx.x * kVoteBlock;
     uint32_t gt = 0, eq = 0;
 #pragma unroll
-    for (int it = 0; it < kVoteBlock / (kVoteThreads * 16); ++it) {
+    for (int it = 0; it < kIt; ++it) {
         const int64_t j = base + ((int64_t)it * kVoteThreads + threadIdx.x) * 16;
-        if (j < d) {   // the vote buffer is padded to 16 bytes with zeros
-            const u32x4 w = *reinterpret_cast<const u32x4*>(votes32 + (j >> 2));
-            const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+        if (j < d) {
+            const uint32_t ww[4] = {w[it].x, w[it].y, w[it].z, w[it].w};
 #pragma unroll
             for (int q = 0; q < 4; ++q)
 #pragma unroll
@@ -913,7 +934,7 @@ __global__ __launch_bounds__(kVoteThreads) void mv_mask_count(const uint32_t* __
                 }
             if (votes_out) {
                 if (j + 16 <= d && ((reinterpret_cast<uintptr_t>(votes_out) & 15) == 0)) {
-                    *reinterpret_cast<u32x4*>(votes_out + j) = w;
+                    *reinterpret_cast<u32x4*>(votes_out + j) = w[it];
                 } else {
                     for (int q = 0; q < 16; ++q)
                         if (j + q < d) votes_out[j + q] = (uint8_t)((ww[q >> 2] >> (8 * (q & 3))) & 255u);
@@ -928,6 +949,10 @@ __global__ __launch_bounds__(kVoteThreads) void mv_mask_count(const uint32_t* __
         r.x = (uint32_t)(total >> 32);
         r.y = (uint32_t)total;
         block_cnt[blockIdx.x] = r;
+        if (blockIdx.x == 0) {                   // the threshold, for mv_mask_emit
+            vote_thr[0] = vstar;
+            vote_thr[1] = take_eq;
+        }
     }
 }
 
@@ -941,18 +966,69 @@ __device__ __forceinline__ void row_emit_block(const u32x2* __restrict__ crow, u
                                                const uint32_t* __restrict__ prow,
                                                const uint32_t* __restrict__ blk_total, uint32_t scan_blocks,
                                                uint32_t K, uint32_t kth, uint32_t tie_cut, uint32_t blk,
-                                               uint32_t nblk, uint32_t* __restrict__ out)
+                                               uint32_t nblk, uint32_t* __restrict__ out,
+                                               uint32_t* blk_pre /*LDS, kMaxScanBlocks*/, uint64_t* scan_lds)
 {
     if ((uint64_t)blk * kVoteThreads >= C) return;           // whole workgroup
-    for (uint64_t i = (uint64_t)blk * kVoteThreads + threadIdx.x; i < C; i += (uint64_t)nblk * kVoteThreads) {
-        const u32x2 c = crow[i];
-        if (!is_taken(c, kth, tie_cut)) continue;
-        const uint32_t s = c.y / kSeg;
-        uint32_t pos = prow[s];
-        const uint32_t run_start = srow[s].x;
-        for (uint32_t b = 0; b < s / 1024u; ++b) pos += blk_total[b];
-        for (uint32_t j = run_start; j < (uint32_t)i; ++j) pos += is_taken(crow[j], kth, tie_cut) ? 1u : 0u;
-        if (pos < K) out[pos] = c.y;
+    // exclusive prefix of the blocks' totals, once per workgroup
+    {
+        constexpr int per = kMaxScanBlocks / kVoteThreads;
+        uint32_t v[per];
+        uint32_t sum = 0;
+#pragma unroll
+        for (int q = 0; q < per; ++q) {
+            const uint32_t b = threadIdx.x * per + q;
+            v[q] = (b < scan_blocks) ? blk_total[b] : 0u;
+            sum += v[q];
+        }
+        uint64_t total;
+        uint64_t ex = block_excl_scan64<kVoteThreads>(sum, scan_lds, total);
+#pragma unroll
+        for (int q = 0; q < per; ++q) {
+            blk_pre[threadIdx.x * per + q] = (uint32_t)ex;
+            ex += v[q];
+        }
+        __syncthreads();
+    }
+    // Lanes of a wavefront hold consecutive list entries, so the entries of one run
+    // sit in neighbouring lanes: the rank inside the run comes from a ballot; only
+    // the part of the first lane's run that lies before the wavefront is counted
+    // from memory, by the whole wavefront together.
+    const uint32_t lane = lane_id();
+    for (uint64_t i0 = (uint64_t)blk * kVoteThreads; i0 < C; i0 += (uint64_t)nblk * kVoteThreads) {
+        const uint64_t i = i0 + threadIdx.x;
+        const uint64_t wave_first = i - lane;
+        u32x2 c = {0u, 0xFFFFFFFFu};
+        bool taken = false;
+        if (i < C) {
+            c = crow[i];
+            taken = is_taken(c, kth, tie_cut);
+        }
+        const uint32_t sg = c.y / kSeg;                       // 0x3FFFFF for lanes past the end
+        const uint32_t prev = __shfl_up(sg, 1, kWave);
+        const uint64_t heads = __ballot(lane == 0 || sg != prev);
+        const uint64_t tk = __ballot(taken);
+        if (tk == 0ull) continue;                             // wave-uniform
+        const uint64_t upto = (lane == 63) ? ~0ull : ((2ull << lane) - 1);      // lanes 0..lane
+        const uint32_t head_lane = 63u - (uint32_t)__clzll((long long)(heads & upto));
+        const uint64_t in_run_before = ((1ull << lane) - 1) & ~((1ull << head_lane) - 1);
+        uint32_t rank = (uint32_t)__popcll(tk & in_run_before);
+        // the run of lane 0 may have started before this wavefront
+        const uint32_t sg0 = __shfl(sg, 0, kWave);
+        uint32_t carry = 0;
+        if (wave_first < C) {                                 // wave-uniform
+            const uint32_t run0 = srow[sg0].x;
+            for (uint64_t j0 = run0; j0 < wave_first; j0 += kWave) {
+                const uint64_t j = j0 + lane;
+                const bool tj = (j < wave_first) && is_taken(crow[j], kth, tie_cut);
+                carry += (uint32_t)__popcll(__ballot(tj));
+            }
+        }
+        if (head_lane == 0) rank += carry;
+        if (taken) {
+            const uint32_t pos = prow[sg] + blk_pre[sg / 1024u] + rank;
+            if (pos < K) out[pos] = c.y;
+        }
     }
 }
 
@@ -960,8 +1036,8 @@ __device__ __forceinline__ void row_emit_block(const u32x2* __restrict__ crow, u
 // vote words for the next step.  Workgroups beyond (only launched when the
 // sorted vote lists are wanted): write row (b / emit_blocks)'s vote list.
 __global__ __launch_bounds__(kVoteThreads) void mv_mask_emit(uint32_t* __restrict__ votes32,
-                                                             int64_t d, uint32_t N, uint32_t K,
-                                                             const uint32_t* __restrict__ cnt_ge,
+                                                             int64_t d, uint32_t K,
+                                                             const uint32_t* __restrict__ vote_thr,
                                                              const u32x2* __restrict__ block_cnt,
                                                              uint32_t* __restrict__ mask_idx,
                                                              uint32_t n_vote_blocks, uint32_t emit_blocks,
@@ -976,8 +1052,7 @@ __global__ __launch_bounds__(kVoteThreads) void mv_mask_emit(uint32_t* __restric
                                                              const uint32_t* __restrict__ slow_flag,
                                                              uint32_t* __restrict__ worker_idx)
 {
-    __shared__ uint32_t lds2[2];
-    __shared__ uint32_t lds_lvl[256];
+    __shared__ uint32_t blk_pre[kMaxScanBlocks];
     __shared__ uint64_t scan_lds[kVoteThreads / kWave + 1];
     if (blockIdx.x >= n_vote_blocks) {
         const uint32_t b = blockIdx.x - n_vote_blocks;
@@ -986,11 +1061,26 @@ __global__ __launch_bounds__(kVoteThreads) void mv_mask_emit(uint32_t* __restric
         row_emit_block(cand + (size_t)row * cap, row_count[row], seg + (size_t)row * nseg,
                        seg_pre + (size_t)row * nseg, blk_total + (size_t)row * scan_blocks, scan_blocks, K,
                        kth_in[row], tie_cut_in[row], b % emit_blocks, emit_blocks,
-                       worker_idx + (size_t)row * K);
+                       worker_idx + (size_t)row * K, blk_pre, scan_lds);
         return;
     }
-    uint32_t vstar, take_eq;
-    vote_threshold(cnt_ge, N, K, lds_lvl, lds2, vstar, take_eq);
+    // the block's vote words first (cleared behind for the next step): their latency
+    // overlaps the loads of the prefix below
+    constexpr int kIt = kVoteBlock / (kVoteThreads * 16);
+    const int64_t base = (int64_t)blockIdx.x * kVoteBlock;
+    u32x4 w[kIt];
+#pragma unroll
+    for (int it = 0; it < kIt; ++it) {
+        const int64_t j = base + ((int64_t)it * kVoteThreads + threadIdx.x) * 16;
+        const u32x4 z = {0u, 0u, 0u, 0u};
+        w[it] = z;
+        if (j < d) {
+            u32x4* p = reinterpret_cast<u32x4*>(votes32 + (j >> 2));
+            w[it] = *p;
+            if ((w[it].x | w[it].y | w[it].z | w[it].w) != 0u) *p = z;
+        }
+    }
+    const uint32_t vstar = vote_thr[0], take_eq = vote_thr[1];   // found by mv_mask_count
 
     // coordinates selected / tied before this block
     uint64_t mine = 0;
@@ -1003,25 +1093,16 @@ __global__ __launch_bounds__(kVoteThreads) void mv_mask_emit(uint32_t* __restric
     __syncthreads();
     uint32_t gt_before = (uint32_t)(before >> 32), eq_before = (uint32_t)before;
 
-    const int64_t base = (int64_t)blockIdx.x * kVoteBlock;
-    for (int it = 0; it < kVoteBlock / (kVoteThreads * 16); ++it) {
-        const int64_t j = base + ((int64_t)it * kVoteThreads + threadIdx.x) * 16;
-        uint32_t ww[4] = {0, 0, 0, 0};
-        uint32_t gt = 0, eq = 0;
-        if (j < d) {
-            u32x4* p = reinterpret_cast<u32x4*>(votes32 + (j >> 2));
-            const u32x4 w = *p;
-            ww[0] = w.x; ww[1] = w.y; ww[2] = w.z; ww[3] = w.w;
-            if ((w.x | w.y | w.z | w.w) != 0u) {
-                const u32x4 z = {0u, 0u, 0u, 0u};
-                *p = z;
-            }
 #pragma unroll
-            for (int q = 0; q < 16; ++q) {
-                const uint32_t v = (ww[q >> 2] >> (8 * (q & 3))) & 255u;
-                gt += (v > vstar);
-                eq += (v == vstar);
-            }
+    for (int it = 0; it < kIt; ++it) {
+        const int64_t j = base + ((int64_t)it * kVoteThreads + threadIdx.x) * 16;
+        const uint32_t ww[4] = {w[it].x, w[it].y, w[it].z, w[it].w};
+        uint32_t gt = 0, eq = 0;
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+            const uint32_t v = (ww[q >> 2] >> (8 * (q & 3))) & 255u;   // zero beyond d: never counted (v* >= 1)
+            gt += (v > vstar);
+            eq += (v == vstar);
         }
         uint64_t total;
         const uint64_t ex = block_excl_scan64<kVoteThreads>(pack2(gt, eq), scan_lds, total);
