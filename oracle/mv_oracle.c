@@ -255,6 +255,158 @@ int mvo_vote_step(const void* grads, int64_t ld_g, int32_t grad_is_bf16,
 }
 
 /* ------------------------------------------------------------------ */
+/* majority voting with add-drop (Algorithm 2)                          */
+/* ------------------------------------------------------------------ */
+
+/*
+ * Readings of Algorithm 2 and Sec. 3 where they are silent or garbled:
+ *   - The add set is taken among A = supp(M_n) \ supp(M~_{n,t-1}), the drop set
+ *     among D = supp(M~_{n,t-1}) \ supp(M_n) (Sec. 3, second paragraph).  The
+ *     printed formulas apply S_top / S_bot to a vector that is zero outside A
+ *     (resp. D); read literally they would pick coordinates outside the set
+ *     when the set has fewer than K_ad members.  Sec. 3 says "at most K_ad"
+ *     indices are added / removed, so: add = the min(K_ad, |A|) members of A
+ *     with the largest |Delta-bar|, drop = the min(K_ad, |D|) members of D with
+ *     the smallest |Delta-bar|.
+ *   - Ties: add under (magnitude desc, index asc); drop under (magnitude asc,
+ *     index asc).  Unpinned by the paper, as for S_top.
+ *   - M~_{n,0} and M^sum_0 are not given: the state starts empty (all zero) and
+ *     is carried by the caller; a first step with K_ad = K then makes
+ *     M~_{n,1} = M_n and M^sum_1 the plain vote count of Algorithm 1.
+ *   - The magnitudes that rank the drop candidates are those of the CURRENT
+ *     Delta-bar (the formula multiplies by Delta-bar_{n,t}).
+ *   - The mask is S_top(M^sum_t, K) with the tie rule of Algorithm 1's mask.
+ */
+
+/* S_top restricted to a set: among the coordinates j with member[j] != 0, the
+ * first `take` under (key desc, index asc) if largest != 0, else under
+ * (key asc, index asc); written ascending.  Returns how many were taken
+ * (min(take, set size)), or -1. */
+static int64_t pick_in_set(const uint32_t* keys, const uint8_t* member, int64_t d, int64_t take,
+                           int largest, uint32_t* idx_out)
+{
+    int64_t n = 0;
+    for (int64_t j = 0; j < d; ++j) n += member[j] ? 1 : 0;
+    mvo_pair* pairs = (mvo_pair*)malloc((size_t)(n > 0 ? n : 1) * sizeof(mvo_pair));
+    if (!pairs) return -1;
+    int64_t m = 0;
+    for (int64_t j = 0; j < d; ++j)
+        if (member[j]) {
+            /* ascending order of keys = descending order of the complemented keys */
+            pairs[m].value = largest ? keys[j] : (0x7FFFFFFFu - keys[j]);
+            pairs[m].index = (uint32_t)j;
+            ++m;
+        }
+    qsort(pairs, (size_t)n, sizeof(mvo_pair), cmp_value_desc_index_asc);
+    const int64_t got = take < n ? take : n;
+    for (int64_t k = 0; k < got; ++k) idx_out[k] = pairs[k].index;
+    qsort(idx_out, (size_t)got, sizeof(uint32_t), cmp_u32_asc);
+    free(pairs);
+    return got;
+}
+
+/*
+ * One iteration of Algorithm 2 for all workers.
+ *   vote      : N x d bytes (0/1), in: M~_{n,t-1}, out: M~_{n,t}
+ *   msum      : d bytes, in: M^sum_{t-1}, out: M^sum_t
+ *   worker_idx: N x K out, supp(M_{n,t}) ascending (the plain top-K, not transmitted)
+ *   add_idx, drop_idx : N x K_ad out, ascending, the first n_add[n] / n_drop[n] entries valid
+ *   mask_idx, agg, err: as in mvo_vote_step
+ * Returns 0, or -1 on bad arguments / allocation failure / inconsistent state.
+ */
+int mvo_ad_vote_step(const void* grads, int64_t ld_g, int32_t grad_is_bf16,
+                     float* err, int64_t ld_e,
+                     int32_t N, int64_t d, int64_t K, int64_t K_ad, int32_t reduce_mean,
+                     uint8_t* vote, uint8_t* msum,
+                     uint32_t* worker_idx, uint32_t* add_idx, uint32_t* drop_idx,
+                     int64_t* n_add, int64_t* n_drop,
+                     uint32_t* mask_idx, float* agg, int32_t threads)
+{
+    if (N < 1 || N > 255 || d < 1 || d > 0x7FFFFFFF || K < 1 || K > d || K_ad < 1 || K_ad > K) return -1;
+    if (ld_g < d || ld_e < d) return -1;
+    if (threads < 1) threads = 1;
+    float* delta_bar = (float*)malloc((size_t)N * (size_t)d * sizeof(float));
+    if (!delta_bar) return -1;
+    int failed = 0;
+
+    /* worker side (Algorithm 2, voting phase): each worker's add and drop lists
+     * depend only on its own row and its own previous vote */
+#ifdef _OPENMP
+#pragma omp parallel for num_threads(threads) schedule(dynamic, 1)
+#endif
+    for (int32_t n = 0; n < N; ++n) {
+        float* row = delta_bar + (int64_t)n * d;
+        const uint8_t* vt = vote + (int64_t)n * d;
+        uint32_t* keys = (uint32_t*)malloc((size_t)d * sizeof(uint32_t));
+        uint8_t*  cur = (uint8_t*)calloc((size_t)d, 1);     /* M_{n,t} */
+        uint8_t*  setA = (uint8_t*)malloc((size_t)d);
+        uint8_t*  setD = (uint8_t*)malloc((size_t)d);
+        float*    wide = grad_is_bf16 ? (float*)malloc((size_t)d * sizeof(float)) : NULL;
+        if (!keys || !cur || !setA || !setD || (grad_is_bf16 && !wide)) {
+            failed = 1;
+        } else {
+            if (grad_is_bf16) {
+                mvo_widen_bf16((const uint16_t*)grads + (int64_t)n * ld_g, wide, d);
+                mvo_error_compensate(wide, err + (int64_t)n * ld_e, row, d);
+            } else {
+                mvo_error_compensate((const float*)grads + (int64_t)n * ld_g, err + (int64_t)n * ld_e, row, d);
+            }
+            uint32_t* widx = worker_idx + (int64_t)n * K;
+            if (mvo_row_topk(row, d, K, widx) != 0) {
+                failed = 1;
+            } else {
+                for (int64_t k = 0; k < K; ++k) cur[widx[k]] = 1;
+                for (int64_t j = 0; j < d; ++j) {
+                    keys[j] = magnitude_key(row[j]);
+                    setA[j] = (uint8_t)(cur[j] && !vt[j]);    /* max(M_n - M~, 0) */
+                    setD[j] = (uint8_t)(vt[j] && !cur[j]);    /* max(M~ - M_n, 0) */
+                }
+                n_add[n] = pick_in_set(keys, setA, d, K_ad, 1, add_idx + (int64_t)n * K_ad);
+                n_drop[n] = pick_in_set(keys, setD, d, K_ad, 0, drop_idx + (int64_t)n * K_ad);
+                if (n_add[n] < 0 || n_drop[n] < 0) failed = 1;
+            }
+        }
+        free(keys); free(cur); free(setA); free(setD); free(wide);
+    }
+    if (failed) {
+        free(delta_bar);
+        return -1;
+    }
+
+    /* M~_n = M~_n + M^add_n - M^drop_n ;  PS side: M^sum += sum_n (M^add_n - M^drop_n) */
+    for (int32_t n = 0; n < N; ++n) {
+        uint8_t* vt = vote + (int64_t)n * d;
+        for (int64_t k = 0; k < n_add[n]; ++k) {
+            const uint32_t j = add_idx[(int64_t)n * K_ad + k];
+            vt[j] = 1;
+            if (msum[j] == 255) failed = 1;
+            msum[j] += 1;
+        }
+    }
+    for (int32_t n = 0; n < N; ++n) {
+        uint8_t* vt = vote + (int64_t)n * d;
+        for (int64_t k = 0; k < n_drop[n]; ++k) {
+            const uint32_t j = drop_idx[(int64_t)n * K_ad + k];
+            vt[j] = 0;
+            if (msum[j] == 0) failed = 1;            /* the state was not a sum of votes */
+            msum[j] -= 1;
+        }
+    }
+    if (failed || mvo_mask(msum, d, K, mask_idx) != 0) {
+        free(delta_bar);
+        return -1;
+    }
+    mvo_aggregate(delta_bar, d, N, mask_idx, K, reduce_mean, agg);
+#ifdef _OPENMP
+#pragma omp parallel for num_threads(threads) schedule(dynamic, 1)
+#endif
+    for (int32_t n = 0; n < N; ++n)
+        mvo_error_update(delta_bar + (int64_t)n * d, d, mask_idx, K, err + (int64_t)n * ld_e);
+    free(delta_bar);
+    return 0;
+}
+
+/* ------------------------------------------------------------------ */
 /* communication-load arithmetic (Sec. 2.1 and Sec. 4.4), reporting only */
 /* ------------------------------------------------------------------ */
 

@@ -59,6 +59,9 @@ def lib() -> ctypes.CDLL:
         L.mvo_error_update.restype = None
         L.mvo_vote_step.argtypes = [vp, i64, i32, vp, i64, i32, i64, i64, i32, vp, vp, vp, vp, i32]
         L.mvo_vote_step.restype = i32
+        L.mvo_ad_vote_step.argtypes = [vp, i64, i32, vp, i64, i32, i64, i64, i64, i32, vp, vp, vp, vp, vp, vp, vp,
+                                       vp, vp, i32]
+        L.mvo_ad_vote_step.restype = i32
         L.mvo_bits_per_position.argtypes = [dbl]
         L.mvo_bits_per_position.restype = i32
         L.mvo_q_val.argtypes = [dbl, dbl, dbl]
@@ -174,6 +177,48 @@ def vote_step(grads: np.ndarray, err: np.ndarray, K: int, reduce_mean: bool = Tr
     if rc != 0:
         raise ValueError("mvo_vote_step rejected its arguments")
     return StepResult(widx, v, m, agg, e)
+
+
+# ---------------------------------------------------------------- add-drop voting (Algorithm 2)
+
+@dataclass
+class AdStepResult:
+    worker_idx: np.ndarray  # N x K uint32: supp(M_n), ascending
+    add_idx: list           # per worker: ascending uint32 array of the added positions
+    drop_idx: list          # per worker: ascending uint32 array of the dropped positions
+    vote: np.ndarray        # N x d uint8 0/1: M~_{n,t}
+    msum: np.ndarray        # d uint8: M^sum_t
+    mask_idx: np.ndarray
+    agg: np.ndarray
+    err: np.ndarray
+
+
+def ad_vote_step(grads: np.ndarray, err: np.ndarray, K: int, K_ad: int, vote: np.ndarray, msum: np.ndarray,
+                 reduce_mean: bool = True, threads: int = 1) -> AdStepResult:
+    """One iteration of majority voting with add-drop.  `vote` (N x d, 0/1) and
+    `msum` (d) are the state before the step; they are not modified, the new
+    state is returned."""
+    assert grads.ndim == 2 and err.shape == grads.shape
+    is_bf16 = grads.dtype == np.uint16
+    g = _c(grads, np.uint16 if is_bf16 else np.float32)
+    e = np.array(err, dtype=np.float32, order="C", copy=True)
+    N, d = g.shape
+    vt = np.array(vote, dtype=np.uint8, order="C", copy=True).reshape(N, d)
+    ms = np.array(msum, dtype=np.uint8, order="C", copy=True).reshape(d)
+    widx = np.empty((N, K), np.uint32)
+    add = np.zeros((N, K_ad), np.uint32)
+    drop = np.zeros((N, K_ad), np.uint32)
+    n_add = np.zeros(N, np.int64)
+    n_drop = np.zeros(N, np.int64)
+    m = np.empty(K, np.uint32)
+    agg = np.empty(K, np.float32)
+    rc = lib().mvo_ad_vote_step(_ptr(g), d, int(is_bf16), _ptr(e), d, N, d, K, K_ad, int(reduce_mean),
+                                _ptr(vt), _ptr(ms), _ptr(widx), _ptr(add), _ptr(drop), _ptr(n_add),
+                                _ptr(n_drop), _ptr(m), _ptr(agg), int(threads))
+    if rc != 0:
+        raise ValueError("mvo_ad_vote_step rejected its arguments or state")
+    return AdStepResult(widx, [add[n, : n_add[n]].copy() for n in range(N)],
+                        [drop[n, : n_drop[n]].copy() for n in range(N)], vt, ms, m, agg, e)
 
 
 # ---------------------------------------------------------------- comm load
