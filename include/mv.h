@@ -45,6 +45,8 @@ typedef enum {
 
 typedef enum { MV_F32 = 0, MV_BF16 = 1 } mv_dtype;          /* dtype of g only; e and agg are fp32 */
 typedef enum { MV_REDUCE_MEAN = 0, MV_REDUCE_SUM = 1 } mv_reduce;
+/* mv_config.flags: the context also carries the scratch of mv_ad_vote_step */
+#define MV_FLAG_ADD_DROP 1
 
 typedef struct {
     uint32_t struct_size;   /* = sizeof(mv_config) */
@@ -54,7 +56,7 @@ typedef struct {
     int64_t  d;             /* coordinates per worker, 1 .. 2^31-1 */
     int64_t  k;             /* K, 1 .. d */
     int32_t  reduce;        /* mv_reduce; MEAN is Sec. 2's definition, SUM is Algorithm 1's last line */
-    int32_t  reserved;      /* must be 0 */
+    int32_t  flags;         /* MV_FLAG_* bits; unknown bits are refused */
     void*    workspace;     /* optional device scratch of >= mv_workspace_bytes(); NULL: the context allocates it */
     size_t   workspace_bytes;
 } mv_config;
@@ -70,7 +72,7 @@ size_t mv_workspace_bytes(const mv_config* cfg);
  * for an invalid configuration), then allocates and zeroes the scratch.
  * cfg.workspace, when given, must be 256-byte aligned device memory.
  * Errors: MV_ERR_INVALID_ARG (null, struct_size, N, d, k, dtype, reduce,
- * reserved != 0, workspace too small or misaligned), MV_ERR_ALLOC, MV_ERR_DEVICE.
+ * unknown flags, workspace too small or misaligned), MV_ERR_ALLOC, MV_ERR_DEVICE.
  */
 mv_status mv_begin(const mv_config* cfg, mv_ctx** out_ctx);
 
@@ -105,6 +107,44 @@ mv_status mv_vote_step(mv_ctx* ctx,
                        uint32_t* mask_idx,
                        float* agg_vals,
                        void* stream);
+
+/*
+ * One iteration of majority voting with add-drop (paper: Algorithm 2, Sec. 3),
+ * enqueued on `stream` like mv_vote_step.  The context must have been begun with
+ * MV_FLAG_ADD_DROP (else MV_ERR_STATE).  Every worker keeps a standing vote
+ * M~_n; per step at most k_ad coordinates join it (the k_ad largest |a| among
+ * the worker's current top-K that are not in it) and at most k_ad leave it (the
+ * k_ad smallest |a| among its members that are not in the current top-K), ties to
+ * the lowest coordinate in both; M^sum, the sum of the standing votes, moves
+ * with them, and the mask is the K most voted coordinates of M^sum.  The state is
+ * the caller's (zero it to start; a first step with k_ad = K then is a plain
+ * majority vote):
+ *
+ *   vote_bits  device, N rows of ld_bits 32-bit words, bit (j % 32) of word j / 32 of
+ *              row n = M~_n[j]; in/out.  ld_bits >= ceil(d/32) rounded up to a multiple
+ *              of 4, itself a multiple of 4; 16-byte aligned; at most K bits per row
+ *   msum       device, d bytes rounded up to a multiple of 16 (the padding stays
+ *              zero), 16-byte aligned; in: M^sum_{t-1}, out: M^sum_t
+ *   k_ad       1 .. K
+ *   add_idx    device, N x k_ad uint32 out: row n = the coordinates added to M~_n,
+ *              ascending, counts[2n] of them valid
+ *   drop_idx   device, N x k_ad uint32 out: the coordinates removed, counts[2n+1] valid
+ *   counts     device, 2N uint32 out
+ *   grads, err, mask_idx, agg_vals: as in mv_vote_step (err is updated with the mask
+ *              of this step)
+ *
+ * Errors as mv_vote_step, plus MV_ERR_INVALID_ARG for k_ad, ld_bits, alignment or a
+ * null state / output pointer.
+ */
+mv_status mv_ad_vote_step(mv_ctx* ctx,
+                          const void* grads, int64_t ld_g,
+                          float* err, int64_t ld_e,
+                          int64_t k_ad,
+                          uint32_t* vote_bits, int64_t ld_bits,
+                          uint8_t* msum,
+                          uint32_t* add_idx, uint32_t* drop_idx, uint32_t* counts,
+                          uint32_t* mask_idx, float* agg_vals,
+                          void* stream);
 
 /*
  * Ends the context: waits for the device, frees scratch the context allocated

@@ -16,10 +16,11 @@ LIB_PATH = os.path.join(_HERE, "libmv.so")
 MV_OK, MV_ERR_INVALID_ARG, MV_ERR_UNSUPPORTED, MV_ERR_ALLOC, MV_ERR_DEVICE, MV_ERR_STATE = range(6)
 MV_F32, MV_BF16 = 0, 1
 MV_REDUCE_MEAN, MV_REDUCE_SUM = 0, 1
+MV_FLAG_ADD_DROP = 1
 
 # every symbol include/mv.h declares
 ABI_SYMBOLS = (
-    "mv_workspace_bytes", "mv_begin", "mv_vote_step", "mv_end", "mv_release", "mv_status_string",
+    "mv_workspace_bytes", "mv_begin", "mv_vote_step", "mv_ad_vote_step", "mv_end", "mv_release", "mv_status_string",
     "mv_kernel_count", "mv_kernel_name", "mv_set_profiling", "mv_step_kernel_ms",
     "mv_last_step_row_stats", "mv_probe_copy",
 )
@@ -34,7 +35,7 @@ class mv_config(ctypes.Structure):
         ("d", ctypes.c_int64),
         ("k", ctypes.c_int64),
         ("reduce", ctypes.c_int32),
-        ("reserved", ctypes.c_int32),
+        ("flags", ctypes.c_int32),
         ("workspace", ctypes.c_void_p),
         ("workspace_bytes", ctypes.c_size_t),
     ]
@@ -66,6 +67,8 @@ def load() -> ctypes.CDLL:
     L.mv_begin.restype = i32
     L.mv_vote_step.argtypes = [vp, vp, i64, vp, i64, vp, vp, vp, vp, vp]
     L.mv_vote_step.restype = i32
+    L.mv_ad_vote_step.argtypes = [vp, vp, i64, vp, i64, i64, vp, i64, vp, vp, vp, vp, vp, vp, vp]
+    L.mv_ad_vote_step.restype = i32
     L.mv_end.argtypes = [vp]
     L.mv_end.restype = i32
     L.mv_release.argtypes = [vp]
@@ -93,8 +96,8 @@ def status_string(status: int) -> str:
 
 
 def make_config(n_workers: int, d: int, k: int, grad_dtype: int = MV_F32, reduce: int = MV_REDUCE_MEAN,
-                device: int = 0, workspace: int = 0, workspace_bytes: int = 0) -> mv_config:
-    return mv_config(ctypes.sizeof(mv_config), device, n_workers, grad_dtype, d, k, reduce, 0,
+                device: int = 0, workspace: int = 0, workspace_bytes: int = 0, flags: int = 0) -> mv_config:
+    return mv_config(ctypes.sizeof(mv_config), device, n_workers, grad_dtype, d, k, reduce, flags,
                      workspace or None, workspace_bytes)
 
 
@@ -131,6 +134,22 @@ def mv_vote_step(ctx: int, grads, err, worker_idx, votes, mask_idx, agg_vals, st
         stream.cuda_stream)
     if st != MV_OK:
         raise MvError(st, "mv_vote_step")
+
+
+def mv_ad_vote_step(ctx: int, grads, err, k_ad: int, vote_bits, msum, add_idx, drop_idx, counts, mask_idx,
+                    agg_vals, stream=None, ld_g: Optional[int] = None, ld_e: Optional[int] = None) -> None:
+    """Enqueues one add-drop vote step (Algorithm 2).  vote_bits: N x ld_bits int32
+    device tensor (the standing votes' bitmaps), msum: uint8 device tensor."""
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream(err.device)
+    st = load().mv_ad_vote_step(
+        ctx, _dev_ptr(grads), grads.stride(0) if ld_g is None else ld_g,
+        _dev_ptr(err), err.stride(0) if ld_e is None else ld_e, int(k_ad),
+        _dev_ptr(vote_bits), vote_bits.stride(0), _dev_ptr(msum), _dev_ptr(add_idx), _dev_ptr(drop_idx),
+        _dev_ptr(counts), _dev_ptr(mask_idx), _dev_ptr(agg_vals), stream.cuda_stream)
+    if st != MV_OK:
+        raise MvError(st, "mv_ad_vote_step")
 
 
 def mv_end(ctx: int) -> None:

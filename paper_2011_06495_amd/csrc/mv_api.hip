@@ -21,11 +21,20 @@ enum KernelId {
     KID_MASK_COUNT,
     KID_MASK_EMIT,
     KID_GATHER,
+    // add-drop voting only
+    KID_AD_COLLECT_ADD,
+    KID_AD_COLLECT_DROP,
+    KID_AD_SELECT,
+    KID_AD_APPLY,
+    KID_AD_COMPACT_COUNT,
+    KID_AD_COMPACT_EMIT,
+    KID_AD_LEVELS,
     KID_COUNT
 };
-const char* const kKernelNames[KID_COUNT] = {"mv_sample_hist", "mv_pick_threshold", "mv_stream_collect",
-                                             "mv_row_select",  "mv_row_votes",      "mv_mask_count",
-                                             "mv_mask_emit",   "mv_gather_update"};
+const char* const kKernelNames[KID_COUNT] = {
+    "mv_sample_hist",    "mv_pick_threshold",  "mv_stream_collect",   "mv_row_select",      "mv_row_votes",
+    "mv_mask_count",     "mv_mask_emit",       "mv_gather_update",    "mv_ad_collect_add",  "mv_ad_collect_drop",
+    "mv_ad_select",      "mv_ad_apply",        "mv_ad_compact_count", "mv_ad_compact_emit", "mv_ad_levels"};
 
 constexpr size_t kAlign = 256;
 constexpr int kEventRing = 64;   // steps whose kernel durations stay readable
@@ -44,10 +53,15 @@ struct Plan {
     uint32_t n_vote_blocks;
     uint32_t emit_blocks;       // workgroups per row that walk the candidate list
     uint32_t scan_blocks;       // workgroups per row that scan the segment tallies
+    // add-drop voting (only with MV_FLAG_ADD_DROP)
+    bool     add_drop;
+    uint32_t nwords, nwords_pad;  // 32-bit words of a row's vote bitmap, and padded to a multiple of 4
+    uint32_t cap_d;               // capacity of a row's list of removal candidates
+    uint32_t bit_blocks;          // workgroups of 1024 bitmap words per row
     // scratch offsets (bytes)
     size_t off_hist, off_tau, off_rowcnt, off_slow, off_kth, off_tiecut, off_cntge, off_seg, off_segsel,
         off_segpre,
-        off_blktotal, off_votethr, off_cand, off_votes, off_blockcnt;
+        off_blktotal, off_votethr, off_alist, off_dlist, off_adcount, off_adthr, off_adbits, off_adblk, off_cand, off_votes, off_blockcnt;
     size_t total_bytes;
 };
 
@@ -60,7 +74,7 @@ bool config_valid(const mv_config* c)
     if (c->k < 1 || c->k > c->d) return false;
     if (c->grad_dtype != MV_F32 && c->grad_dtype != MV_BF16) return false;
     if (c->reduce != MV_REDUCE_MEAN && c->reduce != MV_REDUCE_SUM) return false;
-    if (c->reserved != 0) return false;
+    if ((c->flags & ~MV_FLAG_ADD_DROP) != 0) return false;
     if (c->device < 0) return false;
     return true;
 }
@@ -121,6 +135,19 @@ Plan make_plan(const mv_config* c)
     p.off_cand = off;     off += align_up((size_t)p.N * p.cap * 8);
     p.off_votes = off;    off += align_up(((size_t)p.d + 15) / 16 * 16);
     p.off_blockcnt = off; off += align_up((size_t)p.n_vote_blocks * 8);
+    p.add_drop = (c->flags & MV_FLAG_ADD_DROP) != 0;
+    p.nwords = (uint32_t)((p.d + 31) / 32);
+    p.nwords_pad = (p.nwords + 3) / 4 * 4;
+    p.cap_d = p.K;
+    p.bit_blocks = (p.nwords_pad + 1023) / 1024;
+    if (p.add_drop) {
+        p.off_alist = off;   off += align_up((size_t)p.N * p.cap * 8);
+        p.off_dlist = off;   off += align_up((size_t)p.N * p.cap_d * 8);
+        p.off_adcount = off; off += align_up((size_t)p.N * 2 * 4);
+        p.off_adthr = off;   off += align_up((size_t)p.N * 4 * 4);
+        p.off_adbits = off;  off += align_up((size_t)p.N * 2 * p.nwords_pad * 4);
+        p.off_adblk = off;   off += align_up((size_t)p.N * 2 * p.bit_blocks * 4);
+    }
     p.total_bytes = off;
     return p;
 }
@@ -208,6 +235,8 @@ mv_status mv_begin(const mv_config* cfg, mv_ctx** out_ctx)
     bool ok = hipMemset(c->ws + plan.off_hist, 0, plan.off_tau - plan.off_hist) == hipSuccess &&
               hipMemset(c->ws + plan.off_votes, 0, ((size_t)plan.d + 15) / 16 * 16) == hipSuccess &&
               hipMemset(c->ws + plan.off_tau, 0, plan.off_seg - plan.off_tau) == hipSuccess;
+    if (ok && plan.add_drop)   // the scratch bitmaps start at zero and are left at zero by every step
+        ok = hipMemset(c->ws + plan.off_adcount, 0, plan.off_adblk - plan.off_adcount) == hipSuccess;
     ok = ok && hipDeviceSynchronize() == hipSuccess;
     if (!ok) {
         (void)hipGetLastError();
@@ -219,23 +248,52 @@ mv_status mv_begin(const mv_config* cfg, mv_ctx** out_ctx)
     return MV_OK;
 }
 
-mv_status mv_vote_step(mv_ctx* c, const void* grads, int64_t ld_g, float* err, int64_t ld_e,
-                       uint32_t* worker_idx, uint8_t* votes, uint32_t* mask_idx, float* agg_vals,
-                       void* stream_v)
+}  // extern "C"
+
+namespace {
+
+// What the two step entry points pass down.
+struct StepArgs {
+    const void* grads; int64_t ld_g;
+    float* err;        int64_t ld_e;
+    uint32_t* worker_idx;
+    uint8_t*  votes;
+    uint32_t* mask_idx;
+    float*    agg_vals;
+    // add-drop voting (k_ad == 0: plain majority voting)
+    int64_t   k_ad;
+    uint32_t* vote_bits; int64_t ld_bits;
+    uint8_t*  msum;
+    uint32_t* add_idx;
+    uint32_t* drop_idx;
+    uint32_t* counts;
+};
+
+mv_status check_common(mv_ctx* c, const StepArgs& a)
 {
     if (!c) return MV_ERR_INVALID_ARG;
     if (c->ended) return MV_ERR_STATE;
-    if (!grads || !err || !mask_idx || !agg_vals) return MV_ERR_INVALID_ARG;
+    if (!a.grads || !a.err || !a.mask_idx || !a.agg_vals) return MV_ERR_INVALID_ARG;
     const Plan& p = c->plan;
     const bool bf16 = c->cfg.grad_dtype == MV_BF16;
-    if (ld_g < p.d || ld_e < p.d) return MV_ERR_INVALID_ARG;
-    if (ld_g % (bf16 ? 8 : 4) != 0 || ld_e % 4 != 0) return MV_ERR_INVALID_ARG;
-    if ((reinterpret_cast<uintptr_t>(grads) & 15) || (reinterpret_cast<uintptr_t>(err) & 15))
+    if (a.ld_g < p.d || a.ld_e < p.d) return MV_ERR_INVALID_ARG;
+    if (a.ld_g % (bf16 ? 8 : 4) != 0 || a.ld_e % 4 != 0) return MV_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(a.grads) & 15) || (reinterpret_cast<uintptr_t>(a.err) & 15))
         return MV_ERR_INVALID_ARG;
-    if ((reinterpret_cast<uintptr_t>(mask_idx) & 3) || (reinterpret_cast<uintptr_t>(agg_vals) & 3) ||
-        (reinterpret_cast<uintptr_t>(worker_idx) & 3))
+    if ((reinterpret_cast<uintptr_t>(a.mask_idx) & 3) || (reinterpret_cast<uintptr_t>(a.agg_vals) & 3) ||
+        (reinterpret_cast<uintptr_t>(a.worker_idx) & 3))
         return MV_ERR_INVALID_ARG;
+    return MV_OK;
+}
 
+// Enqueues one step: the part common to both voting schemes (threshold estimate,
+// streaming pass, exact per-row select), then either the plain vote count or the
+// add-drop update of the standing votes, then the mask and the aggregate.
+mv_status enqueue_step(mv_ctx* c, const StepArgs& a, void* stream_v)
+{
+    const Plan& p = c->plan;
+    const bool bf16 = c->cfg.grad_dtype == MV_BF16;
+    const bool add_drop = a.k_ad > 0;
     DeviceGuard guard(c->cfg.device);
     if (!guard.ok) return MV_ERR_DEVICE;
     hipStream_t st = static_cast<hipStream_t>(stream_v);
@@ -255,6 +313,12 @@ mv_status mv_vote_step(mv_ctx* c, const void* grads, int64_t ld_g, float* err, i
     mvk::u32x2* cand = ws_ptr<mvk::u32x2>(c, p.off_cand);
     uint32_t* votes32 = ws_ptr<uint32_t>(c, p.off_votes);
     mvk::u32x2* blockcnt = ws_ptr<mvk::u32x2>(c, p.off_blockcnt);
+    mvk::u32x2* alist = p.add_drop ? ws_ptr<mvk::u32x2>(c, p.off_alist) : nullptr;
+    mvk::u32x2* dlist = p.add_drop ? ws_ptr<mvk::u32x2>(c, p.off_dlist) : nullptr;
+    uint32_t* adcount = p.add_drop ? ws_ptr<uint32_t>(c, p.off_adcount) : nullptr;
+    uint32_t* adthr = p.add_drop ? ws_ptr<uint32_t>(c, p.off_adthr) : nullptr;
+    uint32_t* adbits = p.add_drop ? ws_ptr<uint32_t>(c, p.off_adbits) : nullptr;
+    uint32_t* adblk = p.add_drop ? ws_ptr<uint32_t>(c, p.off_adblk) : nullptr;
 
     const int slot = (int)(c->steps_done % kEventRing);
     for (int i = 0; i < KID_COUNT; ++i) c->ev_recorded[slot][i] = false;
@@ -282,16 +346,16 @@ mv_status mv_vote_step(mv_ctx* c, const void* grads, int64_t ld_g, float* err, i
         before(KID_SAMPLE);
         if (bf16)
             hipLaunchKernelGGL(mvk::mv_sample_hist<uint16_t>, grid, dim3(256), 0, st,
-                               static_cast<const uint16_t*>(grads), ld_g, err, ld_e, p.d, p.stride,
+                               static_cast<const uint16_t*>(a.grads), a.ld_g, a.err, a.ld_e, p.d, p.stride,
                                p.n_sampled_chunks, hist);
         else
             hipLaunchKernelGGL(mvk::mv_sample_hist<float>, grid, dim3(256), 0, st,
-                               static_cast<const float*>(grads), ld_g, err, ld_e, p.d, p.stride,
+                               static_cast<const float*>(a.grads), a.ld_g, a.err, a.ld_e, p.d, p.stride,
                                p.n_sampled_chunks, hist);
         after(KID_SAMPLE);
         before(KID_PICK);
         hipLaunchKernelGGL(mvk::mv_pick_threshold, dim3(p.N), dim3(mvk::kRowThreads), 0, st, hist, p.m_target,
-                           tau, rowcnt, slow, cntge);
+                           tau, rowcnt, slow, cntge, adcount);
         after(KID_PICK);
     }
     // 2. streaming pass: a = g + e over e, candidates out
@@ -300,52 +364,135 @@ mv_status mv_vote_step(mv_ctx* c, const void* grads, int64_t ld_g, float* err, i
         before(KID_STREAM);
         if (bf16)
             hipLaunchKernelGGL(mvk::mv_stream_collect<uint16_t>, grid, dim3(mvk::kStreamThreads), 0, st,
-                               static_cast<const uint16_t*>(grads), ld_g, err, ld_e, p.d, tau, cand, p.cap,
+                               static_cast<const uint16_t*>(a.grads), a.ld_g, a.err, a.ld_e, p.d, tau, cand, p.cap,
                                rowcnt, seg, segsel, p.nseg);
         else
             hipLaunchKernelGGL(mvk::mv_stream_collect<float>, grid, dim3(mvk::kStreamThreads), 0, st,
-                               static_cast<const float*>(grads), ld_g, err, ld_e, p.d, tau, cand, p.cap,
+                               static_cast<const float*>(a.grads), a.ld_g, a.err, a.ld_e, p.d, tau, cand, p.cap,
                                rowcnt, seg, segsel, p.nseg);
         after(KID_STREAM);
     }
     // 3. exact per-row select
     before(KID_ROW_SELECT);
-    hipLaunchKernelGGL(mvk::mv_row_select, dim3(p.N), dim3(mvk::kRowThreads), 0, st, err, ld_e, p.d, p.K, cand,
-                       p.cap, rowcnt, tau, kth, tiecut, worker_idx, votes32, cntge, slow);
+    hipLaunchKernelGGL(mvk::mv_row_select, dim3(p.N), dim3(mvk::kRowThreads), 0, st, a.err, a.ld_e, p.d, p.K, cand,
+                       p.cap, rowcnt, tau, kth, tiecut, a.worker_idx, votes32, cntge, slow, add_drop ? 1 : 0);
     after(KID_ROW_SELECT);
-    // 4. votes (and segment tallies when the sorted lists are wanted)
-    const bool sorted = worker_idx != nullptr;
-    before(KID_ROW_VOTES);
-    hipLaunchKernelGGL(mvk::mv_row_votes, dim3(p.emit_blocks, p.N), dim3(mvk::kVoteThreads), 0, st, cand, p.cap,
-                       rowcnt, p.nseg, kth, tiecut, slow, sorted ? segsel : nullptr, votes32, cntge);
-    after(KID_ROW_VOTES);
-    // 5. global mask; extra workgroups scan the tallies / write the sorted vote lists
+
+    const bool sorted = a.worker_idx != nullptr;
+    uint32_t* mask_votes32 = votes32;     // the packed vote bytes the mask is selected from
+    if (!add_drop) {
+        // 4. votes (and segment tallies when the sorted lists are wanted)
+        before(KID_ROW_VOTES);
+        hipLaunchKernelGGL(mvk::mv_row_votes, dim3(p.emit_blocks, p.N), dim3(mvk::kVoteThreads), 0, st, cand, p.cap,
+                           rowcnt, p.nseg, kth, tiecut, slow, sorted ? segsel : nullptr, votes32, cntge);
+        after(KID_ROW_VOTES);
+    } else {
+        // 4'. add-drop voting: candidates for addition and removal, exact K_ad-selects,
+        // update of msum and of the standing votes, sorted add / drop lists
+        const uint32_t k_ad = (uint32_t)a.k_ad;
+        uint32_t* msum32 = reinterpret_cast<uint32_t*>(a.msum);
+        before(KID_AD_COLLECT_ADD);
+        hipLaunchKernelGGL(mvk::mv_ad_collect_add, dim3(p.emit_blocks, p.N), dim3(mvk::kVoteThreads), 0, st, a.err,
+                           a.ld_e, p.d, cand, p.cap, rowcnt, kth, tiecut, slow, a.vote_bits, a.ld_bits, alist,
+                           adcount);
+        after(KID_AD_COLLECT_ADD);
+        before(KID_AD_COLLECT_DROP);
+        hipLaunchKernelGGL(mvk::mv_ad_collect_drop, dim3(p.bit_blocks, p.N), dim3(mvk::kVoteThreads), 0, st, a.err,
+                           a.ld_e, p.d, kth, tiecut, a.vote_bits, a.ld_bits, p.nwords_pad, dlist, p.cap_d, adcount);
+        after(KID_AD_COLLECT_DROP);
+        before(KID_AD_SELECT);
+        hipLaunchKernelGGL(mvk::mv_ad_select, dim3(2, p.N), dim3(mvk::kRowThreads), 0, st, alist, p.cap, dlist,
+                           p.cap_d, adcount, k_ad, tau, slow, adthr, a.counts);
+        after(KID_AD_SELECT);
+        before(KID_AD_APPLY);
+        hipLaunchKernelGGL(mvk::mv_ad_apply, dim3(p.emit_blocks, p.N), dim3(mvk::kVoteThreads), 0, st, alist, p.cap,
+                           dlist, p.cap_d, adcount, adthr, adbits, p.nwords_pad, msum32);
+        after(KID_AD_APPLY);
+        before(KID_AD_COMPACT_COUNT);
+        hipLaunchKernelGGL(mvk::mv_ad_compact_count, dim3(p.bit_blocks, 2 * p.N), dim3(mvk::kVoteThreads), 0, st,
+                           adbits, p.nwords_pad, p.bit_blocks, adblk);
+        after(KID_AD_COMPACT_COUNT);
+        before(KID_AD_COMPACT_EMIT);
+        hipLaunchKernelGGL(mvk::mv_ad_compact_emit, dim3(p.bit_blocks, 2 * p.N), dim3(mvk::kVoteThreads), 0, st,
+                           adbits, p.nwords_pad, p.bit_blocks, adblk, k_ad, a.add_idx, a.drop_idx, a.vote_bits,
+                           a.ld_bits);
+        after(KID_AD_COMPACT_EMIT);
+        before(KID_AD_LEVELS);
+        hipLaunchKernelGGL(mvk::mv_ad_levels, dim3(p.n_vote_blocks), dim3(mvk::kVoteThreads), 0, st, msum32, p.d,
+                           cntge);
+        after(KID_AD_LEVELS);
+        mask_votes32 = msum32;
+    }
+    // 5. global mask; in plain voting extra workgroups scan the tallies / write the sorted vote lists
+    const bool lists = sorted && !add_drop;
     before(KID_MASK_COUNT);
-    hipLaunchKernelGGL(mvk::mv_mask_count, dim3(p.n_vote_blocks + (sorted ? p.N * p.scan_blocks : 0)),
-                       dim3(mvk::kVoteThreads), 0, st, votes32, p.d, p.N, p.K, cntge, blockcnt, votes,
-                       p.n_vote_blocks, p.scan_blocks, p.nseg, slow, segsel, segpre, blktotal, votethr);
+    hipLaunchKernelGGL(mvk::mv_mask_count, dim3(p.n_vote_blocks + (lists ? p.N * p.scan_blocks : 0)),
+                       dim3(mvk::kVoteThreads), 0, st, mask_votes32, p.d, p.N, p.K, cntge, blockcnt,
+                       add_drop ? nullptr : a.votes, p.n_vote_blocks, p.scan_blocks, p.nseg, slow, segsel, segpre,
+                       blktotal, votethr, add_drop ? 1 : 0);
     after(KID_MASK_COUNT);
     before(KID_MASK_EMIT);
-    hipLaunchKernelGGL(mvk::mv_mask_emit, dim3(p.n_vote_blocks + (sorted ? p.N * p.emit_blocks : 0)),
-                       dim3(mvk::kVoteThreads), 0, st, votes32, p.d, p.K, votethr, blockcnt, mask_idx,
+    hipLaunchKernelGGL(mvk::mv_mask_emit, dim3(p.n_vote_blocks + (lists ? p.N * p.emit_blocks : 0)),
+                       dim3(mvk::kVoteThreads), 0, st, mask_votes32, p.d, p.K, votethr, blockcnt, a.mask_idx,
                        p.n_vote_blocks, p.emit_blocks, cand, p.cap, rowcnt, seg, p.nseg, segpre, blktotal, p.scan_blocks,
-                       kth, tiecut, slow,
-                       worker_idx);
+                       kth, tiecut, slow, a.worker_idx, add_drop ? 0 : 1);
     after(KID_MASK_EMIT);
     // 6. gather + mean + error update
     {
         const float inv_n = 1.0f / (float)p.N;
-        before(KID_GATHER);
         const uint32_t kb = mvk::kGatherThreads / p.N;
+        before(KID_GATHER);
         hipLaunchKernelGGL(mvk::mv_gather_update, dim3((p.K + kb - 1) / kb),
-                           dim3(mvk::kGatherThreads), 0, st, err, ld_e, p.d, p.N, p.K, mask_idx, inv_n,
-                           c->cfg.reduce == MV_REDUCE_MEAN ? 1 : 0, agg_vals);
+                           dim3(mvk::kGatherThreads), 0, st, a.err, a.ld_e, p.d, p.N, p.K, a.mask_idx, inv_n,
+                           c->cfg.reduce == MV_REDUCE_MEAN ? 1 : 0, a.agg_vals);
         after(KID_GATHER);
     }
     c->last_stream = st;
     c->steps_done += 1;
     if (hipGetLastError() != hipSuccess || !ev_ok) return MV_ERR_DEVICE;
     return MV_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+mv_status mv_vote_step(mv_ctx* c, const void* grads, int64_t ld_g, float* err, int64_t ld_e,
+                       uint32_t* worker_idx, uint8_t* votes, uint32_t* mask_idx, float* agg_vals,
+                       void* stream_v)
+{
+    StepArgs a;
+    memset(&a, 0, sizeof a);
+    a.grads = grads; a.ld_g = ld_g; a.err = err; a.ld_e = ld_e;
+    a.worker_idx = worker_idx; a.votes = votes; a.mask_idx = mask_idx; a.agg_vals = agg_vals;
+    const mv_status st = check_common(c, a);
+    if (st != MV_OK) return st;
+    return enqueue_step(c, a, stream_v);
+}
+
+mv_status mv_ad_vote_step(mv_ctx* c, const void* grads, int64_t ld_g, float* err, int64_t ld_e,
+                          int64_t k_ad, uint32_t* vote_bits, int64_t ld_bits, uint8_t* msum,
+                          uint32_t* add_idx, uint32_t* drop_idx, uint32_t* counts,
+                          uint32_t* mask_idx, float* agg_vals, void* stream_v)
+{
+    StepArgs a;
+    memset(&a, 0, sizeof a);
+    a.grads = grads; a.ld_g = ld_g; a.err = err; a.ld_e = ld_e;
+    a.mask_idx = mask_idx; a.agg_vals = agg_vals;
+    a.k_ad = k_ad; a.vote_bits = vote_bits; a.ld_bits = ld_bits; a.msum = msum;
+    a.add_idx = add_idx; a.drop_idx = drop_idx; a.counts = counts;
+    const mv_status st = check_common(c, a);
+    if (st != MV_OK) return st;
+    if (!c->plan.add_drop) return MV_ERR_STATE;              // the context was not begun with MV_FLAG_ADD_DROP
+    if (k_ad < 1 || k_ad > (int64_t)c->plan.K) return MV_ERR_INVALID_ARG;
+    if (!vote_bits || !msum || !add_idx || !drop_idx || !counts) return MV_ERR_INVALID_ARG;
+    if (ld_bits < (int64_t)c->plan.nwords_pad || ld_bits % 4 != 0) return MV_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(vote_bits) & 15) || (reinterpret_cast<uintptr_t>(msum) & 15))
+        return MV_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(add_idx) & 3) || (reinterpret_cast<uintptr_t>(drop_idx) & 3) ||
+        (reinterpret_cast<uintptr_t>(counts) & 3))
+        return MV_ERR_INVALID_ARG;
+    return enqueue_step(c, a, stream_v);
 }
 
 mv_status mv_end(mv_ctx* c)

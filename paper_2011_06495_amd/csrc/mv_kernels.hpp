@@ -191,11 +191,13 @@ __global__ __launch_bounds__(kRowThreads) void mv_pick_threshold(uint32_t* __res
                                                                  uint32_t* __restrict__ tau_bits,
                                                                  uint32_t* __restrict__ row_count,
                                                                  uint32_t* __restrict__ slow_flag,
-                                                                 uint32_t* __restrict__ cnt_ge)
+                                                                 uint32_t* __restrict__ cnt_ge,
+                                                                 uint32_t* __restrict__ ad_count)
 {
     __shared__ uint64_t scan_lds[kRowThreads / kWave + 1];
     __shared__ uint32_t found;
     const uint32_t row = blockIdx.x, t = threadIdx.x;
+    if (ad_count && t < 2) ad_count[2 * row + t] = 0;    // lengths of the row's add / drop candidate lists
     uint32_t* hrow = hist + (size_t)row * kHistBins;
     constexpr int per = kHistBins / kRowThreads;   // bins per thread, descending bin order
     uint32_t c[per];
@@ -671,7 +673,7 @@ __global__ __launch_bounds__(kRowThreads) void mv_row_select(
     const uint32_t* __restrict__ tau_bits,
     uint32_t* __restrict__ kth_out, uint32_t* __restrict__ tie_cut_out,
     uint32_t* __restrict__ worker_idx, uint32_t* __restrict__ votes32,
-    uint32_t* __restrict__ cnt_ge, uint32_t* __restrict__ slow_flag)
+    uint32_t* __restrict__ cnt_ge, uint32_t* __restrict__ slow_flag, int thresholds_only)
 {
     __shared__ SelectLds lds;
     const uint32_t row = blockIdx.x, t = threadIdx.x;
@@ -714,6 +716,24 @@ __global__ __launch_bounds__(kRowThreads) void mv_row_select(
     auto at = [arow](uint64_t i) { return __float_as_uint(arow[i]) & kAbsMask; };
     const KeysInMemory<decltype(at)> src{at, (uint64_t)d};
     const uint32_t kth = block_radix_select(src, K, lds.hist, lds.scan, lds.bcast, take_eq, n_eq);
+    if (thresholds_only) {
+        // add-drop voting only needs the membership test: the tie cut is the take_eq-th
+        // smallest coordinate among the row's ties, selected from memory
+        uint32_t tie_cut = 0xFFFFFFFFu;
+        if (take_eq < n_eq) {
+            uint32_t t_eq, t_n;
+            auto tie_at = [arow, kth](uint64_t i) {
+                return (__float_as_uint(arow[i]) & kAbsMask) == kth ? kAbsMask - (uint32_t)i : 0u;
+            };
+            const KeysInMemory<decltype(tie_at)> ties_src{tie_at, (uint64_t)d};
+            tie_cut = kAbsMask - block_radix_select(ties_src, take_eq, lds.hist, lds.scan, lds.bcast, t_eq, t_n);
+        }
+        if (t == 0) {
+            kth_out[row] = kth;
+            tie_cut_out[row] = tie_cut;
+        }
+        return;
+    }
     uint32_t gt_before = 0, eq_before = 0;
     for (int64_t j0 = 0; j0 < d; j0 += (int64_t)kRowThreads * 4) {
         const int64_t j = j0 + (int64_t)t * 4;
@@ -818,8 +838,25 @@ __global__ __launch_bounds__(kVoteThreads) void mv_row_votes(
 // (in coordinate order) with exactly v* votes.
 __device__ __forceinline__ void vote_threshold(const uint32_t* __restrict__ cnt_ge, uint32_t N,
                                                uint32_t K, uint32_t* lds_lvl /*256*/, uint32_t* lds2,
-                                               uint32_t& vstar, uint32_t& take_eq)
+                                               uint32_t& vstar, uint32_t& take_eq, int exact_levels)
 {
+    if (exact_levels) {
+        // cnt_ge[v] = number of coordinates with EXACTLY v votes, v = 0..N (one set of
+        // counters): walk down from N until K coordinates are covered
+        if (threadIdx.x == 0) {
+            uint32_t above = 0, v = N;
+            while (v > 0 && above + cnt_ge[v] < K) {
+                above += cnt_ge[v];
+                --v;
+            }
+            lds2[0] = v;
+            lds2[1] = K - above;
+        }
+        __syncthreads();
+        vstar = lds2[0];
+        take_eq = lds2[1];
+        return;
+    }
     // cnt_ge holds one set of 256 level counters per worker row; add the rows up
     // (levels 1..N matter), all loads of a thread in flight together
     for (uint32_t v = threadIdx.x; v < 256; v += blockDim.x) lds_lvl[v] = 0;
@@ -893,7 +930,8 @@ __global__ __launch_bounds__(kVoteThreads) void mv_mask_count(const uint32_t* __
                                                               const uint32_t* __restrict__ seg_sel,
                                                               uint32_t* __restrict__ seg_pre,
                                                               uint32_t* __restrict__ blk_total,
-                                                              uint32_t* __restrict__ vote_thr)
+                                                              uint32_t* __restrict__ vote_thr,
+                                                              int exact_levels)
 {
     __shared__ uint32_t lds2[2];
     __shared__ uint32_t lds_lvl[256];
@@ -917,7 +955,7 @@ __global__ __launch_bounds__(kVoteThreads) void mv_mask_count(const uint32_t* __
         w[it] = (j < d) ? *reinterpret_cast<const u32x4*>(votes32 + (j >> 2)) : z;   // padded to 16 bytes with zeros
     }
     uint32_t vstar, take_eq;
-    vote_threshold(cnt_ge, N, K, lds_lvl, lds2, vstar, take_eq);
+    vote_threshold(cnt_ge, N, K, lds_lvl, lds2, vstar, take_eq, exact_levels);
     uint32_t gt = 0, eq = 0;
 #pragma unroll
     for (int it = 0; it < kIt; ++it) {
@@ -929,8 +967,9 @@ __global__ __launch_bounds__(kVoteThreads) void mv_mask_count(const uint32_t* __
 #pragma unroll
                 for (int b = 0; b < 4; ++b) {
                     const uint32_t v = (ww[q] >> (8 * b)) & 255u;
-                    gt += (v > vstar);
-                    eq += (v == vstar);
+                    const bool inside = j + q * 4 + b < d;      // matters when v* is 0
+                    gt += (inside && v > vstar);
+                    eq += (inside && v == vstar);
                 }
             if (votes_out) {
                 if (j + 16 <= d && ((reinterpret_cast<uintptr_t>(votes_out) & 15) == 0)) {
@@ -1050,7 +1089,8 @@ __global__ __launch_bounds__(kVoteThreads) void mv_mask_emit(uint32_t* __restric
                                                              const uint32_t* __restrict__ kth_in,
                                                              const uint32_t* __restrict__ tie_cut_in,
                                                              const uint32_t* __restrict__ slow_flag,
-                                                             uint32_t* __restrict__ worker_idx)
+                                                             uint32_t* __restrict__ worker_idx,
+                                                             int clear_votes)
 {
     __shared__ uint32_t blk_pre[kMaxScanBlocks];
     __shared__ uint64_t scan_lds[kVoteThreads / kWave + 1];
@@ -1077,7 +1117,7 @@ __global__ __launch_bounds__(kVoteThreads) void mv_mask_emit(uint32_t* __restric
         if (j < d) {
             u32x4* p = reinterpret_cast<u32x4*>(votes32 + (j >> 2));
             w[it] = *p;
-            if ((w[it].x | w[it].y | w[it].z | w[it].w) != 0u) *p = z;
+            if (clear_votes && (w[it].x | w[it].y | w[it].z | w[it].w) != 0u) *p = z;
         }
     }
     const uint32_t vstar = vote_thr[0], take_eq = vote_thr[1];   // found by mv_mask_count
@@ -1100,9 +1140,10 @@ __global__ __launch_bounds__(kVoteThreads) void mv_mask_emit(uint32_t* __restric
         uint32_t gt = 0, eq = 0;
 #pragma unroll
         for (int q = 0; q < 16; ++q) {
-            const uint32_t v = (ww[q >> 2] >> (8 * (q & 3))) & 255u;   // zero beyond d: never counted (v* >= 1)
-            gt += (v > vstar);
-            eq += (v == vstar);
+            const uint32_t v = (ww[q >> 2] >> (8 * (q & 3))) & 255u;
+            const bool inside = j + q < d;                             // matters when v* is 0
+            gt += (inside && v > vstar);
+            eq += (inside && v == vstar);
         }
         uint64_t total;
         const uint64_t ex = block_excl_scan64<kVoteThreads>(pack2(gt, eq), scan_lds, total);
@@ -1111,7 +1152,8 @@ __global__ __launch_bounds__(kVoteThreads) void mv_mask_emit(uint32_t* __restric
 #pragma unroll
             for (int q = 0; q < 16; ++q) {
                 const uint32_t v = (ww[q >> 2] >> (8 * (q & 3))) & 255u;
-                const bool is_gt = v > vstar, is_eq = v == vstar;
+                const bool inside = j + q < d;
+                const bool is_gt = inside && v > vstar, is_eq = inside && v == vstar;
                 if (is_gt || (is_eq && e0 < take_eq)) {
                     const uint32_t pos = g0 + min(e0, take_eq);
                     if (pos < K) mask_idx[pos] = (uint32_t)(j + q);
@@ -1165,6 +1207,312 @@ __global__ __launch_bounds__(kGatherThreads) void mv_gather_update(float* __rest
             agg[kk] = apply_scale ? s * scale : s;
         }
     }
+}
+
+// ----------------------------------------------------------------------------
+// 7. majority voting with add-drop (Algorithm 2)
+// ----------------------------------------------------------------------------
+// State, owned by the caller: vote_bits (row n = the bitmap of M~_n, the worker's
+// standing vote) and msum (one byte per coordinate, M^sum = the sum of the
+// standing votes).  After mv_row_select, membership of coordinate j in a row's
+// plain top-K is a local test on (|a[n][j]|, j) against (kth, tie_cut), so
+//   A = top-K and not in the standing vote   -> candidates for addition
+//   D = in the standing vote and not top-K   -> candidates for removal
+// are gathered into two lists per row; the K_ad largest of A and the K_ad
+// smallest of D are selected exactly (ties to the lowest coordinate), applied to
+// scratch bitmaps and to msum, and the scratch bitmaps are compacted in
+// coordinate order into the sorted add / drop lists while the standing vote is
+// updated.
+
+// One workgroup-wide reservation: every thread brings `n_mine` entries; returns the
+// position of the thread's first entry in the row's list (the list counter is bumped
+// once per workgroup).  All threads of the workgroup must call it.
+__device__ __forceinline__ uint32_t reserve_in_list(uint32_t n_mine, uint32_t* __restrict__ counter,
+                                                    uint64_t* scan_lds, uint32_t* bcast)
+{
+    uint64_t total;
+    const uint64_t ex = block_excl_scan64<kVoteThreads>(n_mine, scan_lds, total);
+    if (threadIdx.x == 0) bcast[0] = total ? atomicAdd(counter, (uint32_t)total) : 0u;
+    __syncthreads();
+    const uint32_t base = bcast[0];
+    __syncthreads();
+    return base + (uint32_t)ex;
+}
+
+__device__ __forceinline__ bool vote_bit(const uint32_t* __restrict__ bits_row, uint32_t j)
+{
+    return (bits_row[j >> 5] >> (j & 31u)) & 1u;
+}
+
+// A-lists.  Rows whose top-K came from the candidate list: one thread per candidate.
+// Rows selected from memory (slow_flag == 1): the whole row is read.
+__global__ __launch_bounds__(kVoteThreads) void mv_ad_collect_add(
+    const float* __restrict__ e, int64_t ld_e, int64_t d,
+    const u32x2* __restrict__ cand, uint32_t cap, const uint32_t* __restrict__ row_count,
+    const uint32_t* __restrict__ kth_in, const uint32_t* __restrict__ tie_cut_in,
+    const uint32_t* __restrict__ slow_flag, const uint32_t* __restrict__ vote_bits, int64_t ld_bits,
+    u32x2* __restrict__ a_list, uint32_t* __restrict__ ad_count)
+{
+    __shared__ uint64_t scan_lds[kVoteThreads / kWave + 1];
+    __shared__ uint32_t bcast[1];
+    const uint32_t row = blockIdx.y, t = threadIdx.x;
+    const uint32_t kth = kth_in[row], tie_cut = tie_cut_in[row];
+    const uint32_t* bits = vote_bits + (int64_t)row * ld_bits;
+    u32x2* arow = a_list + (size_t)row * cap;
+    uint32_t* counter = ad_count + 2 * row;
+    if (slow_flag[row] == 1u) {
+        const float* xrow = e + (int64_t)row * ld_e;
+        for (int64_t j0 = (int64_t)blockIdx.x * kVoteThreads; j0 < d; j0 += (int64_t)gridDim.x * kVoteThreads) {
+            const int64_t j = j0 + t;
+            u32x2 c = {0u, 0u};
+            bool in_a = false;
+            if (j < d) {
+                c.x = __float_as_uint(xrow[j]) & kAbsMask;
+                c.y = (uint32_t)j;
+                in_a = is_taken(c, kth, tie_cut) && !vote_bit(bits, c.y);
+            }
+            const uint32_t pos = reserve_in_list(in_a ? 1u : 0u, counter, scan_lds, bcast);
+            if (in_a && pos < cap) arow[pos] = c;
+        }
+        return;
+    }
+    const uint32_t C = row_count[row];
+    const u32x2* crow = cand + (size_t)row * cap;
+    for (uint64_t i0 = (uint64_t)blockIdx.x * kVoteThreads; i0 < C; i0 += (uint64_t)gridDim.x * kVoteThreads) {
+        const uint64_t i = i0 + t;
+        u32x2 c = {0u, 0u};
+        bool in_a = false;
+        if (i < C) {
+            c = crow[i];
+            in_a = is_taken(c, kth, tie_cut) && !vote_bit(bits, c.y);
+        }
+        const uint32_t pos = reserve_in_list(in_a ? 1u : 0u, counter, scan_lds, bcast);
+        if (in_a && pos < cap) arow[pos] = c;
+    }
+}
+
+// D-lists: the standing vote's bitmap is scanned, 4 words per thread; a set
+// coordinate that is not in the row's top-K goes to the list with the
+// complemented magnitude, so that "largest first" selects the smallest magnitudes.
+__global__ __launch_bounds__(kVoteThreads) void mv_ad_collect_drop(
+    const float* __restrict__ e, int64_t ld_e, int64_t d,
+    const uint32_t* __restrict__ kth_in, const uint32_t* __restrict__ tie_cut_in,
+    const uint32_t* __restrict__ vote_bits, int64_t ld_bits, uint32_t nwords,
+    u32x2* __restrict__ d_list, uint32_t cap_d, uint32_t* __restrict__ ad_count)
+{
+    __shared__ uint64_t scan_lds[kVoteThreads / kWave + 1];
+    __shared__ uint32_t bcast[1];
+    const uint32_t row = blockIdx.y, t = threadIdx.x;
+    const uint32_t kth = kth_in[row], tie_cut = tie_cut_in[row];
+    const float* xrow = e + (int64_t)row * ld_e;
+    const uint32_t w0 = (blockIdx.x * kVoteThreads + t) * 4;
+    uint32_t w[4] = {0, 0, 0, 0};
+    if (w0 < nwords) {                            // rows are padded to a multiple of 4 words
+        const u32x4 v = *reinterpret_cast<const u32x4*>(vote_bits + (int64_t)row * ld_bits + w0);
+        w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
+    }
+    uint32_t n_mine = 0;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        uint32_t m = w[q];
+        while (m) {
+            const uint32_t b = __ffs((int)m) - 1;
+            m &= m - 1;
+            const uint32_t j = (w0 + q) * 32 + b;
+            if ((int64_t)j < d) {
+                u32x2 c;
+                c.x = __float_as_uint(xrow[j]) & kAbsMask;
+                c.y = j;
+                if (is_taken(c, kth, tie_cut)) w[q] &= ~(1u << b);   // stays in the vote: not a drop candidate
+            } else {
+                w[q] &= ~(1u << b);
+            }
+        }
+        n_mine += __popc(w[q]);
+    }
+    uint32_t pos = reserve_in_list(n_mine, ad_count + 2 * row + 1, scan_lds, bcast);
+    u32x2* drow = d_list + (size_t)row * cap_d;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        uint32_t m = w[q];
+        while (m) {
+            const uint32_t b = __ffs((int)m) - 1;
+            m &= m - 1;
+            const uint32_t j = (w0 + q) * 32 + b;
+            if (pos < cap_d) {
+                u32x2 c;
+                c.x = kAbsMask - (__float_as_uint(xrow[j]) & kAbsMask);
+                c.y = j;
+                drow[pos] = c;
+            }
+            ++pos;
+        }
+    }
+}
+
+// Workgroup (0, n): the K_ad first of row n's A-list under (magnitude desc,
+// coordinate asc); workgroup (1, n): the same for the D-list, whose keys are the
+// complemented magnitudes.  Result: ad_thr[n][2*which] = key threshold,
+// [2*which+1] = tie cut (membership test as for the top-K), and
+// counts_out[2n + which] = how many are taken = min(K_ad, list length).
+__global__ __launch_bounds__(kRowThreads) void mv_ad_select(
+    const u32x2* __restrict__ a_list, uint32_t cap_a, const u32x2* __restrict__ d_list, uint32_t cap_d,
+    const uint32_t* __restrict__ ad_count, uint32_t k_ad, const uint32_t* __restrict__ tau_bits,
+    const uint32_t* __restrict__ slow_flag, uint32_t* __restrict__ ad_thr, uint32_t* __restrict__ counts_out)
+{
+    __shared__ SelectLds lds;
+    const uint32_t which = blockIdx.x, row = blockIdx.y, t = threadIdx.x;
+    const u32x2* list = which ? d_list + (size_t)row * cap_d : a_list + (size_t)row * cap_a;
+    const uint32_t len = min(ad_count[2 * row + which], which ? cap_d : cap_a);
+    uint32_t kth, tie_cut;
+    if (len == 0) {
+        kth = 0xFFFFFFFFu;                        // nothing passes the membership test
+        tie_cut = 0;
+    } else if (len <= k_ad) {
+        kth = 0;                                  // everything passes
+        tie_cut = 0xFFFFFFFFu;
+    } else {
+        uint32_t path;
+        auto at = [list](uint64_t i) { return list[i].x; };
+        const KeysInMemory<decltype(at)> src{at, len};
+        // every A-list magnitude is at least the row's estimate tau when the row's top-K
+        // came from its candidate list; the D-list has no such bound
+        const uint32_t tau = (which || slow_flag[row] == 1u) ? 0u : tau_bits[row];
+        select_among_candidates(src, list, len, k_ad, tau, lds, kth, tie_cut, path);
+    }
+    if (t == 0) {
+        ad_thr[4 * row + 2 * which] = kth;
+        ad_thr[4 * row + 2 * which + 1] = tie_cut;
+        counts_out[2 * row + which] = min(len, k_ad);
+    }
+}
+
+// Applies the selected additions and removals: marks them in the scratch bitmaps
+// (add: row 2n, drop: row 2n+1) and moves msum by +1 / -1 (bytes packed four to a
+// word; a byte never carries because 0 <= msum <= N <= 255 holds before and after).
+__global__ __launch_bounds__(kVoteThreads) void mv_ad_apply(
+    const u32x2* __restrict__ a_list, uint32_t cap_a, const u32x2* __restrict__ d_list, uint32_t cap_d,
+    const uint32_t* __restrict__ ad_count, const uint32_t* __restrict__ ad_thr,
+    uint32_t* __restrict__ ad_bits, uint32_t nwords_pad, uint32_t* __restrict__ msum32)
+{
+    const uint32_t row = blockIdx.y;
+#pragma unroll
+    for (int which = 0; which < 2; ++which) {
+        const u32x2* list = which ? d_list + (size_t)row * cap_d : a_list + (size_t)row * cap_a;
+        const uint32_t len = min(ad_count[2 * row + which], which ? cap_d : cap_a);
+        const uint32_t kth = ad_thr[4 * row + 2 * which], tie_cut = ad_thr[4 * row + 2 * which + 1];
+        uint32_t* bits = ad_bits + (size_t)(2 * row + which) * nwords_pad;
+        for (uint32_t i = blockIdx.x * kVoteThreads + threadIdx.x; i < len; i += gridDim.x * kVoteThreads) {
+            const u32x2 c = list[i];
+            if (is_taken(c, kth, tie_cut)) {
+                atomicOr(&bits[c.y >> 5], 1u << (c.y & 31u));
+                const uint32_t one = 1u << ((c.y & 3u) * 8u);
+                if (which) atomicSub(&msum32[c.y >> 2], one);
+                else       atomicAdd(&msum32[c.y >> 2], one);
+            }
+        }
+    }
+}
+
+// Ordered compaction of the 2N scratch bitmaps, in two kernels: set bits per block of
+// 1024 words, then (prefix over the blocks before + scan inside the block) each
+// thread writes its set coordinates in ascending order.  The second kernel also
+// clears the scratch words and folds them into the standing vote.
+__global__ __launch_bounds__(kVoteThreads) void mv_ad_compact_count(const uint32_t* __restrict__ ad_bits,
+                                                                    uint32_t nwords_pad, uint32_t nblk,
+                                                                    uint32_t* __restrict__ blk_cnt)
+{
+    __shared__ uint64_t scan_lds[kVoteThreads / kWave + 1];
+    const uint32_t r = blockIdx.y;
+    const uint32_t w0 = (blockIdx.x * kVoteThreads + threadIdx.x) * 4;
+    uint32_t n = 0;
+    if (w0 < nwords_pad) {
+        const u32x4 v = *reinterpret_cast<const u32x4*>(ad_bits + (size_t)r * nwords_pad + w0);
+        n = __popc(v.x) + __popc(v.y) + __popc(v.z) + __popc(v.w);
+    }
+    uint64_t total;
+    (void)block_excl_scan64<kVoteThreads>(n, scan_lds, total);
+    if (threadIdx.x == 0) blk_cnt[(size_t)r * nblk + blockIdx.x] = (uint32_t)total;
+}
+
+__global__ __launch_bounds__(kVoteThreads) void mv_ad_compact_emit(uint32_t* __restrict__ ad_bits,
+                                                                   uint32_t nwords_pad, uint32_t nblk,
+                                                                   const uint32_t* __restrict__ blk_cnt,
+                                                                   uint32_t k_ad,
+                                                                   uint32_t* __restrict__ add_idx,
+                                                                   uint32_t* __restrict__ drop_idx,
+                                                                   uint32_t* __restrict__ vote_bits,
+                                                                   int64_t ld_bits)
+{
+    __shared__ uint64_t scan_lds[kVoteThreads / kWave + 1];
+    const uint32_t r = blockIdx.y, row = r >> 1, which = r & 1u;
+    uint64_t mine = 0;
+    for (uint32_t b = threadIdx.x; b < blockIdx.x; b += kVoteThreads) mine += blk_cnt[(size_t)r * nblk + b];
+    uint64_t before;
+    (void)block_excl_scan64<kVoteThreads>(mine, scan_lds, before);
+    __syncthreads();
+    const uint32_t w0 = (blockIdx.x * kVoteThreads + threadIdx.x) * 4;
+    uint32_t w[4] = {0, 0, 0, 0};
+    if (w0 < nwords_pad) {
+        u32x4* p = reinterpret_cast<u32x4*>(ad_bits + (size_t)r * nwords_pad + w0);
+        const u32x4 v = *p;
+        w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
+        if ((v.x | v.y | v.z | v.w) != 0u) {
+            const u32x4 z = {0u, 0u, 0u, 0u};
+            *p = z;
+        }
+    }
+    const uint32_t n = __popc(w[0]) + __popc(w[1]) + __popc(w[2]) + __popc(w[3]);
+    uint64_t total;
+    uint32_t pos = (uint32_t)(before + block_excl_scan64<kVoteThreads>(n, scan_lds, total));
+    uint32_t* out = (which ? drop_idx : add_idx) + (size_t)row * k_ad;
+    uint32_t* vrow = vote_bits + (int64_t)row * ld_bits;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        uint32_t m = w[q];
+        if (m) {
+            // additions and removals never touch the same bit, but may share a word
+            if (which) atomicAnd(&vrow[w0 + q], ~m);
+            else       atomicOr(&vrow[w0 + q], m);
+        }
+        while (m) {
+            const uint32_t b = __ffs((int)m) - 1;
+            m &= m - 1;
+            if (pos < k_ad) out[pos] = (w0 + q) * 32 + b;
+            ++pos;
+        }
+    }
+}
+
+// Histogram of the vote levels of msum (one byte per coordinate, values 0..N):
+// lvl_cnt[v] = number of coordinates with exactly v votes.
+__global__ __launch_bounds__(kVoteThreads) void mv_ad_levels(const uint32_t* __restrict__ msum32, int64_t d,
+                                                             uint32_t* __restrict__ lvl_cnt)
+{
+    __shared__ uint32_t h[256];
+    h[threadIdx.x] = 0;
+    __syncthreads();
+    const int64_t base = (int64_t)blockIdx.x * kVoteBlock;
+    uint32_t zeros = 0;                           // most coordinates have no vote
+#pragma unroll
+    for (int it = 0; it < kVoteBlock / (kVoteThreads * 16); ++it) {
+        const int64_t j = base + ((int64_t)it * kVoteThreads + threadIdx.x) * 16;
+        if (j < d) {
+            const u32x4 w = *reinterpret_cast<const u32x4*>(msum32 + (j >> 2));
+            const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+            if ((w.x | w.y | w.z | w.w) == 0u) {
+                zeros += (uint32_t)min((int64_t)16, d - j);
+            } else {
+#pragma unroll
+                for (int q = 0; q < 16; ++q)
+                    if (j + q < d) atomicAdd(&h[(ww[q >> 2] >> (8 * (q & 3))) & 255u], 1u);
+            }
+        }
+    }
+    if (zeros) atomicAdd(&h[0], zeros);
+    __syncthreads();
+    const uint32_t c = h[threadIdx.x];
+    if (c) atomicAdd(&lvl_cnt[threadIdx.x], c);
 }
 
 // ----------------------------------------------------------------------------

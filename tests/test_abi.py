@@ -49,7 +49,7 @@ def test_workspace_bytes_and_invalid_configs(lib):
     wrong_size = B.make_config(4, 100, 10)
     wrong_size.struct_size = 48
     reserved = B.make_config(4, 100, 10)
-    reserved.reserved = 1
+    reserved.flags = 2
     for cfg in bad + [wrong_size, reserved]:
         assert B.mv_workspace_bytes(cfg) == 0
         h = ctypes.c_void_p()
