@@ -60,6 +60,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="C4", choices=["C1", "C2", "C3", "C4", "C5"])
     ap.add_argument("--grad-sets", type=int, default=2, help="distinct gradient matrices cycled over")
+    ap.add_argument("--scheme", default="mv", choices=["mv", "ad"],
+                    help="mv: majority voting (Algorithm 1); ad: majority voting with add-drop (Algorithm 2), "
+                         "a full first vote untimed, then K_ad = K/10 per step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-worker-idx", action="store_true",
                     help="do not request the per-worker sorted vote lists (optional output)")
@@ -109,12 +112,26 @@ def main():
     votes = torch.zeros(d, dtype=torch.uint8, device=dev)
     mask = torch.zeros(K, dtype=torch.int32, device=dev)
     agg = torch.zeros(K, dtype=torch.float32, device=dev)
-    ctx = B.mv_begin(B.make_config(N, d, K, B.MV_BF16 if bf16 else B.MV_F32))
+    ad = args.scheme == "ad"
+    ctx = B.mv_begin(B.make_config(N, d, K, B.MV_BF16 if bf16 else B.MV_F32,
+                                   flags=B.MV_FLAG_ADD_DROP if ad else 0))
     stream = torch.cuda.current_stream(dev)
+    k_ad = max(1, K // 10)
+    if ad:
+        ld_bits = ((d + 31) // 32 + 3) // 4 * 4
+        vote_bits = torch.zeros((N, ld_bits), dtype=torch.int32, device=dev)
+        msum = torch.zeros((d + 15) // 16 * 16, dtype=torch.uint8, device=dev)
+        add_idx = torch.zeros((N, K), dtype=torch.int32, device=dev)
+        drop_idx = torch.zeros((N, K), dtype=torch.int32, device=dev)
+        counts = torch.zeros(2 * N, dtype=torch.int32, device=dev)
 
     def step(i):
-        B.mv_vote_step(ctx, g_dev[i % len(g_dev)], e_dev, widx, votes, mask, agg, stream=stream,
-                       ld_g=ld_g, ld_e=ld_e)
+        if ad:   # step 0 is a full vote from the empty state, every later step changes at most K/10 votes
+            B.mv_ad_vote_step(ctx, g_dev[i % len(g_dev)], e_dev, K if i == 0 else k_ad, vote_bits, msum,
+                              add_idx, drop_idx, counts, mask, agg, stream=stream, ld_g=ld_g, ld_e=ld_e)
+        else:
+            B.mv_vote_step(ctx, g_dev[i % len(g_dev)], e_dev, widx, votes, mask, agg, stream=stream,
+                           ld_g=ld_g, ld_e=ld_e)
 
     # ---- step 0 result kept for the check against the oracle
     step(0)
@@ -199,19 +216,24 @@ def main():
         e0 = np.zeros((N, d), np.float32)
         log("timing the oracle on one step of %s with %d threads ..." % (w.name, threads))
         t1 = time.perf_counter()
-        ref = mv_oracle.vote_step(g_host0, e0, K, threads=threads)
+        if ad:
+            ref = mv_oracle.ad_vote_step(g_host0, e0, K, K, np.zeros((N, d), np.uint8), np.zeros(d, np.uint8),
+                                         threads=threads)
+        else:
+            ref = mv_oracle.vote_step(g_host0, e0, K, threads=threads)
         t_or = time.perf_counter() - t1
         oracle_agrees = bool(np.array_equal(ref.mask_idx, mask0) and
                              np.array_equal(ref.agg.view(np.uint32), agg0.view(np.uint32)))
         cpu_baseline = {"value": round(coords / t_or, 1), "unit": "coords/s", "cores": threads,
                         "kind": "oracle", "seconds": round(t_or, 2),
-                        "sample": "one full vote step of %s (all %d rows, d=%d), step-0 inputs" % (w.name, N, d)}
+                        "sample": "one full %s of %s (all %d rows, d=%d), step-0 inputs" %
+                                  ("add-drop step (first, full vote)" if ad else "vote step", w.name, N, d)}
 
     B.mv_end(ctx)
     B.mv_release(ctx)
 
     out = {
-        "metric": "vote-step throughput (N*d coords/sec), 1 GPU",
+        "metric": "vote-step throughput (N*d coords/sec), 1 GPU" + (", add-drop voting" if ad else ""),
         "value": round(value, 1),
         "unit": "coords/s",
         "n_gpus": 1,
@@ -226,7 +248,9 @@ def main():
         "config": {"workload": "%s: N=%d d=%d K=%d grads=%s, %s, error feedback carried" %
                                (w.name, N, d, K, w.grad_dtype, w.kind),
                    "N": N, "d": d, "K": K, "grad_sets_cycled": len(g_dev),
-                   "outputs": "mask_idx, agg_vals, votes" + ("" if args.no_worker_idx else ", worker_idx")},
+                   "scheme": "majority voting with add-drop, K_ad=%d" % k_ad if ad else "majority voting",
+                   "outputs": "mask_idx, agg_vals, add/drop lists, standing votes, vote sum" if ad else
+                              "mask_idx, agg_vals, votes" + ("" if args.no_worker_idx else ", worker_idx")},
         "step_hbm_frac_algorithmic": round(step_frac, 4),
         "copy_probe_GBs": round(copy_gbs, 1),
         "roofline": roofline,

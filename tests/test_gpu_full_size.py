@@ -76,3 +76,41 @@ def test_c4_full_lattice_ties_five_steps(oracle):
 @pytest.mark.timeout(1200)
 def test_c5_full_bf16(oracle):
     run_full(oracle, W.C5, 10)
+
+
+# ---- majority voting with add-drop (Algorithm 2) at full size
+
+def run_full_ad(oracle, w, k_ads):
+    from tests.test_gpu_add_drop import GpuAdStepper
+    threads = min(16, oracle.max_threads())
+    gs = GpuAdStepper(w.N, w.d, w.K, max(k_ads), bf16=(w.grad_dtype == "bf16"))
+    try:
+        vote = np.zeros((w.N, w.d), np.uint8)
+        msum = np.zeros(w.d, np.uint8)
+        e = W.zero_error(w)
+        for t, k_ad in enumerate(k_ads):
+            t0 = time.time()
+            g = W.gradients(w, t, threads=threads)
+            gs.step(g, k_ad)
+            ref = oracle.ad_vote_step(g, e, w.K, k_ad, vote, msum, threads=threads)
+            gs.compare(ref, "%s add-drop full size, step %d" % (w.name, t))
+            vote, msum, e = ref.vote, ref.msum, ref.err
+            say("%s add-drop step %d (K_ad=%d) ok (%.1f s), added %s.. dropped %s.." %
+                (w.name, t, k_ad, time.time() - t0, [x.size for x in ref.add_idx[:3]],
+                 [x.size for x in ref.drop_idx[:3]]))
+    finally:
+        gs.close()
+
+
+@pytest.mark.timeout(1200)
+def test_add_drop_c4_full(oracle):
+    # a full first vote, then the regime phi_ad = phi / 10 (Sec. 4.2)
+    k_ad = W.C4.K // 10
+    run_full_ad(oracle, W.C4, [W.C4.K, k_ad, k_ad, k_ad])
+
+
+@pytest.mark.timeout(1200)
+def test_add_drop_paper_regime_full(oracle):
+    # the paper's setting: ResNet-18 size, N = 10 workers, phi = 1e-2, phi_ad = 1e-3 (Sec. 4.1, 4.2)
+    w = W.C2.with_size(W.C2.d, K=111740)
+    run_full_ad(oracle, w, [w.K, 11174, 11174])
