@@ -407,6 +407,94 @@ int mvo_ad_vote_step(const void* grads, int64_t ld_g, int32_t grad_is_bf16,
 }
 
 /* ------------------------------------------------------------------ */
+/* sparse position code (Sec. 4.3.1)                                    */
+/* ------------------------------------------------------------------ */
+
+/*
+ * The vector's d coordinates are cut into blocks of block_len = 1/phi
+ * coordinates.  The stream lists, block after block, every non-zero position
+ * of the block as a 1 bit followed by the position inside the block in
+ * B = ceil(log2(block_len)) bits, and closes the block with a 0 bit.
+ *
+ * Readings where Sec. 4.3.1 is silent: the in-block position is written most
+ * significant bit first; every block, also an empty one and the last (possibly
+ * shorter) one, gets its closing 0, so the stream has exactly
+ * n * (1 + B) + ceil(d / block_len) bits -- with n = phi * d positions that is
+ * log(1/phi) + 2 bits per position, the figure of Sec. 2.1; bit k of the stream
+ * is bit (k % 32) of 32-bit word k / 32; unused bits of the last word are 0.
+ */
+int32_t mvo_codec_offset_bits(int64_t block_len)
+{
+    int32_t b = 0;
+    while (((int64_t)1 << b) < block_len) ++b;
+    return b;
+}
+
+static void put_bit(uint32_t* words, uint64_t k, uint32_t bit)
+{
+    if (bit) words[k >> 5] |= (uint32_t)1 << (k & 31);
+}
+
+static uint32_t get_bit(const uint32_t* words, uint64_t k) { return (words[k >> 5] >> (k & 31)) & 1u; }
+
+/* Encoder: writes the stream of the ascending positions idx[0..n) and returns its
+ * length in bits, or -1 on bad arguments (positions not ascending or >= d, or
+ * `words` too short: max_words 32-bit words are available and are zeroed first). */
+int64_t mvo_codec_encode(const uint32_t* idx, int64_t n, int64_t d, int64_t block_len,
+                         uint32_t* words, int64_t max_words)
+{
+    if (d < 1 || block_len < 1 || n < 0 || n > d) return -1;
+    const int32_t B = mvo_codec_offset_bits(block_len);
+    const int64_t n_blocks = (d + block_len - 1) / block_len;
+    const uint64_t total = (uint64_t)n * (uint64_t)(1 + B) + (uint64_t)n_blocks;
+    if ((int64_t)((total + 31) / 32) > max_words) return -1;
+    memset(words, 0, (size_t)max_words * sizeof(uint32_t));
+    uint64_t k = 0;
+    int64_t i = 0;
+    for (int64_t b = 0; b < n_blocks; ++b) {
+        const int64_t lo = b * block_len, hi = lo + block_len;
+        while (i < n && (int64_t)idx[i] < hi) {
+            if ((int64_t)idx[i] < lo || (int64_t)idx[i] >= d) return -1;     /* not ascending / out of range */
+            if (i > 0 && idx[i] <= idx[i - 1]) return -1;
+            const uint32_t off = (uint32_t)((int64_t)idx[i] - lo);
+            put_bit(words, k++, 1);                                           /* a position follows */
+            for (int32_t q = B - 1; q >= 0; --q) put_bit(words, k++, (off >> q) & 1u);
+            ++i;
+        }
+        put_bit(words, k++, 0);                                               /* end of block */
+    }
+    if (i != n || k != total) return -1;
+    return (int64_t)total;
+}
+
+/* Decoder, as the receiver of Sec. 4.3.1 reads the stream: a 1 bit -> read the
+ * next B bits as the position inside the current block; a 0 bit -> next block;
+ * until the cursor reaches the end of the stream.  Returns the number of
+ * positions written to idx_out, or -1 (more than max_n positions, a position
+ * outside its block or the vector, or a truncated code). */
+int64_t mvo_codec_decode(const uint32_t* words, int64_t n_bits, int64_t d, int64_t block_len,
+                         uint32_t* idx_out, int64_t max_n)
+{
+    if (d < 1 || block_len < 1 || n_bits < 0) return -1;
+    const int32_t B = mvo_codec_offset_bits(block_len);
+    int64_t block = 0, n = 0;
+    uint64_t k = 0;
+    while (k < (uint64_t)n_bits) {
+        if (get_bit(words, k++)) {
+            if (k + (uint64_t)B > (uint64_t)n_bits) return -1;
+            uint32_t off = 0;
+            for (int32_t q = 0; q < B; ++q) off = (off << 1) | get_bit(words, k++);
+            const int64_t pos = block * block_len + (int64_t)off;
+            if ((int64_t)off >= block_len || pos >= d || n >= max_n) return -1;
+            idx_out[n++] = (uint32_t)pos;
+        } else {
+            ++block;
+        }
+    }
+    return n;
+}
+
+/* ------------------------------------------------------------------ */
 /* communication-load arithmetic (Sec. 2.1 and Sec. 4.4), reporting only */
 /* ------------------------------------------------------------------ */
 

@@ -62,6 +62,12 @@ def lib() -> ctypes.CDLL:
         L.mvo_ad_vote_step.argtypes = [vp, i64, i32, vp, i64, i32, i64, i64, i64, i32, vp, vp, vp, vp, vp, vp, vp,
                                        vp, vp, i32]
         L.mvo_ad_vote_step.restype = i32
+        L.mvo_codec_offset_bits.argtypes = [i64]
+        L.mvo_codec_offset_bits.restype = i32
+        L.mvo_codec_encode.argtypes = [vp, i64, i64, i64, vp, i64]
+        L.mvo_codec_encode.restype = i64
+        L.mvo_codec_decode.argtypes = [vp, i64, i64, i64, vp, i64]
+        L.mvo_codec_decode.restype = i64
         L.mvo_bits_per_position.argtypes = [dbl]
         L.mvo_bits_per_position.restype = i32
         L.mvo_q_val.argtypes = [dbl, dbl, dbl]
@@ -219,6 +225,38 @@ def ad_vote_step(grads: np.ndarray, err: np.ndarray, K: int, K_ad: int, vote: np
         raise ValueError("mvo_ad_vote_step rejected its arguments or state")
     return AdStepResult(widx, [add[n, : n_add[n]].copy() for n in range(N)],
                         [drop[n, : n_drop[n]].copy() for n in range(N)], vt, ms, m, agg, e)
+
+
+# ---------------------------------------------------------------- sparse position code (Sec. 4.3.1)
+
+def codec_offset_bits(block_len: int) -> int:
+    return int(lib().mvo_codec_offset_bits(int(block_len)))
+
+
+def codec_stream_bits(n: int, d: int, block_len: int) -> int:
+    """Length of the stream of n positions: n (1 + B) + number of blocks."""
+    return n * (1 + codec_offset_bits(block_len)) + (d + block_len - 1) // block_len
+
+
+def codec_encode(idx: np.ndarray, d: int, block_len: int):
+    """Returns (words, n_bits): the stream as uint32 words, bit k = bit k % 32 of word k // 32."""
+    idx = _c(idx, np.uint32)
+    n_bits = codec_stream_bits(idx.size, d, block_len)
+    words = np.zeros((n_bits + 31) // 32 + 1, np.uint32)
+    got = lib().mvo_codec_encode(_ptr(idx), idx.size, d, block_len, _ptr(words), words.size)
+    if got < 0:
+        raise ValueError("mvo_codec_encode rejected its arguments")
+    assert got == n_bits
+    return words, int(got)
+
+
+def codec_decode(words: np.ndarray, n_bits: int, d: int, block_len: int, max_n: int) -> np.ndarray:
+    words = _c(words, np.uint32)
+    out = np.empty(max(1, max_n), np.uint32)
+    n = lib().mvo_codec_decode(_ptr(words), n_bits, d, block_len, _ptr(out), max_n)
+    if n < 0:
+        raise ValueError("mvo_codec_decode: malformed stream")
+    return out[:n].copy()
 
 
 # ---------------------------------------------------------------- comm load
