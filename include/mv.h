@@ -192,6 +192,55 @@ mv_status mv_step_kernel_ms(mv_ctx* ctx, int32_t steps_back, float* ms, int32_t 
 mv_status mv_last_step_row_stats(mv_ctx* ctx, uint32_t* cand_count,
                                  uint32_t* threshold_bits, uint32_t* slow_path);
 
+/* ---- sparse position code (paper: Sec. 4.3.1) ------------------------------ */
+
+/*
+ * The code of an ascending list of n coordinates of a d-vector: the coordinates
+ * are cut into blocks of block_len = 1/phi; per listed coordinate a 1 bit and the
+ * position inside its block in B = ceil(log2(block_len)) bits, most significant
+ * first; a 0 bit closes every block (also empty ones and the last, shorter one).
+ * Bit k of a stream is bit k % 32 of its 32-bit word k / 32; unused bits of the
+ * last word are 0.  A stream has n (1 + B) + ceil(d / block_len) bits, i.e.
+ * log2(1/phi) + 2 bits per coordinate when n = phi d (Sec. 2.1).
+ * Returns that length in bits (host arithmetic), 0 for invalid arguments.
+ */
+uint64_t mv_codec_stream_bits(int64_t n, int64_t d, int64_t block_len);
+
+/* Bytes of device scratch mv_codec_decode needs for `rows` streams of up to max_bits bits. */
+size_t mv_codec_scratch_bytes(uint64_t max_bits, int32_t rows);
+
+/*
+ * Encodes `rows` lists at once (for instance the N workers' votes), enqueued on
+ * `stream`; allocates nothing.
+ *   idx       device, row r = idx + r * ld_idx: ascending coordinates < d
+ *   counts    device or NULL: the length of row r is counts[r * counts_stride]
+ *             (<= n); NULL: every row holds n coordinates
+ *   streams   device out, row r = streams + r * ld_words; ld_words >=
+ *             ceil(mv_codec_stream_bits(n, d, block_len) / 32); words beyond a
+ *             row's stream are left untouched
+ *   n_bits    device out, rows entries: the length of each stream in bits
+ * Lists that are not ascending or reach beyond d give an unspecified stream (no
+ * out-of-bounds access).  Errors: MV_ERR_INVALID_ARG, MV_ERR_DEVICE.
+ */
+mv_status mv_codec_encode(const uint32_t* idx, int64_t ld_idx, const uint32_t* counts, int64_t counts_stride,
+                          int64_t n, int32_t rows, int64_t d, int64_t block_len, uint32_t* streams,
+                          int64_t ld_words, uint64_t* n_bits, void* stream);
+
+/*
+ * Decodes `rows` streams as the receiver of Sec. 4.3.1 reads them (a 1 bit: the
+ * next B bits are a position inside the current block; a 0 bit: next block).
+ *   streams, ld_words   device, as written by mv_codec_encode
+ *   n_bits    device, rows entries: the length of each stream in bits (<= max_bits)
+ *   idx_out   device out, row r = idx_out + r * ld_idx, room for max_n coordinates
+ *   counts_out device out, rows entries: coordinates found in each stream (those
+ *             beyond max_n are counted but not written)
+ *   scratch   device, >= mv_codec_scratch_bytes(max_bits, rows) bytes
+ * Malformed streams give unspecified lists (no out-of-bounds access).
+ */
+mv_status mv_codec_decode(const uint32_t* streams, int64_t ld_words, const uint64_t* n_bits, uint64_t max_bits,
+                          int32_t rows, int64_t d, int64_t block_len, uint32_t* idx_out, int64_t ld_idx,
+                          int64_t max_n, uint32_t* counts_out, void* scratch, size_t scratch_bytes, void* stream);
+
 /*
  * Measurement aid, not part of the method: enqueues a plain streaming copy of
  * `bytes` (a multiple of 16; dst and src 16-byte aligned DEVICE pointers, not

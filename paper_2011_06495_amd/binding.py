@@ -23,6 +23,7 @@ ABI_SYMBOLS = (
     "mv_workspace_bytes", "mv_begin", "mv_vote_step", "mv_ad_vote_step", "mv_end", "mv_release", "mv_status_string",
     "mv_kernel_count", "mv_kernel_name", "mv_set_profiling", "mv_step_kernel_ms",
     "mv_last_step_row_stats", "mv_probe_copy",
+    "mv_codec_stream_bits", "mv_codec_scratch_bytes", "mv_codec_encode", "mv_codec_decode",
 )
 
 
@@ -85,6 +86,15 @@ def load() -> ctypes.CDLL:
     L.mv_step_kernel_ms.restype = i32
     L.mv_last_step_row_stats.argtypes = [vp, u32p, u32p, u32p]
     L.mv_last_step_row_stats.restype = i32
+    u64 = ctypes.c_uint64
+    L.mv_codec_stream_bits.argtypes = [i64, i64, i64]
+    L.mv_codec_stream_bits.restype = u64
+    L.mv_codec_scratch_bytes.argtypes = [u64, i32]
+    L.mv_codec_scratch_bytes.restype = ctypes.c_size_t
+    L.mv_codec_encode.argtypes = [vp, i64, vp, i64, i64, i32, i64, i64, vp, i64, vp, vp]
+    L.mv_codec_encode.restype = i32
+    L.mv_codec_decode.argtypes = [vp, i64, vp, u64, i32, i64, i64, vp, i64, i64, vp, vp, ctypes.c_size_t, vp]
+    L.mv_codec_decode.restype = i32
     L.mv_probe_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
     L.mv_probe_copy.restype = i32
     _lib = L
@@ -200,3 +210,38 @@ def mv_probe_copy(dst, src, stream=None) -> None:
     st = load().mv_probe_copy(dst.data_ptr(), src.data_ptr(), nbytes, stream.cuda_stream)
     if st != MV_OK:
         raise MvError(st, "mv_probe_copy")
+
+
+def mv_codec_stream_bits(n: int, d: int, block_len: int) -> int:
+    return int(load().mv_codec_stream_bits(n, d, block_len))
+
+
+def mv_codec_scratch_bytes(max_bits: int, rows: int) -> int:
+    return int(load().mv_codec_scratch_bytes(max_bits, rows))
+
+
+def mv_codec_encode(idx, n: int, d: int, block_len: int, streams, n_bits, counts=None, counts_stride: int = 1,
+                    stream=None) -> None:
+    """idx: rows x ld int32 device tensor of ascending coordinates; streams: rows x ld_words
+    int32 device tensor (out); n_bits: rows int64 device tensor (out); counts: optional
+    int32 device tensor with the rows' lengths at stride counts_stride."""
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream(idx.device)
+    st = load().mv_codec_encode(_dev_ptr(idx), idx.stride(0), _dev_ptr(counts), counts_stride, n, idx.shape[0], d,
+                                block_len, _dev_ptr(streams), streams.stride(0), _dev_ptr(n_bits),
+                                stream.cuda_stream)
+    if st != MV_OK:
+        raise MvError(st, "mv_codec_encode")
+
+
+def mv_codec_decode(streams, n_bits, max_bits: int, d: int, block_len: int, idx_out, max_n: int, counts_out,
+                    scratch, stream=None) -> None:
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream(streams.device)
+    st = load().mv_codec_decode(_dev_ptr(streams), streams.stride(0), _dev_ptr(n_bits), max_bits, streams.shape[0],
+                                d, block_len, _dev_ptr(idx_out), idx_out.stride(0), max_n, _dev_ptr(counts_out),
+                                _dev_ptr(scratch), scratch.numel() * scratch.element_size(), stream.cuda_stream)
+    if st != MV_OK:
+        raise MvError(st, "mv_codec_decode")

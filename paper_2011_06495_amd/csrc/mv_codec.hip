@@ -1,0 +1,321 @@
+// Sparse position code of the paper's Sec. 4.3.1 on the GPU: encoder and decoder
+// for batches of ascending coordinate lists (the workers' votes, the add / drop
+// lists, the global mask).
+//
+// Stream of one list: the vector's d coordinates are cut into blocks of
+// block_len = 1/phi; per listed position a 1 bit followed by the position inside
+// its block in B = ceil(log2(block_len)) bits, most significant first; a 0 bit
+// closes every block.  Bit k of a stream is bit k % 32 of its word k / 32.
+// With n positions the stream has n (1 + B) + ceil(d / block_len) bits.
+//
+// Encoder: position i of the list lies in block b_i = idx[i] / block_len and is
+// preceded by i codes and b_i closing bits, so its code starts at bit
+// i (1 + B) + b_i -- no prefix sum is needed.  One thread per OUTPUT word finds the
+// codes that overlap it by bisection over that increasing function and writes the
+// word once: no atomics, no clearing pass, coalesced stores.
+//
+// Decoder: the receiver's parse is a finite automaton (state = offset bits still
+// to skip, 0..B).  Each 64-bit chunk of the stream is run once for every possible
+// entry state (exit state, codes begun, blocks closed); composing these maps along
+// the stream gives every chunk its true entry state and the number of codes and
+// closed blocks before it; a last pass parses each chunk for real and writes
+// coordinate = closed blocks * block_len + offset at its place in the list.
+#include "../../include/mv.h"
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace mvc {
+
+constexpr int kThreads = 256;
+constexpr int kMaxB = 31;
+constexpr int kChunkBits = 64;
+constexpr int kWalkThreads = 1024;
+
+__host__ __device__ inline int offset_bits(int64_t block_len)
+{
+    int b = 0;
+    while (((int64_t)1 << b) < block_len) ++b;
+    return b;
+}
+
+__device__ __forceinline__ uint32_t stream_bit(const uint32_t* __restrict__ w, uint64_t k)
+{
+    return (w[k >> 5] >> (k & 31u)) & 1u;
+}
+
+// first bit of the code of list entry i
+__device__ __forceinline__ uint64_t code_start(const uint32_t* __restrict__ idx, uint32_t i, uint32_t code_len,
+                                               uint32_t block_len)
+{
+    return (uint64_t)i * code_len + idx[i] / block_len;
+}
+
+__global__ __launch_bounds__(kThreads) void codec_encode_kernel(
+    const uint32_t* __restrict__ idx, int64_t ld_idx, const uint32_t* __restrict__ counts, int64_t counts_stride,
+    uint32_t n_fixed, int64_t d, uint32_t block_len, uint32_t B, uint32_t* __restrict__ streams, int64_t ld_words,
+    unsigned long long* __restrict__ n_bits_out)
+{
+    const uint32_t row = blockIdx.y;
+    const uint32_t n = counts ? counts[(int64_t)row * counts_stride] : n_fixed;
+    const uint32_t code_len = 1 + B;
+    const uint64_t n_blocks = ((uint64_t)d + block_len - 1) / block_len;
+    const uint64_t total = (uint64_t)n * code_len + n_blocks;
+    const uint64_t n_words = (total + 31) / 32;
+    const uint32_t* list = idx + (int64_t)row * ld_idx;
+    if (blockIdx.x == 0 && threadIdx.x == 0) n_bits_out[row] = total;
+    for (uint64_t w = (uint64_t)blockIdx.x * kThreads + threadIdx.x; w < n_words; w += (uint64_t)gridDim.x * kThreads) {
+        const uint64_t lo_bit = w * 32, hi_bit = lo_bit + 32;
+        // first entry whose code ends beyond the word's first bit
+        uint32_t lo = 0, hi = n;
+        while (lo < hi) {
+            const uint32_t mid = lo + (hi - lo) / 2;
+            if (code_start(list, mid, code_len, block_len) + code_len > lo_bit) hi = mid;
+            else lo = mid + 1;
+        }
+        uint32_t word = 0;
+        for (uint32_t i = lo; i < n; ++i) {
+            const uint64_t s = code_start(list, i, code_len, block_len);
+            if (s >= hi_bit) break;
+            // the code as it lies in the stream, first bit in bit 0: the flag, then the offset MSB first
+            const uint32_t off = list[i] % block_len;
+            const uint64_t code = 1ull | ((uint64_t)(B ? (__brev(off) >> (32 - B)) : 0u) << 1);
+            word |= (s >= lo_bit) ? (uint32_t)(code << (s - lo_bit)) : (uint32_t)(code >> (lo_bit - s));
+        }
+        streams[(int64_t)row * ld_words + w] = word;
+    }
+}
+
+// ---- decoder -----------------------------------------------------------------
+
+struct ChunkMap {                // what a chunk does to the parse, for one entry state
+    uint8_t  exit_state;
+    uint8_t  codes;              // codes begun in the chunk (at most 64)
+    uint8_t  closed;             // blocks closed in the chunk (at most 64)
+    uint8_t  pad;
+};
+
+__device__ __forceinline__ ChunkMap run_chunk(const uint32_t* __restrict__ words, uint64_t first, uint64_t last,
+                                              uint32_t state, uint32_t B)
+{
+    // bits [first, last); state = offset bits still to skip
+    ChunkMap m = {0, 0, 0, 0};
+    uint64_t k = first;
+    while (k < last) {
+        if (state) {
+            const uint64_t skip = min((uint64_t)state, last - k);
+            k += skip;
+            state -= (uint32_t)skip;
+        } else if (stream_bit(words, k)) {
+            ++m.codes;
+            state = B;
+            ++k;
+        } else {
+            ++m.closed;
+            ++k;
+        }
+    }
+    m.exit_state = (uint8_t)state;
+    return m;
+}
+
+// maps[row][chunk][state]
+__global__ __launch_bounds__(kThreads) void codec_chunk_maps_kernel(
+    const uint32_t* __restrict__ streams, int64_t ld_words, const unsigned long long* __restrict__ n_bits,
+    uint32_t B, ChunkMap* __restrict__ maps, uint64_t max_chunks)
+{
+    const uint32_t row = blockIdx.y;
+    const uint64_t total = n_bits[row];
+    const uint64_t n_chunks = (total + kChunkBits - 1) / kChunkBits;
+    const uint32_t* words = streams + (int64_t)row * ld_words;
+    const uint32_t n_states = B + 1;
+    for (uint64_t item = (uint64_t)blockIdx.x * kThreads + threadIdx.x; item < n_chunks * n_states;
+         item += (uint64_t)gridDim.x * kThreads) {
+        const uint64_t c = item / n_states;
+        const uint32_t s = (uint32_t)(item % n_states);
+        const uint64_t first = c * kChunkBits, last = min(first + kChunkBits, total);
+        maps[((uint64_t)row * max_chunks + c) * (kMaxB + 1) + s] = run_chunk(words, first, last, s, B);
+    }
+}
+
+struct Entry {                   // the parse at the start of a chunk
+    uint32_t state;
+    uint32_t codes;              // codes begun before the chunk
+    uint32_t closed;             // blocks closed before the chunk
+};
+
+// One workgroup per row: thread t owns a contiguous range of chunks.  It composes
+// the range's maps for every entry state; thread 0 then walks the 1024 range maps
+// with the true state; every thread finally walks its range with its true entry
+// and records each chunk's entry.
+__global__ __launch_bounds__(kWalkThreads) void codec_walk_kernel(
+    const unsigned long long* __restrict__ n_bits, uint32_t B, const ChunkMap* __restrict__ maps, uint64_t max_chunks,
+    Entry* __restrict__ entries, uint32_t* __restrict__ counts_out)
+{
+    __shared__ uint8_t  r_exit[kWalkThreads][kMaxB + 1];
+    __shared__ uint32_t r_codes[kWalkThreads][2];     // only for the true entry state (filled in the second sweep)
+    __shared__ Entry    r_entry[kWalkThreads];
+    const uint32_t row = blockIdx.x, t = threadIdx.x;
+    const uint64_t total = n_bits[row];
+    const uint64_t n_chunks = (total + kChunkBits - 1) / kChunkBits;
+    const uint64_t per = (n_chunks + kWalkThreads - 1) / kWalkThreads;
+    const uint64_t c0 = min((uint64_t)t * per, n_chunks), c1 = min(c0 + per, n_chunks);
+    const ChunkMap* rmaps = maps + (uint64_t)row * max_chunks * (kMaxB + 1);
+    const uint32_t n_states = B + 1;
+    // sweep 1: exit state of the range for every entry state
+    for (uint32_t s = 0; s < n_states; ++s) {
+        uint32_t st = s;
+        for (uint64_t c = c0; c < c1; ++c) st = rmaps[c * (kMaxB + 1) + st].exit_state;
+        r_exit[t][s] = (uint8_t)st;
+    }
+    __syncthreads();
+    // true entry state of every range
+    if (t == 0) {
+        uint32_t st = 0;
+        for (uint32_t r = 0; r < kWalkThreads; ++r) {
+            r_entry[r].state = st;
+            st = r_exit[r][st];
+        }
+    }
+    __syncthreads();
+    // sweep 2: codes and closed blocks of the range on its true path
+    {
+        uint32_t st = r_entry[t].state, codes = 0, closed = 0;
+        for (uint64_t c = c0; c < c1; ++c) {
+            const ChunkMap m = rmaps[c * (kMaxB + 1) + st];
+            codes += m.codes;
+            closed += m.closed;
+            st = m.exit_state;
+        }
+        r_codes[t][0] = codes;
+        r_codes[t][1] = closed;
+    }
+    __syncthreads();
+    if (t == 0) {
+        uint32_t codes = 0, closed = 0;
+        for (uint32_t r = 0; r < kWalkThreads; ++r) {
+            r_entry[r].codes = codes;
+            r_entry[r].closed = closed;
+            codes += r_codes[r][0];
+            closed += r_codes[r][1];
+        }
+        counts_out[row] = codes;
+    }
+    __syncthreads();
+    // sweep 3: every chunk's entry
+    {
+        Entry e = r_entry[t];
+        for (uint64_t c = c0; c < c1; ++c) {
+            entries[(uint64_t)row * max_chunks + c] = e;
+            const ChunkMap m = rmaps[c * (kMaxB + 1) + e.state];
+            e.codes += m.codes;
+            e.closed += m.closed;
+            e.state = m.exit_state;
+        }
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void codec_emit_kernel(
+    const uint32_t* __restrict__ streams, int64_t ld_words, const unsigned long long* __restrict__ n_bits, int64_t d,
+    uint32_t block_len, uint32_t B, const Entry* __restrict__ entries, uint64_t max_chunks,
+    uint32_t* __restrict__ idx_out, int64_t ld_idx, uint32_t max_n)
+{
+    const uint32_t row = blockIdx.y;
+    const uint64_t total = n_bits[row];
+    const uint64_t n_chunks = (total + kChunkBits - 1) / kChunkBits;
+    const uint32_t* words = streams + (int64_t)row * ld_words;
+    uint32_t* out = idx_out + (int64_t)row * ld_idx;
+    for (uint64_t c = (uint64_t)blockIdx.x * kThreads + threadIdx.x; c < n_chunks; c += (uint64_t)gridDim.x * kThreads) {
+        Entry e = entries[(uint64_t)row * max_chunks + c];
+        const uint64_t first = c * kChunkBits, last = min(first + kChunkBits, total);
+        uint64_t k = first + min((uint64_t)e.state, last - first);     // rest of a code begun earlier
+        while (k < last) {
+            if (stream_bit(words, k)) {
+                uint32_t off = 0;
+                for (uint32_t q = 0; q < B; ++q)                       // may run into the next chunks
+                    off = (off << 1) | ((k + 1 + q < total) ? stream_bit(words, k + 1 + q) : 0u);
+                const uint64_t pos = (uint64_t)e.closed * block_len + off;
+                if (e.codes < max_n && pos < (uint64_t)d) out[e.codes] = (uint32_t)pos;
+                ++e.codes;
+                k += 1 + B;
+            } else {
+                ++e.closed;
+                ++k;
+            }
+        }
+    }
+}
+
+}  // namespace mvc
+
+extern "C" {
+
+uint64_t mv_codec_stream_bits(int64_t n, int64_t d, int64_t block_len)
+{
+    if (n < 0 || d < 1 || block_len < 1 || block_len > 0x7FFFFFFFll || d > 0x7FFFFFFFll || n > d) return 0;
+    return (uint64_t)n * (uint64_t)(1 + mvc::offset_bits(block_len)) + (uint64_t)((d + block_len - 1) / block_len);
+}
+
+size_t mv_codec_scratch_bytes(uint64_t max_bits, int32_t rows)
+{
+    if (rows < 1) return 0;
+    const uint64_t chunks = (max_bits + mvc::kChunkBits - 1) / mvc::kChunkBits;
+    return (size_t)rows * chunks * ((mvc::kMaxB + 1) * sizeof(mvc::ChunkMap) + sizeof(mvc::Entry)) + 256;
+}
+
+mv_status mv_codec_encode(const uint32_t* idx, int64_t ld_idx, const uint32_t* counts, int64_t counts_stride,
+                          int64_t n, int32_t rows, int64_t d, int64_t block_len, uint32_t* streams,
+                          int64_t ld_words, uint64_t* n_bits, void* stream)
+{
+    if (!idx || !streams || !n_bits || rows < 1 || rows > 65535) return MV_ERR_INVALID_ARG;
+    if (d < 1 || d > 0x7FFFFFFFll || block_len < 1 || block_len > d || n < 0 || n > d || ld_idx < n)
+        return MV_ERR_INVALID_ARG;
+    if (counts && counts_stride < 1) return MV_ERR_INVALID_ARG;
+    const uint64_t max_bits = mv_codec_stream_bits(n, d, block_len);
+    const uint64_t max_words = (max_bits + 31) / 32;
+    if ((uint64_t)ld_words < max_words) return MV_ERR_INVALID_ARG;
+    uint64_t bx = (max_words + mvc::kThreads - 1) / mvc::kThreads;
+    if (bx > 4096) bx = 4096;
+    if (bx < 1) bx = 1;
+    hipLaunchKernelGGL(mvc::codec_encode_kernel, dim3((uint32_t)bx, (uint32_t)rows), dim3(mvc::kThreads), 0,
+                       static_cast<hipStream_t>(stream), idx, ld_idx, counts, counts_stride, (uint32_t)n, d,
+                       (uint32_t)block_len, (uint32_t)mvc::offset_bits(block_len), streams, ld_words,
+                       reinterpret_cast<unsigned long long*>(n_bits));
+    return hipGetLastError() == hipSuccess ? MV_OK : MV_ERR_DEVICE;
+}
+
+mv_status mv_codec_decode(const uint32_t* streams, int64_t ld_words, const uint64_t* n_bits, uint64_t max_bits,
+                          int32_t rows, int64_t d, int64_t block_len, uint32_t* idx_out, int64_t ld_idx,
+                          int64_t max_n, uint32_t* counts_out, void* scratch, size_t scratch_bytes, void* stream)
+{
+    if (!streams || !n_bits || !idx_out || !counts_out || !scratch || rows < 1 || rows > 65535)
+        return MV_ERR_INVALID_ARG;
+    if (d < 1 || d > 0x7FFFFFFFll || block_len < 1 || block_len > d || max_n < 0 || ld_idx < max_n ||
+        max_n > 0xFFFFFFFFll)
+        return MV_ERR_INVALID_ARG;
+    if ((uint64_t)ld_words * 32 < max_bits) return MV_ERR_INVALID_ARG;
+    if (scratch_bytes < mv_codec_scratch_bytes(max_bits, rows)) return MV_ERR_INVALID_ARG;
+    const uint64_t max_chunks = (max_bits + mvc::kChunkBits - 1) / mvc::kChunkBits;
+    if (max_chunks == 0) return MV_ERR_INVALID_ARG;
+    uintptr_t base = (reinterpret_cast<uintptr_t>(scratch) + 255) & ~(uintptr_t)255;
+    mvc::ChunkMap* maps = reinterpret_cast<mvc::ChunkMap*>(base);
+    mvc::Entry* entries =
+        reinterpret_cast<mvc::Entry*>(base + (size_t)rows * max_chunks * (mvc::kMaxB + 1) * sizeof(mvc::ChunkMap));
+    const uint32_t B = (uint32_t)mvc::offset_bits(block_len);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const unsigned long long* nb = reinterpret_cast<const unsigned long long*>(n_bits);
+    uint64_t bx = (max_chunks * (B + 1) + mvc::kThreads - 1) / mvc::kThreads;
+    if (bx > 4096) bx = 4096;
+    hipLaunchKernelGGL(mvc::codec_chunk_maps_kernel, dim3((uint32_t)bx, (uint32_t)rows), dim3(mvc::kThreads), 0, st,
+                       streams, ld_words, nb, B, maps, max_chunks);
+    hipLaunchKernelGGL(mvc::codec_walk_kernel, dim3((uint32_t)rows), dim3(mvc::kWalkThreads), 0, st, nb, B, maps,
+                       max_chunks, entries, counts_out);
+    uint64_t bx2 = (max_chunks + mvc::kThreads - 1) / mvc::kThreads;
+    if (bx2 > 4096) bx2 = 4096;
+    hipLaunchKernelGGL(mvc::codec_emit_kernel, dim3((uint32_t)bx2, (uint32_t)rows), dim3(mvc::kThreads), 0, st,
+                       streams, ld_words, nb, d, (uint32_t)block_len, B, entries, max_chunks, idx_out, ld_idx,
+                       (uint32_t)max_n);
+    return hipGetLastError() == hipSuccess ? MV_OK : MV_ERR_DEVICE;
+}
+
+}  // extern "C"

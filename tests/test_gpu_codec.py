@@ -1,0 +1,97 @@
+"""Parity of the GPU position codec (Sec. 4.3.1) against the oracle: streams
+bit-exact word by word, lengths, and the decoded lists; on random lists, on
+clustered lists, on the lists a vote step really produces, on the add / drop lists
+with their per-row counts."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2011_06495_amd import binding as B
+from paper_2011_06495_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print("[case] " + msg, flush=True)
+    sys.stdout.flush()
+
+
+def gpu_codec_round_trip(oracle, lists, d, block_len, n_max):
+    """lists: python list of ascending uint32 arrays (rows, variable length <= n_max)."""
+    dev = torch.device("cuda:0")
+    rows = len(lists)
+    idx = torch.full((rows, max(1, n_max)), -1, dtype=torch.int32, device=dev)
+    counts = torch.zeros(rows, dtype=torch.int32, device=dev)
+    for r, l in enumerate(lists):
+        if l.size:
+            idx[r, : l.size] = torch.from_numpy(l.astype(np.int64)).to(torch.int32)
+        counts[r] = int(l.size)
+    max_bits = B.mv_codec_stream_bits(n_max, d, block_len)
+    assert max_bits == oracle.codec_stream_bits(n_max, d, block_len)
+    ld_words = (max_bits + 31) // 32 + 3
+    streams = torch.full((rows, ld_words), 0x5A5A5A5A, dtype=torch.int32, device=dev)
+    n_bits = torch.zeros(rows, dtype=torch.int64, device=dev)
+    B.mv_codec_encode(idx, n_max, d, block_len, streams, n_bits, counts=counts)
+    torch.cuda.synchronize()
+    got_words = streams.cpu().numpy().view(np.uint32)
+    got_bits = n_bits.cpu().numpy()
+    for r, l in enumerate(lists):
+        words, nb = oracle.codec_encode(l, d, block_len)
+        assert got_bits[r] == nb, "row %d length" % r
+        nw = (nb + 31) // 32
+        assert np.array_equal(got_words[r, :nw], words[:nw]), "row %d stream" % r
+        assert np.all(got_words[r, nw:] == 0x5A5A5A5A), "row %d: words beyond the stream were touched" % r
+    # decode what was encoded
+    out = torch.full((rows, max(1, n_max) + 8), -1, dtype=torch.int32, device=dev)
+    cnt = torch.zeros(rows, dtype=torch.int32, device=dev)
+    scratch = torch.empty(B.mv_codec_scratch_bytes(max_bits, rows), dtype=torch.uint8, device=dev)
+    B.mv_codec_decode(streams, n_bits, max_bits, d, block_len, out, n_max, cnt, scratch)
+    torch.cuda.synchronize()
+    o = out.cpu().numpy().view(np.uint32)
+    c = cnt.cpu().numpy()
+    for r, l in enumerate(lists):
+        assert c[r] == l.size, "row %d decoded count" % r
+        assert np.array_equal(o[r, : l.size], l), "row %d decoded list" % r
+        assert np.all(o[r, max(1, n_max):] == 0xFFFFFFFF)
+        # and it is what the oracle's receiver reads from the oracle's stream
+        words, nb = oracle.codec_encode(l, d, block_len)
+        assert np.array_equal(oracle.codec_decode(words, nb, d, block_len, max(1, n_max)), l)
+
+
+@pytest.mark.parametrize("d,L,n,rows", [(1, 1, 1, 1), (64, 1, 40, 2), (1000, 7, 0, 2), (1000, 7, 1000, 1),
+                                        (100000, 100, 1000, 5), (123457, 1000, 124, 3), (65536, 64, 5000, 4),
+                                        (11173962, 1000, 11174, 3), (11173962, 4001, 2793, 2)])
+def test_codec_random_lists(oracle, d, L, n, rows):
+    say("codec d=%d block=%d n=%d rows=%d" % (d, L, n, rows))
+    rng = np.random.default_rng(d + n)
+    lists = []
+    for r in range(rows):
+        m = n if r == 0 else int(rng.integers(0, n + 1))
+        lists.append(np.sort(rng.choice(d, m, replace=False)).astype(np.uint32))
+    gpu_codec_round_trip(oracle, lists, d, L, n)
+
+
+def test_codec_clustered_lists(oracle):
+    d, L = 300000, 128
+    say("codec clustered")
+    lists = [np.arange(5000, 9000, dtype=np.uint32),                          # 4000 consecutive coordinates
+             np.concatenate([np.arange(0, 64), np.arange(299000, 300000)]).astype(np.uint32),
+             np.array([299999], np.uint32), np.array([], np.uint32)]
+    gpu_codec_round_trip(oracle, lists, d, L, 4000)
+
+
+def test_codec_on_the_lists_of_a_vote_step(oracle):
+    """Encodes the workers' votes and the mask that mv_vote_step produces, with the
+    block length 1/phi of the workload, and checks the bit budget of Sec. 2.1."""
+    w = W.C2.with_size(400003, N=6)
+    say("codec on vote-step lists N=%d d=%d K=%d" % (w.N, w.d, w.K))
+    g, e = W.gradients(w, 0), W.zero_error(w)
+    ref = oracle.vote_step(g, e, w.K)
+    block_len = int(round(w.d / w.K))
+    lists = [ref.worker_idx[n] for n in range(w.N)] + [ref.mask_idx]
+    gpu_codec_round_trip(oracle, lists, w.d, block_len, w.K)
+    bits = B.mv_codec_stream_bits(w.K, w.d, block_len)
+    assert abs(bits / w.K - oracle.bits_per_position(block_len)) < 0.01       # log2(1/phi) + 2 per position
