@@ -63,6 +63,9 @@ def main():
     ap.add_argument("--scheme", default="mv", choices=["mv", "ad"],
                     help="mv: majority voting (Algorithm 1); ad: majority voting with add-drop (Algorithm 2), "
                          "a full first vote untimed, then K_ad = K/10 per step")
+    ap.add_argument("--codec", action="store_true",
+                    help="also time the sparse position code (Sec. 4.3.1) on the workers' vote lists "
+                         "of the last step (untimed extra; needs worker_idx, scheme mv)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-worker-idx", action="store_true",
                     help="do not request the per-worker sorted vote lists (optional output)")
@@ -179,6 +182,35 @@ def main():
         breakdown = {n: round(float(np.median(v)) * 1e3, 2) for n, v in acc.items()}   # microseconds
     B.mv_set_profiling(ctx, 0)
 
+    # ---- optional: the position code on the vote lists of the last step
+    codec = None
+    if args.codec and not ad and widx is not None:
+        block_len = int(round(d / K))
+        max_bits = B.mv_codec_stream_bits(K, d, block_len)
+        ld_words = (max_bits + 31) // 32
+        streams = torch.zeros((N, ld_words), dtype=torch.int32, device=dev)
+        nbits = torch.zeros(N, dtype=torch.int64, device=dev)
+        dec = torch.zeros((N, K), dtype=torch.int32, device=dev)
+        dcnt = torch.zeros(N, dtype=torch.int32, device=dev)
+        scratch = torch.empty(B.mv_codec_scratch_bytes(max_bits, N), dtype=torch.uint8, device=dev)
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        reps = 20
+        for it in range(2):                       # first round warms up
+            evs[0].record(stream)
+            for _ in range(reps):
+                B.mv_codec_encode(widx, K, d, block_len, streams, nbits, stream=stream)
+            evs[1].record(stream)
+            for _ in range(reps):
+                B.mv_codec_decode(streams, nbits, max_bits, d, block_len, dec, K, dcnt, scratch, stream=stream)
+            evs[2].record(stream)
+            torch.cuda.synchronize()
+        codec = {"rows": N, "positions_per_row": K, "block_len": block_len,
+                 "bits_per_position": round(float(nbits.cpu().numpy().mean()) / K, 3),
+                 "paper_bits_per_position": comm_load_context(w)["bits_per_position"],
+                 "encode_us": round(evs[0].elapsed_time(evs[1]) * 1e3 / reps, 2),
+                 "decode_us": round(evs[1].elapsed_time(evs[2]) * 1e3 / reps, 2),
+                 "round_trip_ok": bool(torch.equal(dec, widx) and int(dcnt.min()) == K and int(dcnt.max()) == K)}
+
     # ---- yardstick: a plain streaming copy of the same footprint (read n, write n bytes)
     src = torch.empty(N * ld_e, dtype=torch.float32, device=dev).normal_()
     dst = torch.empty_like(src)
@@ -263,6 +295,8 @@ def main():
         out["kernel_us_in_timed_region"] = {n: round(float(np.mean(v)) * 1e3, 2) for n, v in per_kernel.items()}
     if breakdown:
         out["kernel_us_breakdown"] = breakdown
+    if codec:
+        out["position_codec"] = codec
     print(json.dumps(out), flush=True)
 
 

@@ -495,6 +495,99 @@ int64_t mvo_codec_decode(const uint32_t* words, int64_t n_bits, int64_t d, int64
 }
 
 /* ------------------------------------------------------------------ */
+/* fractional quantisation (Sec. 4.3.2)                                 */
+/* ------------------------------------------------------------------ */
+
+/*
+ * q bits per value: q-1 bits name one of L = 2^(q-1) geometric intervals of
+ * |v| between v_max and v_min, I_l = [v_max / alpha^(l-1), v_max / alpha^l] with
+ * alpha = (v_max / v_min)^(1/L), one bit is the sign; the L means mu_l of the
+ * magnitudes that fall into I_l follow the codes, and the receiver reproduces
+ * sign * mu_l.
+ *
+ * Readings where Sec. 4.3.2 is silent or loose (the interval ends overlap as
+ * printed, and nothing fixes the arithmetic of the edges):
+ *   - v_min is the smallest NON-ZERO magnitude (a zero would make alpha
+ *     infinite); zeros go to the last interval.  If all values are zero every
+ *     mean is zero.
+ *   - Edges in fp64: ratio = v_max / v_min; alpha = ratio under q-1 successive
+ *     square roots (L is a power of two, so this is the L-th root, and every step
+ *     is a correctly rounded IEEE operation on any machine); edge_0 = v_max,
+ *     edge_l = edge_{l-1} / alpha for l = 1..L-1.
+ *   - |v| belongs to interval l = 1 + #{ j in 1..L-1 : |v| <= edge_j }: a value on
+ *     an edge goes to the interval of the smaller magnitudes.
+ *   - code = (l - 1) | (sign << (q-1)), sign = 1 for negative values (and -0);
+ *     value k occupies bits [k q, (k+1) q) of the stream, bit b of the stream
+ *     being bit b % 32 of word b / 32.
+ *   - mu_l = (sum of the magnitudes in I_l, accumulated in fp64 in index order)
+ *     / count, rounded to fp32; 0 for an empty interval.
+ */
+int32_t mvo_quant_edges(const float* v, int64_t n, int32_t q, double* edges /* L entries: edge_0..edge_{L-1} */)
+{
+    if (n < 1 || q < 2 || q > 9) return -1;
+    const int32_t L = 1 << (q - 1);
+    double vmax = 0.0, vmin = 0.0;
+    for (int64_t k = 0; k < n; ++k) {
+        const double m = fabs((double)v[k]);
+        if (m > vmax) vmax = m;
+        if (m > 0.0 && (vmin == 0.0 || m < vmin)) vmin = m;
+    }
+    if (vmax == 0.0) {
+        for (int32_t l = 0; l < L; ++l) edges[l] = 0.0;
+        return 0;
+    }
+    double alpha = vmax / vmin;
+    for (int32_t r = 0; r < q - 1; ++r) alpha = sqrt(alpha);
+    edges[0] = vmax;
+    for (int32_t l = 1; l < L; ++l) edges[l] = edges[l - 1] / alpha;
+    return 0;
+}
+
+/* codes: one uint8 per value ((l-1) | sign << (q-1)); means: L floats. */
+int32_t mvo_quant_encode(const float* v, int64_t n, int32_t q, uint8_t* codes, float* means)
+{
+    if (n < 1 || q < 2 || q > 8) return -1;
+    const int32_t L = 1 << (q - 1);
+    double edges[256];
+    if (mvo_quant_edges(v, n, q, edges) != 0) return -1;
+    double sum[256];
+    int64_t cnt[256];
+    for (int32_t l = 0; l < L; ++l) {
+        sum[l] = 0.0;
+        cnt[l] = 0;
+    }
+    for (int64_t k = 0; k < n; ++k) {
+        const double m = fabs((double)v[k]);
+        int32_t l = 0;                                   /* l - 1 */
+        for (int32_t j = 1; j < L; ++j) l += (m <= edges[j]) ? 1 : 0;
+        const uint32_t sign = (f32_bits(v[k]) >> 31) & 1u;
+        codes[k] = (uint8_t)((uint32_t)l | (sign << (q - 1)));
+        sum[l] += m;
+        cnt[l] += 1;
+    }
+    for (int32_t l = 0; l < L; ++l) means[l] = cnt[l] ? (float)(sum[l] / (double)cnt[l]) : 0.0f;
+    return 0;
+}
+
+void mvo_quant_decode(const uint8_t* codes, int64_t n, int32_t q, const float* means, float* out)
+{
+    const uint32_t lmask = ((uint32_t)1 << (q - 1)) - 1;
+    for (int64_t k = 0; k < n; ++k) {
+        const float m = means[codes[k] & lmask];
+        out[k] = ((codes[k] >> (q - 1)) & 1u) ? -m : m;
+    }
+}
+
+/* packs / unpacks q-bit codes into the stream layout stated above */
+void mvo_quant_pack(const uint8_t* codes, int64_t n, int32_t q, uint32_t* words /* ceil(n q / 32), zeroed here */)
+{
+    memset(words, 0, (size_t)(((uint64_t)n * (uint64_t)q + 31) / 32) * sizeof(uint32_t));
+    for (int64_t k = 0; k < n; ++k)
+        for (int32_t b = 0; b < q; ++b)
+            put_bit(words, (uint64_t)k * (uint64_t)q + (uint64_t)b, (codes[k] >> b) & 1u);
+}
+
+/* ------------------------------------------------------------------ */
 /* communication-load arithmetic (Sec. 2.1 and Sec. 4.4), reporting only */
 /* ------------------------------------------------------------------ */
 

@@ -68,6 +68,14 @@ def lib() -> ctypes.CDLL:
         L.mvo_codec_encode.restype = i64
         L.mvo_codec_decode.argtypes = [vp, i64, i64, i64, vp, i64]
         L.mvo_codec_decode.restype = i64
+        L.mvo_quant_edges.argtypes = [vp, i64, i32, vp]
+        L.mvo_quant_edges.restype = i32
+        L.mvo_quant_encode.argtypes = [vp, i64, i32, vp, vp]
+        L.mvo_quant_encode.restype = i32
+        L.mvo_quant_decode.argtypes = [vp, i64, i32, vp, vp]
+        L.mvo_quant_decode.restype = None
+        L.mvo_quant_pack.argtypes = [vp, i64, i32, vp]
+        L.mvo_quant_pack.restype = None
         L.mvo_bits_per_position.argtypes = [dbl]
         L.mvo_bits_per_position.restype = i32
         L.mvo_q_val.argtypes = [dbl, dbl, dbl]
@@ -257,6 +265,40 @@ def codec_decode(words: np.ndarray, n_bits: int, d: int, block_len: int, max_n: 
     if n < 0:
         raise ValueError("mvo_codec_decode: malformed stream")
     return out[:n].copy()
+
+
+# ---------------------------------------------------------------- fractional quantisation (Sec. 4.3.2)
+
+def quant_edges(v: np.ndarray, q: int) -> np.ndarray:
+    v = _c(v, np.float32)
+    edges = np.zeros(1 << (q - 1), np.float64)
+    if lib().mvo_quant_edges(_ptr(v), v.size, q, _ptr(edges)) != 0:
+        raise ValueError("mvo_quant_edges rejected its arguments")
+    return edges
+
+
+def quant_encode(v: np.ndarray, q: int):
+    """Returns (codes uint8, means float32[L]): code = (interval - 1) | sign << (q - 1)."""
+    v = _c(v, np.float32)
+    codes = np.zeros(v.size, np.uint8)
+    means = np.zeros(1 << (q - 1), np.float32)
+    if lib().mvo_quant_encode(_ptr(v), v.size, q, _ptr(codes), _ptr(means)) != 0:
+        raise ValueError("mvo_quant_encode rejected its arguments")
+    return codes, means
+
+
+def quant_decode(codes: np.ndarray, q: int, means: np.ndarray) -> np.ndarray:
+    codes, means = _c(codes, np.uint8), _c(means, np.float32)
+    out = np.empty(codes.size, np.float32)
+    lib().mvo_quant_decode(_ptr(codes), codes.size, q, _ptr(means), _ptr(out))
+    return out
+
+
+def quant_pack(codes: np.ndarray, q: int) -> np.ndarray:
+    codes = _c(codes, np.uint8)
+    words = np.zeros((codes.size * q + 31) // 32, np.uint32)
+    lib().mvo_quant_pack(_ptr(codes), codes.size, q, _ptr(words))
+    return words
 
 
 # ---------------------------------------------------------------- comm load
