@@ -210,6 +210,28 @@ def main():
                  "encode_us": round(evs[0].elapsed_time(evs[1]) * 1e3 / reps, 2),
                  "decode_us": round(evs[1].elapsed_time(evs[2]) * 1e3 / reps, 2),
                  "round_trip_ok": bool(torch.equal(dec, widx) and int(dcnt.min()) == K and int(dcnt.max()) == K)}
+        # the fractional quantiser (Sec. 4.3.2, q = 4) on N x K values: the gradients at the mask's coordinates
+        q = 4
+        sent = g_dev[0][:, :d].float()[:, mask.long()].contiguous() if not bf16 else None
+        if sent is not None:
+            qs = torch.zeros((N, (K * q + 31) // 32), dtype=torch.int32, device=dev)
+            qm = torch.zeros((N, 1 << (q - 1)), dtype=torch.float32, device=dev)
+            qo = torch.zeros((N, K), dtype=torch.float32, device=dev)
+            qscr = torch.empty(B.mv_quant_scratch_bytes(K, N, q), dtype=torch.uint8, device=dev)
+            for it in range(2):
+                evs[0].record(stream)
+                for _ in range(reps):
+                    B.mv_quant_encode(sent, q, qs, qm, qscr, stream=stream)
+                evs[1].record(stream)
+                for _ in range(reps):
+                    B.mv_quant_decode(qs, K, q, qm, qo, stream=stream)
+                evs[2].record(stream)
+                torch.cuda.synchronize()
+            rel = float(((qo - sent).abs().sum() / sent.abs().sum()).item())
+            codec["quantiser"] = {"q_bits": q, "rows": N, "values_per_row": K,
+                                  "encode_us": round(evs[0].elapsed_time(evs[1]) * 1e3 / reps, 2),
+                                  "decode_us": round(evs[1].elapsed_time(evs[2]) * 1e3 / reps, 2),
+                                  "relative_l1_error": round(rel, 4)}
 
     # ---- yardstick: a plain streaming copy of the same footprint (read n, write n bytes)
     src = torch.empty(N * ld_e, dtype=torch.float32, device=dev).normal_()

@@ -241,6 +241,33 @@ mv_status mv_codec_decode(const uint32_t* streams, int64_t ld_words, const uint6
                           int32_t rows, int64_t d, int64_t block_len, uint32_t* idx_out, int64_t ld_idx,
                           int64_t max_n, uint32_t* counts_out, void* scratch, size_t scratch_bytes, void* stream);
 
+/* ---- fractional quantisation (paper: Sec. 4.3.2) --------------------------- */
+
+/*
+ * q bits per value (2 <= q <= 8): q-1 bits name one of L = 2^(q-1) geometric
+ * intervals of |v| between the row's largest and smallest non-zero magnitude,
+ * I_l = [v_max / alpha^(l-1), v_max / alpha^l], alpha = (v_max / v_min)^(1/L); one
+ * bit is the sign; L means of the magnitudes that fell into the intervals follow
+ * and the receiver reproduces sign * mean.  The paper leaves the arithmetic of the
+ * edges open; here they are fp64 numbers from correctly rounded operations only
+ * (alpha by q-1 square roots of v_max / v_min, edge_l = edge_{l-1} / alpha), a value
+ * on an edge goes to the interval of the smaller magnitudes and zeros to the last.
+ *   vals      device, `rows` rows of n fp32 values, row stride ld_vals
+ *   streams   device out, row stride ld_words >= ceil(n q / 32): value k occupies
+ *             bits [k q, (k+1) q) of its row's stream (bit b = bit b % 32 of word
+ *             b / 32), code = (interval - 1) | sign << (q - 1)
+ *   means     device out, rows x L fp32 (0 for an empty interval)
+ *   scratch   device, >= mv_quant_scratch_bytes(n, rows, q)
+ * Enqueued on `stream`; allocates nothing.
+ */
+size_t    mv_quant_scratch_bytes(int64_t n, int32_t rows, int32_t q);
+mv_status mv_quant_encode(const float* vals, int64_t ld_vals, int64_t n, int32_t rows, int32_t q,
+                          uint32_t* streams, int64_t ld_words, float* means, void* scratch, size_t scratch_bytes,
+                          void* stream);
+/* out[r][k] = +-means[r][interval of value k], row stride ld_out >= n. */
+mv_status mv_quant_decode(const uint32_t* streams, int64_t ld_words, int64_t n, int32_t rows, int32_t q,
+                          const float* means, float* out, int64_t ld_out, void* stream);
+
 /*
  * Measurement aid, not part of the method: enqueues a plain streaming copy of
  * `bytes` (a multiple of 16; dst and src 16-byte aligned DEVICE pointers, not

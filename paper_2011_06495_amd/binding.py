@@ -24,6 +24,7 @@ ABI_SYMBOLS = (
     "mv_kernel_count", "mv_kernel_name", "mv_set_profiling", "mv_step_kernel_ms",
     "mv_last_step_row_stats", "mv_probe_copy",
     "mv_codec_stream_bits", "mv_codec_scratch_bytes", "mv_codec_encode", "mv_codec_decode",
+    "mv_quant_scratch_bytes", "mv_quant_encode", "mv_quant_decode",
 )
 
 
@@ -95,6 +96,12 @@ def load() -> ctypes.CDLL:
     L.mv_codec_encode.restype = i32
     L.mv_codec_decode.argtypes = [vp, i64, vp, u64, i32, i64, i64, vp, i64, i64, vp, vp, ctypes.c_size_t, vp]
     L.mv_codec_decode.restype = i32
+    L.mv_quant_scratch_bytes.argtypes = [i64, i32, i32]
+    L.mv_quant_scratch_bytes.restype = ctypes.c_size_t
+    L.mv_quant_encode.argtypes = [vp, i64, i64, i32, i32, vp, i64, vp, vp, ctypes.c_size_t, vp]
+    L.mv_quant_encode.restype = i32
+    L.mv_quant_decode.argtypes = [vp, i64, i64, i32, i32, vp, vp, i64, vp]
+    L.mv_quant_decode.restype = i32
     L.mv_probe_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
     L.mv_probe_copy.restype = i32
     _lib = L
@@ -245,3 +252,30 @@ def mv_codec_decode(streams, n_bits, max_bits: int, d: int, block_len: int, idx_
                                 _dev_ptr(scratch), scratch.numel() * scratch.element_size(), stream.cuda_stream)
     if st != MV_OK:
         raise MvError(st, "mv_codec_decode")
+
+
+def mv_quant_scratch_bytes(n: int, rows: int, q: int) -> int:
+    return int(load().mv_quant_scratch_bytes(n, rows, q))
+
+
+def mv_quant_encode(vals, q: int, streams, means, scratch, stream=None) -> None:
+    """vals: rows x n float32 device tensor; streams: rows x ld_words int32 (out);
+    means: rows x 2**(q-1) float32 (out)."""
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream(vals.device)
+    st = load().mv_quant_encode(_dev_ptr(vals), vals.stride(0), vals.shape[1], vals.shape[0], q, _dev_ptr(streams),
+                                streams.stride(0), _dev_ptr(means), _dev_ptr(scratch),
+                                scratch.numel() * scratch.element_size(), stream.cuda_stream)
+    if st != MV_OK:
+        raise MvError(st, "mv_quant_encode")
+
+
+def mv_quant_decode(streams, n: int, q: int, means, out, stream=None) -> None:
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream(out.device)
+    st = load().mv_quant_decode(_dev_ptr(streams), streams.stride(0), n, streams.shape[0], q, _dev_ptr(means),
+                                _dev_ptr(out), out.stride(0), stream.cuda_stream)
+    if st != MV_OK:
+        raise MvError(st, "mv_quant_decode")

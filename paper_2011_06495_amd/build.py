@@ -7,7 +7,8 @@ import subprocess
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB_PATH = os.path.join(_HERE, "libmv.so")
-SOURCES = [os.path.join(CSRC, "mv_api.hip"), os.path.join(CSRC, "mv_codec.hip")]
+SOURCES = [os.path.join(CSRC, "mv_api.hip"), os.path.join(CSRC, "mv_codec.hip"),
+           os.path.join(CSRC, "mv_quant.hip")]
 HEADERS = [os.path.join(CSRC, "mv_kernels.hpp"),
            os.path.join(os.path.dirname(_HERE), "include", "mv.h")]
 
