@@ -25,7 +25,15 @@ namespace mvq {
 
 constexpr int kThreads = 1024;
 constexpr int kMaxL = 128;          // q <= 8
-constexpr int kGroup = 32;          // values per packing group: 32 values = q whole words
+constexpr int kGroup = 32;          // most values per packing group (32 values = q whole words)
+
+// values per packing group: the fewest whose codes fill whole words
+__host__ __device__ constexpr int group_size(int q)
+{
+    int g = 32;
+    while (g > 1 && ((g / 2) * q) % 32 == 0) g /= 2;
+    return g;
+}
 
 __device__ __forceinline__ uint32_t interval_of(double m, const double* edges, int L)
 {
@@ -35,14 +43,15 @@ __device__ __forceinline__ uint32_t interval_of(double m, const double* edges, i
 }
 
 // partial[row][group][l] = sum of the magnitudes of the group's values in interval l, in index order
+template <int q>                      // the bit budget is a template parameter: the packing indexes registers
 __global__ __launch_bounds__(kThreads) void quant_encode_kernel(
-    const float* __restrict__ vals, int64_t ld_vals, int64_t n, int32_t q, uint32_t* __restrict__ streams,
+    const float* __restrict__ vals, int64_t ld_vals, int64_t n, uint32_t* __restrict__ streams,
     int64_t ld_words, float* __restrict__ means, double* __restrict__ partial, uint32_t* __restrict__ pcount,
     int64_t n_groups)
 {
     __shared__ uint32_t red_max[kThreads / 64], red_min[kThreads / 64];
     __shared__ double edges[kMaxL];
-    const int L = 1 << (q - 1);
+    constexpr int L = 1 << (q - 1);
     const uint32_t row = blockIdx.x, t = threadIdx.x;
     const float* v = vals + (int64_t)row * ld_vals;
 
@@ -83,40 +92,60 @@ __global__ __launch_bounds__(kThreads) void quant_encode_kernel(
     uint32_t* out = streams + (int64_t)row * ld_words;
     double* prow = partial + (int64_t)row * n_groups * L;
     uint32_t* crow = pcount + (int64_t)row * n_groups * L;
+    constexpr int G = group_size(q);                 // G values = G q / 32 whole words
+    constexpr int gw = G * q / 32;
     for (int64_t g = t; g < n_groups; g += kThreads) {
+        // the group's values in registers: codes first, then per-interval sums in index order
         uint32_t words[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        float    mag[kGroup];
+        uint8_t  lv[kGroup];
+#pragma unroll
+        for (int i = 0; i < G; ++i) {
+            const int64_t k = g * G + i;
+            const bool live = k < n;
+            const float x = live ? v[k] : 0.0f;
+            mag[i] = fabsf(x);
+            const uint32_t l = live ? interval_of((double)mag[i], edges, L) : 0xFFu;
+            lv[i] = (uint8_t)l;
+            if (live) {
+                const uint32_t code = l | ((__float_as_uint(x) >> 31) << (q - 1));
+                const uint32_t bit = (uint32_t)i * (uint32_t)q;
+                words[bit >> 5] |= code << (bit & 31);
+                if ((bit & 31) + q > 32) words[(bit >> 5) + 1] |= code >> (32 - (bit & 31));
+            }
+        }
         for (int l = 0; l < L; ++l) {
-            prow[g * L + l] = 0.0;
-            crow[g * L + l] = 0;
+            double s = 0.0;
+            uint32_t c = 0;
+#pragma unroll
+            for (int i = 0; i < G; ++i)
+                if (lv[i] == (uint8_t)l) {
+                    s += (double)mag[i];
+                    ++c;
+                }
+            prow[g * L + l] = s;
+            crow[g * L + l] = c;
         }
-        for (int i = 0; i < kGroup; ++i) {
-            const int64_t k = g * kGroup + i;
-            if (k >= n) break;
-            const float x = v[k];
-            const double m = fabs((double)x);
-            const uint32_t l = interval_of(m, edges, L);
-            const uint32_t code = l | ((__float_as_uint(x) >> 31) << (q - 1));
-            const uint32_t bit = (uint32_t)i * (uint32_t)q;
-            words[bit >> 5] |= code << (bit & 31);
-            if ((bit & 31) + q > 32) words[(bit >> 5) + 1] |= code >> (32 - (bit & 31));
-            prow[g * L + l] += m;                    // index order inside the group
-            crow[g * L + l] += 1;
-        }
-        const int64_t w0 = g * q;                    // 32 values * q bits = q words
+        const int64_t w0 = g * gw;
         const int64_t n_words = ((int64_t)n * q + 31) / 32;
-        for (int w = 0; w < q; ++w)
+        for (int w = 0; w < gw; ++w)
             if (w0 + w < n_words) out[w0 + w] = words[w];
     }
     __syncthreads();
-    // means: thread l adds the groups' partial sums in group order
-    if (t < (uint32_t)L) {
+    // means: one wavefront per interval; lane j adds the partial sums of groups j, j+64, ...
+    // and the lanes are then added in a fixed tree, so the result does not depend on timing
+    for (int l = (int)(t / 64); l < L; l += kThreads / 64) {
         double s = 0.0;
-        uint64_t c = 0;
-        for (int64_t g = 0; g < n_groups; ++g) {
-            s += prow[g * L + t];
-            c += crow[g * L + t];
+        uint32_t c = 0;
+        for (int64_t g = t & 63; g < n_groups; g += 64) {
+            s += prow[g * L + l];
+            c += crow[g * L + l];
         }
-        means[(int64_t)row * L + t] = c ? (float)(s / (double)c) : 0.0f;
+        for (int o = 32; o >= 1; o >>= 1) {
+            s += __shfl_xor(s, o, 64);
+            c += __shfl_xor(c, o, 64);
+        }
+        if ((t & 63) == 0) means[(int64_t)row * L + l] = c ? (float)(s / (double)c) : 0.0f;
     }
 }
 
@@ -145,7 +174,7 @@ extern "C" {
 size_t mv_quant_scratch_bytes(int64_t n, int32_t rows, int32_t q)
 {
     if (n < 1 || rows < 1 || q < 2 || q > 8) return 0;
-    const int64_t groups = (n + mvq::kGroup - 1) / mvq::kGroup;
+    const int64_t groups = (n + mvq::group_size(q) - 1) / mvq::group_size(q);
     return (size_t)rows * (size_t)groups * (size_t)(1 << (q - 1)) * (sizeof(double) + sizeof(uint32_t)) + 256;
 }
 
@@ -157,14 +186,23 @@ mv_status mv_quant_encode(const float* vals, int64_t ld_vals, int64_t n, int32_t
     if (n < 1 || rows < 1 || rows > 65535 || q < 2 || q > 8 || ld_vals < n) return MV_ERR_INVALID_ARG;
     if (ld_words < (n * q + 31) / 32) return MV_ERR_INVALID_ARG;
     if (scratch_bytes < mv_quant_scratch_bytes(n, rows, q)) return MV_ERR_INVALID_ARG;
-    const int64_t groups = (n + mvq::kGroup - 1) / mvq::kGroup;
+    const int64_t groups = (n + mvq::group_size(q) - 1) / mvq::group_size(q);
     const int L = 1 << (q - 1);
     uintptr_t base = (reinterpret_cast<uintptr_t>(scratch) + 255) & ~(uintptr_t)255;
     double* partial = reinterpret_cast<double*>(base);
     uint32_t* pcount = reinterpret_cast<uint32_t*>(base + (size_t)rows * groups * L * sizeof(double));
-    hipLaunchKernelGGL(mvq::quant_encode_kernel, dim3((uint32_t)rows), dim3(mvq::kThreads), 0,
-                       static_cast<hipStream_t>(stream), vals, ld_vals, n, q, streams, ld_words, means, partial,
-                       pcount, groups);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+#define MV_QUANT_LAUNCH(Q)                                                                                     \
+    case Q:                                                                                                    \
+        hipLaunchKernelGGL(mvq::quant_encode_kernel<Q>, dim3((uint32_t)rows), dim3(mvq::kThreads), 0, st, vals, \
+                           ld_vals, n, streams, ld_words, means, partial, pcount, groups);                     \
+        break;
+    switch (q) {
+        MV_QUANT_LAUNCH(2) MV_QUANT_LAUNCH(3) MV_QUANT_LAUNCH(4) MV_QUANT_LAUNCH(5)
+        MV_QUANT_LAUNCH(6) MV_QUANT_LAUNCH(7) MV_QUANT_LAUNCH(8)
+        default: return MV_ERR_INVALID_ARG;
+    }
+#undef MV_QUANT_LAUNCH
     return hipGetLastError() == hipSuccess ? MV_OK : MV_ERR_DEVICE;
 }
 
