@@ -92,49 +92,89 @@ struct ChunkMap {                // what a chunk does to the parse, for one entr
     uint8_t  exit_state;
     uint8_t  codes;              // codes begun in the chunk (at most 64)
     uint8_t  closed;             // blocks closed in the chunk (at most 64)
-    uint8_t  pad;
 };
 
-__device__ __forceinline__ ChunkMap run_chunk(const uint32_t* __restrict__ words, uint64_t first, uint64_t last,
-                                              uint32_t state, uint32_t B)
+// up to 64 stream bits from bit `first` (a multiple of 64), first bit in bit 0;
+// bits at or beyond `total` read as zero
+__device__ __forceinline__ uint64_t load_chunk(const uint32_t* __restrict__ words, uint64_t first, uint64_t total)
 {
-    // bits [first, last); state = offset bits still to skip
-    ChunkMap m = {0, 0, 0, 0};
-    uint64_t k = first;
-    while (k < last) {
-        if (state) {
-            const uint64_t skip = min((uint64_t)state, last - k);
-            k += skip;
-            state -= (uint32_t)skip;
-        } else if (stream_bit(words, k)) {
-            ++m.codes;
-            state = B;
-            ++k;
-        } else {
-            ++m.closed;
-            ++k;
-        }
+    const uint64_t n_words = (total + 31) / 32, i = first >> 5;
+    uint64_t v = (i < n_words) ? words[i] : 0u;
+    if (i + 1 < n_words) v |= (uint64_t)words[i + 1] << 32;
+    const uint64_t len = total - first;
+    return len < 64 ? (v & ((1ull << len) - 1)) : v;
+}
+
+// `len` (at most 31) stream bits from bit k, first bit in bit 0; zero beyond `total`
+__device__ __forceinline__ uint32_t load_field(const uint32_t* __restrict__ words, uint64_t k, uint32_t len,
+                                               uint64_t total)
+{
+    const uint64_t n_words = (total + 31) / 32, i = k >> 5;
+    uint64_t v = (i < n_words) ? words[i] : 0u;
+    if (i + 1 < n_words) v |= (uint64_t)words[i + 1] << 32;
+    uint32_t f = (uint32_t)(v >> (k & 31u)) & ((1u << len) - 1u);
+    if (k + len > total) f &= (k < total) ? ((1u << (uint32_t)(total - k)) - 1u) : 0u;
+    return f;
+}
+
+// Parse the `len` bits of a chunk held in `w`, entering with `state` offset bits
+// still to skip.  Runs of zero flags are taken in one step, so the loop runs once
+// per code.
+__device__ __forceinline__ ChunkMap run_chunk(uint64_t w, uint32_t len, uint32_t state, uint32_t B)
+{
+    ChunkMap m = {0, 0, 0};
+    uint32_t j = min(state, len);
+    state -= j;
+    while (j < len) {
+        const uint64_t rest = w >> j;
+        const uint32_t zeros = rest ? (uint32_t)__builtin_ctzll(rest) : 64u;
+        const uint32_t run = min(zeros, len - j);
+        m.closed += (uint8_t)run;
+        j += run;
+        if (j >= len) break;
+        ++m.codes;                                   // flag bit, then B offset bits
+        const uint32_t end = j + 1 + B;
+        state = end > len ? end - len : 0;
+        j = min(end, len);
     }
     m.exit_state = (uint8_t)state;
     return m;
 }
 
-// maps[row][chunk][state]
+// Three byte tables per row, each [chunk][state] with B + 1 states per chunk:
+// exit state, codes begun, blocks closed.
+struct MapTables {
+    uint8_t* exit_state;
+    uint8_t* codes;
+    uint8_t* closed;
+};
+
+__device__ __forceinline__ MapTables row_tables(uint8_t* base, uint64_t max_chunks, uint32_t row)
+{
+    const uint64_t per_table = max_chunks * (kMaxB + 1);
+    uint8_t* r = base + (uint64_t)row * 3 * per_table;
+    return MapTables{r, r + per_table, r + 2 * per_table};
+}
+
 __global__ __launch_bounds__(kThreads) void codec_chunk_maps_kernel(
     const uint32_t* __restrict__ streams, int64_t ld_words, const unsigned long long* __restrict__ n_bits,
-    uint32_t B, ChunkMap* __restrict__ maps, uint64_t max_chunks)
+    uint32_t B, uint8_t* __restrict__ maps, uint64_t max_chunks)
 {
     const uint32_t row = blockIdx.y;
     const uint64_t total = n_bits[row];
     const uint64_t n_chunks = (total + kChunkBits - 1) / kChunkBits;
     const uint32_t* words = streams + (int64_t)row * ld_words;
     const uint32_t n_states = B + 1;
+    const MapTables tb = row_tables(maps, max_chunks, row);
     for (uint64_t item = (uint64_t)blockIdx.x * kThreads + threadIdx.x; item < n_chunks * n_states;
          item += (uint64_t)gridDim.x * kThreads) {
         const uint64_t c = item / n_states;
         const uint32_t s = (uint32_t)(item % n_states);
         const uint64_t first = c * kChunkBits, last = min(first + kChunkBits, total);
-        maps[((uint64_t)row * max_chunks + c) * (kMaxB + 1) + s] = run_chunk(words, first, last, s, B);
+        const ChunkMap m = run_chunk(load_chunk(words, first, total), (uint32_t)(last - first), s, B);
+        tb.exit_state[item] = m.exit_state;      // compact: index = chunk * n_states + state
+        tb.codes[item] = m.codes;
+        tb.closed[item] = m.closed;
     }
 }
 
@@ -144,74 +184,102 @@ struct Entry {                   // the parse at the start of a chunk
     uint32_t closed;             // blocks closed before the chunk
 };
 
-// One workgroup per row: thread t owns a contiguous range of chunks.  It composes
-// the range's maps for every entry state; thread 0 then walks the 1024 range maps
-// with the true state; every thread finally walks its range with its true entry
-// and records each chunk's entry.
+constexpr int kExitLds = 24576;  // exit-state bytes staged in LDS when the row's table fits
+
+// One workgroup per row.  Thread t owns a contiguous range of chunks and composes
+// the range's exit states for every entry state; 32 threads compose 32 ranges each;
+// one thread walks the 32 groups from state 0; the true entry states then flow back
+// down the two levels, and every thread walks its range for real, counting the codes
+// and closed blocks before each chunk (a workgroup scan joins the ranges).
 __global__ __launch_bounds__(kWalkThreads) void codec_walk_kernel(
-    const unsigned long long* __restrict__ n_bits, uint32_t B, const ChunkMap* __restrict__ maps, uint64_t max_chunks,
+    const unsigned long long* __restrict__ n_bits, uint32_t B, uint8_t* __restrict__ maps, uint64_t max_chunks,
     Entry* __restrict__ entries, uint32_t* __restrict__ counts_out)
 {
+    __shared__ uint8_t  ex_lds[kExitLds];
     __shared__ uint8_t  r_exit[kWalkThreads][kMaxB + 1];
-    __shared__ uint32_t r_codes[kWalkThreads][2];     // only for the true entry state (filled in the second sweep)
-    __shared__ Entry    r_entry[kWalkThreads];
+    __shared__ uint8_t  g_exit[32][kMaxB + 1];
+    __shared__ uint8_t  r_state[kWalkThreads];
+    __shared__ uint8_t  g_state[32];
+    __shared__ unsigned long long wave_sum[kWalkThreads / 64 + 1];
     const uint32_t row = blockIdx.x, t = threadIdx.x;
     const uint64_t total = n_bits[row];
     const uint64_t n_chunks = (total + kChunkBits - 1) / kChunkBits;
     const uint64_t per = (n_chunks + kWalkThreads - 1) / kWalkThreads;
     const uint64_t c0 = min((uint64_t)t * per, n_chunks), c1 = min(c0 + per, n_chunks);
-    const ChunkMap* rmaps = maps + (uint64_t)row * max_chunks * (kMaxB + 1);
+    const MapTables tb = row_tables(maps, max_chunks, row);
     const uint32_t n_states = B + 1;
-    // sweep 1: exit state of the range for every entry state
-    for (uint32_t s = 0; s < n_states; ++s) {
+    const bool staged = n_chunks * n_states <= (uint64_t)kExitLds;
+    if (staged)
+        for (uint64_t i = t; i < n_chunks * n_states; i += kWalkThreads) ex_lds[i] = tb.exit_state[i];
+    __syncthreads();
+    const uint8_t* ex = staged ? ex_lds : tb.exit_state;
+
+    for (uint32_t s = 0; s < n_states; ++s) {                 // range maps
         uint32_t st = s;
-        for (uint64_t c = c0; c < c1; ++c) st = rmaps[c * (kMaxB + 1) + st].exit_state;
+        for (uint64_t c = c0; c < c1; ++c) st = ex[c * n_states + st];
         r_exit[t][s] = (uint8_t)st;
     }
     __syncthreads();
-    // true entry state of every range
-    if (t == 0) {
+    if (t < 32)                                               // group maps: 32 ranges each
+        for (uint32_t s = 0; s < n_states; ++s) {
+            uint32_t st = s;
+            for (uint32_t r = t * 32; r < t * 32 + 32; ++r) st = r_exit[r][st];
+            g_exit[t][s] = (uint8_t)st;
+        }
+    __syncthreads();
+    if (t == 0) {                                             // true entry state of every group
         uint32_t st = 0;
-        for (uint32_t r = 0; r < kWalkThreads; ++r) {
-            r_entry[r].state = st;
+        for (uint32_t g = 0; g < 32; ++g) {
+            g_state[g] = (uint8_t)st;
+            st = g_exit[g][st];
+        }
+    }
+    __syncthreads();
+    if (t < 32) {                                             // ... of every range
+        uint32_t st = g_state[t];
+        for (uint32_t r = t * 32; r < t * 32 + 32; ++r) {
+            r_state[r] = (uint8_t)st;
             st = r_exit[r][st];
         }
     }
     __syncthreads();
-    // sweep 2: codes and closed blocks of the range on its true path
-    {
-        uint32_t st = r_entry[t].state, codes = 0, closed = 0;
-        for (uint64_t c = c0; c < c1; ++c) {
-            const ChunkMap m = rmaps[c * (kMaxB + 1) + st];
-            codes += m.codes;
-            closed += m.closed;
-            st = m.exit_state;
-        }
-        r_codes[t][0] = codes;
-        r_codes[t][1] = closed;
+    // codes and closed blocks of the range on its true path, then their prefix over the ranges
+    uint32_t st = r_state[t], codes = 0, closed = 0;
+    for (uint64_t c = c0; c < c1; ++c) {
+        codes += tb.codes[c * n_states + st];
+        closed += tb.closed[c * n_states + st];
+        st = ex[c * n_states + st];
     }
+    unsigned long long v = ((unsigned long long)codes << 32) | closed, incl = v;
+    const uint32_t lane = t & 63, wave = t / 64;
+    for (int o = 1; o < 64; o <<= 1) {
+        const unsigned long long up = __shfl_up(incl, o, 64);
+        if (lane >= (uint32_t)o) incl += up;
+    }
+    if (lane == 63) wave_sum[wave] = incl;
     __syncthreads();
     if (t == 0) {
-        uint32_t codes = 0, closed = 0;
-        for (uint32_t r = 0; r < kWalkThreads; ++r) {
-            r_entry[r].codes = codes;
-            r_entry[r].closed = closed;
-            codes += r_codes[r][0];
-            closed += r_codes[r][1];
+        unsigned long long run = 0;
+        for (int w = 0; w < kWalkThreads / 64; ++w) {
+            const unsigned long long x = wave_sum[w];
+            wave_sum[w] = run;
+            run += x;
         }
-        counts_out[row] = codes;
+        wave_sum[kWalkThreads / 64] = run;
+        counts_out[row] = (uint32_t)(run >> 32);
     }
     __syncthreads();
-    // sweep 3: every chunk's entry
-    {
-        Entry e = r_entry[t];
-        for (uint64_t c = c0; c < c1; ++c) {
-            entries[(uint64_t)row * max_chunks + c] = e;
-            const ChunkMap m = rmaps[c * (kMaxB + 1) + e.state];
-            e.codes += m.codes;
-            e.closed += m.closed;
-            e.state = m.exit_state;
-        }
+    const unsigned long long before = wave_sum[wave] + incl - v;
+    Entry e;
+    e.state = r_state[t];
+    e.codes = (uint32_t)(before >> 32);
+    e.closed = (uint32_t)before;
+    for (uint64_t c = c0; c < c1; ++c) {                      // every chunk's entry
+        entries[(uint64_t)row * max_chunks + c] = e;
+        const uint64_t i = c * n_states + e.state;
+        e.codes += tb.codes[i];
+        e.closed += tb.closed[i];
+        e.state = ex[i];
     }
 }
 
@@ -227,21 +295,24 @@ __global__ __launch_bounds__(kThreads) void codec_emit_kernel(
     uint32_t* out = idx_out + (int64_t)row * ld_idx;
     for (uint64_t c = (uint64_t)blockIdx.x * kThreads + threadIdx.x; c < n_chunks; c += (uint64_t)gridDim.x * kThreads) {
         Entry e = entries[(uint64_t)row * max_chunks + c];
-        const uint64_t first = c * kChunkBits, last = min(first + kChunkBits, total);
-        uint64_t k = first + min((uint64_t)e.state, last - first);     // rest of a code begun earlier
-        while (k < last) {
-            if (stream_bit(words, k)) {
-                uint32_t off = 0;
-                for (uint32_t q = 0; q < B; ++q)                       // may run into the next chunks
-                    off = (off << 1) | ((k + 1 + q < total) ? stream_bit(words, k + 1 + q) : 0u);
-                const uint64_t pos = (uint64_t)e.closed * block_len + off;
-                if (e.codes < max_n && pos < (uint64_t)d) out[e.codes] = (uint32_t)pos;
-                ++e.codes;
-                k += 1 + B;
-            } else {
-                ++e.closed;
-                ++k;
-            }
+        const uint64_t first = c * kChunkBits;
+        const uint32_t len = (uint32_t)(min(first + kChunkBits, total) - first);
+        const uint64_t w = load_chunk(words, first, total);
+        uint32_t j = min(e.state, len);                                // rest of a code begun earlier
+        while (j < len) {
+            const uint64_t rest = w >> j;
+            const uint32_t zeros = rest ? (uint32_t)__builtin_ctzll(rest) : 64u;
+            const uint32_t run = min(zeros, len - j);
+            e.closed += run;
+            j += run;
+            if (j >= len) break;
+            // the offset lies MSB first in the stream and may run into the next chunk
+            const uint32_t field = B ? load_field(words, first + j + 1, B, total) : 0u;
+            const uint32_t off = B ? (__brev(field) >> (32 - B)) : 0u;
+            const uint64_t pos = (uint64_t)e.closed * block_len + off;
+            if (e.codes < max_n && pos < (uint64_t)d) out[e.codes] = (uint32_t)pos;
+            ++e.codes;
+            j += 1 + B;
         }
     }
 }
@@ -260,7 +331,7 @@ size_t mv_codec_scratch_bytes(uint64_t max_bits, int32_t rows)
 {
     if (rows < 1) return 0;
     const uint64_t chunks = (max_bits + mvc::kChunkBits - 1) / mvc::kChunkBits;
-    return (size_t)rows * chunks * ((mvc::kMaxB + 1) * sizeof(mvc::ChunkMap) + sizeof(mvc::Entry)) + 256;
+    return (size_t)rows * chunks * (3 * (mvc::kMaxB + 1) + sizeof(mvc::Entry)) + 512;
 }
 
 mv_status mv_codec_encode(const uint32_t* idx, int64_t ld_idx, const uint32_t* counts, int64_t counts_stride,
@@ -298,9 +369,9 @@ mv_status mv_codec_decode(const uint32_t* streams, int64_t ld_words, const uint6
     const uint64_t max_chunks = (max_bits + mvc::kChunkBits - 1) / mvc::kChunkBits;
     if (max_chunks == 0) return MV_ERR_INVALID_ARG;
     uintptr_t base = (reinterpret_cast<uintptr_t>(scratch) + 255) & ~(uintptr_t)255;
-    mvc::ChunkMap* maps = reinterpret_cast<mvc::ChunkMap*>(base);
-    mvc::Entry* entries =
-        reinterpret_cast<mvc::Entry*>(base + (size_t)rows * max_chunks * (mvc::kMaxB + 1) * sizeof(mvc::ChunkMap));
+    uint8_t* maps = reinterpret_cast<uint8_t*>(base);
+    const size_t maps_bytes = ((size_t)rows * max_chunks * 3 * (mvc::kMaxB + 1) + 255) & ~(size_t)255;
+    mvc::Entry* entries = reinterpret_cast<mvc::Entry*>(base + maps_bytes);
     const uint32_t B = (uint32_t)mvc::offset_bits(block_len);
     hipStream_t st = static_cast<hipStream_t>(stream);
     const unsigned long long* nb = reinterpret_cast<const unsigned long long*>(n_bits);
