@@ -365,7 +365,7 @@ constexpr int kSelBins = 2048;   // radix-select digit: 11, 10, 10 bits of the 3
 constexpr int kKeyBins = 4096;   // exact magnitudes inside one fine-histogram bin (1 << kFineShift)
 constexpr int kKeep    = 32;     // candidate keys a thread of mv_row_select can hold in registers
 constexpr int kTieCap  = 8192;   // ties with the K-th magnitude that fit the LDS list
-constexpr int kBinCap  = 1024;   // candidates of one fine-histogram bin ranked by brute force
+constexpr int kRankCap = 256;    // at most this many entries are ranked by counting (quadratic work)
 
 __device__ __forceinline__ int      sel_shift(int pass) { return pass == 0 ? 20 : pass == 1 ? 10 : 0; }
 __device__ __forceinline__ uint32_t sel_dmask(int pass) { return pass == 0 ? 2047u : 1023u; }
@@ -524,11 +524,12 @@ struct SelectLds {
     uint64_t scan[kRowThreads / kWave + 1];
 };
 
-// The take-th SMALLEST of the n coordinates in lds.ties[0..n): ranked by counting
-// when few, else by a radix select on (0x7FFFFFFF - coordinate).
+// The take-th SMALLEST of the n distinct coordinates in lds.ties[0..n): ranked by
+// counting when few; else narrowed by one histogram and then ranked by counting;
+// a radix select on (0x7FFFFFFF - coordinate) if they crowd into one bin.
 __device__ __forceinline__ uint32_t smallest_coordinate(SelectLds& lds, uint32_t n, uint32_t take)
 {
-    if (n <= (uint32_t)kRowThreads) {
+    if (n <= (uint32_t)kRankCap) {
         if (threadIdx.x < 4) lds.ties[n + threadIdx.x] = 0xFFFFFFFFu;   // pad to a multiple of 4, ranked last
         __syncthreads();
         if (threadIdx.x < n) {
@@ -541,6 +542,66 @@ __device__ __forceinline__ uint32_t smallest_coordinate(SelectLds& lds, uint32_t
                 below += (o.x < mine) + (o.y < mine) + (o.z < mine) + (o.w < mine);
             }
             if (below == take - 1) lds.bcast[0] = mine;
+        }
+        __syncthreads();
+        const uint32_t r = lds.bcast[0];
+        __syncthreads();
+        return r;
+    }
+    // Many ties: their coordinates are spread over the row, so one histogram of the
+    // coordinate's leading bits (relative to the ties' own range) isolates a handful
+    // around the wanted rank, which are then ranked by counting.
+    const uint32_t t = threadIdx.x;
+    if (t == 0) {
+        lds.bcast[0] = 0u;
+        lds.bcast[1] = 0xFFFFFFFFu;
+    }
+    for (int b = t; b < kSelBins; b += kRowThreads) lds.hist[b] = 0;
+    __syncthreads();
+    uint32_t mx = 0u, mn = 0xFFFFFFFFu;
+    for (uint32_t i = t; i < n; i += kRowThreads) {
+        const uint32_t c = lds.ties[i];
+        mx = max(mx, c);
+        mn = min(mn, c);
+    }
+    for (int o = 1; o < kWave; o <<= 1) {
+        mx = max(mx, (uint32_t)__shfl_xor(mx, o, kWave));
+        mn = min(mn, (uint32_t)__shfl_xor(mn, o, kWave));
+    }
+    if (lane_id() == 0) {
+        atomicMax(&lds.bcast[0], mx);
+        atomicMin(&lds.bcast[1], mn);
+    }
+    __syncthreads();
+    mx = lds.bcast[0];
+    mn = lds.bcast[1];
+    const uint32_t span = mx - mn;
+    const uint32_t shift = span < (uint32_t)kSelBins ? 0u : (32u - (uint32_t)__clz(span)) - 11u;
+    // bins ordered like the select's keys: the smallest coordinates in the highest bin
+    for (uint32_t i = t; i < n; i += kRowThreads)
+        atomicAdd(&lds.hist[(uint32_t)(kSelBins - 1) - ((lds.ties[i] - mn) >> shift)], 1u);
+    __syncthreads();                                  // also: everyone has read bcast
+    uint32_t bin, want, in_bin;
+    find_rank_bin<kSelBins>(lds.hist, lds.scan, lds.bcast, take, bin, want, in_bin);
+    if (in_bin <= (uint32_t)kRowThreads) {            // uniform
+        if (t == 0) lds.n_list = 0;
+        __syncthreads();
+        for (uint32_t i = t; i < n; i += kRowThreads) {
+            const uint32_t c = lds.ties[i];
+            if ((uint32_t)(kSelBins - 1) - ((c - mn) >> shift) == bin) lds.hist[atomicAdd(&lds.n_list, 1u)] = c;
+        }
+        if (t < 4) lds.hist[in_bin + t] = 0xFFFFFFFFu;
+        __syncthreads();
+        if (t < in_bin) {
+            const uint32_t mine = lds.hist[t];
+            const u32x4* tv = reinterpret_cast<const u32x4*>(lds.hist);
+            uint32_t below = 0;
+#pragma unroll 4
+            for (uint32_t j = 0; j < (in_bin + 3) / 4; ++j) {
+                const u32x4 o = tv[j];
+                below += (o.x < mine) + (o.y < mine) + (o.z < mine) + (o.w < mine);
+            }
+            if (below == want - 1) lds.bcast[0] = mine;
         }
         __syncthreads();
         const uint32_t r = lds.bcast[0];
@@ -577,7 +638,7 @@ __device__ __forceinline__ void select_among_candidates(const Keys& keys, const 
         __syncthreads();
         uint32_t bin, want, in_bin;
         find_rank_bin<kFineBins>(lds.hist, lds.scan, lds.bcast, K, bin, want, in_bin);
-        if (in_bin <= (uint32_t)kBinCap) {        // uniform
+        if (in_bin <= (uint32_t)kRankCap) {       // uniform
             // few candidates in that bin: collect them (magnitude in hist[], coordinate
             // in ties[]) and rank them by brute force under (magnitude desc, coordinate
             // asc); the one with exactly want-1 others ahead is the last of the top K
@@ -677,21 +738,22 @@ __global__ __launch_bounds__(kRowThreads) void mv_row_select(
 {
     __shared__ SelectLds lds;
     const uint32_t row = blockIdx.x, t = threadIdx.x;
+    // The first kKeep * kRowThreads list entries are fetched before the row's
+    // candidate count is known (the list's storage holds cap entries; what lies at
+    // or beyond the count is ignored later), so the two loads do not queue up.
+    const u32x2* crow = cand + (size_t)row * cap;
+    uint32_t k[kKeep];
+#pragma unroll
+    for (int q = 0; q < kKeep; ++q) {
+        k[q] = crow[min((uint32_t)q * kRowThreads + t, cap - 1)].x;
+        if ((q & 7) == 7) __builtin_amdgcn_sched_barrier(0);   // keep address arithmetic from piling up
+    }
     const uint32_t C = row_count[row];
 
     if (C >= K && C <= cap) {
-        const u32x2* crow = cand + (size_t)row * cap;
         const uint32_t tau = tau_bits[row];
         uint32_t kth, tie_cut, path;
         if (C <= (uint32_t)kKeep * kRowThreads) {
-            // entries past C are clamped to the last candidate and ignored later
-            uint32_t k[kKeep];
-            const uint32_t last = C - 1;
-#pragma unroll
-            for (int q = 0; q < kKeep; ++q) {
-                k[q] = crow[min((uint32_t)q * kRowThreads + t, last)].x;
-                if ((q & 7) == 7) __builtin_amdgcn_sched_barrier(0);   // keep address arithmetic from piling up
-            }
             const KeysInRegs src{k, C};
             select_among_candidates(src, crow, C, K, tau, lds, kth, tie_cut, path);
         } else {

@@ -254,7 +254,7 @@ def _levels_row(rng, d, groups, noise=1e-3):
     return row
 
 
-@pytest.mark.parametrize("case", ["ties_in_lds_by_counting", "ties_in_lds_by_radix", "ties_beyond_lds",
+@pytest.mark.parametrize("case", ["ties_in_lds_by_counting", "ties_in_lds_by_histogram", "ties_beyond_lds",
                                   "kth_far_above_threshold", "more_candidates_than_registers"])
 def test_every_route_of_the_row_select(oracle, case):
     """Rows built to drive mv_row_select down each of its routes: crowded
@@ -265,7 +265,7 @@ def test_every_route_of_the_row_select(oracle, case):
     N, d, K = 3, 300007, 3000
     if case == "ties_in_lds_by_counting":
         groups = [(2600, 2.0, 3.0), (900, 1.0, 1.0)]            # 900 ties, 400 taken
-    elif case == "ties_in_lds_by_radix":
+    elif case == "ties_in_lds_by_histogram":
         groups = [(2000, 2.0, 3.0), (5000, 1.0, 1.0)]           # 5000 ties, 1000 taken
     elif case == "ties_beyond_lds":
         groups = [(2000, 2.0, 3.0), (20000, 1.0, 1.0)]          # 20000 ties, 1000 taken
@@ -293,3 +293,31 @@ def test_every_route_of_the_row_select(oracle, case):
         assert all(p == 2 for p in path)
     if case == "more_candidates_than_registers":
         assert min(cand) > 32768
+
+
+def test_tie_cut_inside_a_run_of_neighbouring_ties(oracle):
+    """6000 coordinates tie at the K-th magnitude; 1500 of them are neighbours at the
+    start of a long row and the cut falls among these, so the narrowing by the
+    coordinates' leading bits leaves more than a workgroup can rank by counting."""
+    rng = np.random.default_rng(77)
+    N, d, K = 2, 5000011, 30000
+    g = np.empty((N, d), np.float32)
+    for n in range(N):
+        row = (rng.standard_normal(d) * 1e-3).astype(np.float32)
+        far = 10000 + rng.permutation(d - 10000)
+        row[far[:29000]] = rng.uniform(2.0, 3.0, 29000).astype(np.float32)
+        row[far[29000:59000]] = rng.uniform(0.5, 0.9, 30000).astype(np.float32)
+        row[far[59000:63500]] = 1.0
+        row[100 + 7 * n:1600 + 7 * n] = -1.0                  # the neighbours; 1000 of them are taken
+        g[n] = row
+    e = np.zeros_like(g)
+    say("tie cut among neighbouring ties N=%d d=%d K=%d" % (N, d, K))
+    with GpuStepper(N, d, K) as gs:
+        gs.set_error(e)
+        gs.set_grads(g)
+        gs.step()
+        got = gs.fetch()
+        cand, _, path = gs.row_stats()
+    say("  candidates %s path %s" % (cand, path))
+    assert all(p != 1 for p in path), "meant for the candidate-list routes"
+    assert_matches_oracle(got, oracle.vote_step(g, e, K), "neighbouring ties")
