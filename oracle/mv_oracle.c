@@ -199,11 +199,16 @@ void mvo_error_update(const float* delta_bar, int64_t d,
  *              one OpenMP task per worker row; the arithmetic is unchanged.
  * Returns 0 on success, -1 on bad arguments / allocation failure.
  */
-int mvo_vote_step(const void* grads, int64_t ld_g, int32_t grad_is_bf16,
-                  float* err, int64_t ld_e,
-                  int32_t N, int64_t d, int64_t K, int32_t reduce_mean,
-                  uint32_t* worker_idx, uint8_t* votes, uint32_t* mask_idx, float* agg,
-                  int32_t threads)
+int mvo_rs_mask_keys(const uint8_t* votes, int64_t d, int64_t K, const float* rand_exp, uint32_t* mask_idx);
+
+/* rand_exp == NULL: the mask is the K most voted coordinates (Algorithm 1, the
+ * line with S_top); else the randomly selected one (the line with
+ * S_rand-weighted), see mvo_rs_mask_keys. */
+static int vote_step_impl(const void* grads, int64_t ld_g, int32_t grad_is_bf16,
+                          float* err, int64_t ld_e,
+                          int32_t N, int64_t d, int64_t K, int32_t reduce_mean, const float* rand_exp,
+                          uint32_t* worker_idx, uint8_t* votes, uint32_t* mask_idx, float* agg,
+                          int32_t threads)
 {
     if (N < 1 || N > 255 || d < 1 || d > 0x7FFFFFFF || K < 1 || K > d) return -1;
     if (ld_g < d || ld_e < d) return -1;
@@ -238,7 +243,10 @@ int mvo_vote_step(const void* grads, int64_t ld_g, int32_t grad_is_bf16,
         return -1;
     }
 
-    if (mvo_votes(worker_idx, N, K, d, votes) != 0 || mvo_mask(votes, d, K, mask_idx) != 0) {
+    int mask_rc = mvo_votes(worker_idx, N, K, d, votes);
+    if (mask_rc == 0)
+        mask_rc = rand_exp ? mvo_rs_mask_keys(votes, d, K, rand_exp, mask_idx) : mvo_mask(votes, d, K, mask_idx);
+    if (mask_rc != 0) {
         free(delta_bar);
         return -1;
     }
@@ -252,6 +260,153 @@ int mvo_vote_step(const void* grads, int64_t ld_g, int32_t grad_is_bf16,
 
     free(delta_bar);
     return 0;
+}
+
+int mvo_vote_step(const void* grads, int64_t ld_g, int32_t grad_is_bf16,
+                  float* err, int64_t ld_e,
+                  int32_t N, int64_t d, int64_t K, int32_t reduce_mean,
+                  uint32_t* worker_idx, uint8_t* votes, uint32_t* mask_idx, float* agg,
+                  int32_t threads)
+{
+    return vote_step_impl(grads, ld_g, grad_is_bf16, err, ld_e, N, d, K, reduce_mean, NULL,
+                          worker_idx, votes, mask_idx, agg, threads);
+}
+
+/* ------------------------------------------------------------------ */
+/* majority voting with random selection (Algorithm 1, S_rand-weighted) */
+/* ------------------------------------------------------------------ */
+
+/*
+ * Sec. 2 (the paragraph after Algorithm 1): the winning positions are sampled
+ * with probabilities proportional to the received votes; Sec. 4.2: indices are
+ * selected at random "using the votes" until K distinct ones are selected.
+ *
+ * Reading (the paper names no sampler and no random generator): positions are
+ * drawn one at a time, each draw independent with P(j) = votes[j] / sum(votes),
+ * a position drawn before is drawn again in vain, and the procedure stops at K
+ * distinct positions.  mvo_rs_mask_draws is that procedure, fed with uniform
+ * numbers from the caller.  Discarding repeats means each NEW position is drawn
+ * in proportion to its votes among the positions not yet selected (successive
+ * sampling without replacement).
+ *
+ * mvo_rs_mask_keys states the same distribution in a form that does not depend
+ * on the order of the draws: give every voted position j an independent
+ * exponential clock of rate votes[j], i.e. the time rand_exp[j] / votes[j] with
+ * rand_exp[j] ~ Exp(1) supplied by the caller, and select the K positions
+ * whose clocks ring first.  The first clock to ring is j with probability
+ * votes[j] / sum(votes), and the clocks are memoryless, so the order of ringing
+ * is a successive sample -- the two functions agree in distribution, not draw
+ * by draw.  The key is one fp32 division; ties (equal times) go to the lowest
+ * position; positions without a vote are never selected.  "Parity unpinned" by
+ * the paper beyond the proportionality of the probabilities to the votes.
+ */
+
+/* The sequential procedure.  u: n_u numbers in [0, 1).  Writes the K selected
+ * positions ascending; returns the number of draws used, or -1 (bad arguments,
+ * fewer than K voted positions, or u exhausted). */
+int64_t mvo_rs_mask_draws(const uint8_t* votes, int64_t d, int64_t K, const double* u, int64_t n_u,
+                          uint32_t* mask_idx)
+{
+    if (d < 1 || K < 1 || K > d) return -1;
+    int64_t* cum = (int64_t*)malloc((size_t)d * sizeof(int64_t));
+    uint8_t* chosen = (uint8_t*)calloc((size_t)d, 1);
+    if (!cum || !chosen) {
+        free(cum);
+        free(chosen);
+        return -1;
+    }
+    int64_t total = 0, voted = 0;
+    for (int64_t j = 0; j < d; ++j) {
+        total += votes[j];
+        voted += votes[j] != 0;
+        cum[j] = total; /* votes of positions 0..j */
+    }
+    int64_t used = -1;
+    if (voted >= K) {
+        int64_t n_chosen = 0, t = 0;
+        while (n_chosen < K && t < n_u) {
+            int64_t x = (int64_t)(u[t] * (double)total); /* the x-th vote, 0 <= x < total */
+            if (x >= total) x = total - 1;
+            ++t;
+            int64_t lo = 0, hi = d - 1; /* first j with cum[j] > x: the position that holds vote x */
+            while (lo < hi) {
+                const int64_t mid = lo + (hi - lo) / 2;
+                if (cum[mid] > x) hi = mid;
+                else lo = mid + 1;
+            }
+            if (!chosen[lo]) {
+                chosen[lo] = 1;
+                ++n_chosen;
+            }
+        }
+        if (n_chosen == K) {
+            used = t;
+            int64_t k = 0;
+            for (int64_t j = 0; j < d; ++j)
+                if (chosen[j]) mask_idx[k++] = (uint32_t)j;
+        }
+    }
+    free(cum);
+    free(chosen);
+    return used;
+}
+
+typedef struct {
+    float    time;
+    uint32_t index;
+} rs_clock;
+
+static int cmp_time_asc_index_asc(const void* pa, const void* pb)
+{
+    const rs_clock* a = (const rs_clock*)pa;
+    const rs_clock* b = (const rs_clock*)pb;
+    if (a->time != b->time) return a->time < b->time ? -1 : 1;
+    return a->index < b->index ? -1 : (a->index > b->index ? 1 : 0);
+}
+
+/* The exponential-clock form.  rand_exp: d non-negative finite fp32 numbers
+ * (only those of voted positions are read).  Returns 0, or -1 (bad arguments or
+ * fewer than K voted positions). */
+int mvo_rs_mask_keys(const uint8_t* votes, int64_t d, int64_t K, const float* rand_exp, uint32_t* mask_idx)
+{
+    if (d < 1 || K < 1 || K > d) return -1;
+    int64_t voted = 0;
+    for (int64_t j = 0; j < d; ++j) voted += votes[j] != 0;
+    if (voted < K) return -1;
+    rs_clock* c = (rs_clock*)malloc((size_t)voted * sizeof(rs_clock));
+    uint32_t* sel = (uint32_t*)malloc((size_t)K * sizeof(uint32_t));
+    if (!c || !sel) {
+        free(c);
+        free(sel);
+        return -1;
+    }
+    int64_t n = 0;
+    for (int64_t j = 0; j < d; ++j)
+        if (votes[j]) {
+            c[n].time = rand_exp[j] / (float)votes[j];
+            c[n].index = (uint32_t)j;
+            ++n;
+        }
+    qsort(c, (size_t)voted, sizeof(rs_clock), cmp_time_asc_index_asc);
+    for (int64_t k = 0; k < K; ++k) sel[k] = c[k].index;
+    qsort(sel, (size_t)K, sizeof(uint32_t), cmp_u32_asc);
+    memcpy(mask_idx, sel, (size_t)K * sizeof(uint32_t));
+    free(c);
+    free(sel);
+    return 0;
+}
+
+/* Algorithm 1 with the S_rand-weighted line: as mvo_vote_step, the mask being
+ * mvo_rs_mask_keys of the step's votes.  rand_exp: d fp32 numbers. */
+int mvo_rs_vote_step(const void* grads, int64_t ld_g, int32_t grad_is_bf16,
+                     float* err, int64_t ld_e,
+                     int32_t N, int64_t d, int64_t K, int32_t reduce_mean, const float* rand_exp,
+                     uint32_t* worker_idx, uint8_t* votes, uint32_t* mask_idx, float* agg,
+                     int32_t threads)
+{
+    if (!rand_exp) return -1;
+    return vote_step_impl(grads, ld_g, grad_is_bf16, err, ld_e, N, d, K, reduce_mean, rand_exp,
+                          worker_idx, votes, mask_idx, agg, threads);
 }
 
 /* ------------------------------------------------------------------ */

@@ -59,6 +59,12 @@ def lib() -> ctypes.CDLL:
         L.mvo_error_update.restype = None
         L.mvo_vote_step.argtypes = [vp, i64, i32, vp, i64, i32, i64, i64, i32, vp, vp, vp, vp, i32]
         L.mvo_vote_step.restype = i32
+        L.mvo_rs_mask_draws.argtypes = [vp, i64, i64, vp, i64, vp]
+        L.mvo_rs_mask_draws.restype = i64
+        L.mvo_rs_mask_keys.argtypes = [vp, i64, i64, vp, vp]
+        L.mvo_rs_mask_keys.restype = i32
+        L.mvo_rs_vote_step.argtypes = [vp, i64, i32, vp, i64, i32, i64, i64, i32, vp, vp, vp, vp, vp, i32]
+        L.mvo_rs_vote_step.restype = i32
         L.mvo_ad_vote_step.argtypes = [vp, i64, i32, vp, i64, i32, i64, i64, i64, i32, vp, vp, vp, vp, vp, vp, vp,
                                        vp, vp, i32]
         L.mvo_ad_vote_step.restype = i32
@@ -190,6 +196,53 @@ def vote_step(grads: np.ndarray, err: np.ndarray, K: int, reduce_mean: bool = Tr
                              _ptr(widx), _ptr(v), _ptr(m), _ptr(agg), int(threads))
     if rc != 0:
         raise ValueError("mvo_vote_step rejected its arguments")
+    return StepResult(widx, v, m, agg, e)
+
+
+# ---------------------------------------------------------------- random selection (Algorithm 1, S_rand-weighted)
+
+def rs_mask_draws(votes: np.ndarray, K: int, u: np.ndarray):
+    """The sequential sampler: draws positions in proportion to their votes, with the
+    uniform numbers u, until K distinct ones are selected.  Returns (mask ascending,
+    draws used)."""
+    v = _c(votes, np.uint8)
+    uu = _c(u, np.float64)
+    m = np.empty(K, np.uint32)
+    used = lib().mvo_rs_mask_draws(_ptr(v), v.size, K, _ptr(uu), uu.size, _ptr(m))
+    if used < 0:
+        raise ValueError("mvo_rs_mask_draws: bad arguments, fewer than K voted positions or too few numbers")
+    return m, int(used)
+
+
+def rs_mask_keys(votes: np.ndarray, K: int, rand_exp: np.ndarray) -> np.ndarray:
+    """The K voted positions whose exponential clocks rand_exp[j] / votes[j] ring first."""
+    v = _c(votes, np.uint8)
+    r = _c(rand_exp, np.float32)
+    assert r.size == v.size
+    m = np.empty(K, np.uint32)
+    if lib().mvo_rs_mask_keys(_ptr(v), v.size, K, _ptr(r), _ptr(m)) != 0:
+        raise ValueError("mvo_rs_mask_keys: bad arguments or fewer than K voted positions")
+    return m
+
+
+def rs_vote_step(grads: np.ndarray, err: np.ndarray, K: int, rand_exp: np.ndarray, reduce_mean: bool = True,
+                 threads: int = 1) -> StepResult:
+    """One vote step whose mask is selected at random in proportion to the votes."""
+    assert grads.ndim == 2 and err.shape == grads.shape
+    is_bf16 = grads.dtype == np.uint16
+    g = _c(grads, np.uint16 if is_bf16 else np.float32)
+    e = np.array(err, dtype=np.float32, order="C", copy=True)
+    N, d = g.shape
+    r = _c(rand_exp, np.float32)
+    assert r.size == d
+    widx = np.empty((N, K), np.uint32)
+    v = np.empty(d, np.uint8)
+    m = np.empty(K, np.uint32)
+    agg = np.empty(K, np.float32)
+    rc = lib().mvo_rs_vote_step(_ptr(g), d, int(is_bf16), _ptr(e), d, N, d, K, int(reduce_mean), _ptr(r),
+                                _ptr(widx), _ptr(v), _ptr(m), _ptr(agg), int(threads))
+    if rc != 0:
+        raise ValueError("mvo_rs_vote_step rejected its arguments")
     return StepResult(widx, v, m, agg, e)
 
 
