@@ -60,9 +60,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="C4", choices=["C1", "C2", "C3", "C4", "C5"])
     ap.add_argument("--grad-sets", type=int, default=2, help="distinct gradient matrices cycled over")
-    ap.add_argument("--scheme", default="mv", choices=["mv", "ad"],
+    ap.add_argument("--scheme", default="mv", choices=["mv", "ad", "rs"],
                     help="mv: majority voting (Algorithm 1); ad: majority voting with add-drop (Algorithm 2), "
-                         "a full first vote untimed, then K_ad = K/10 per step")
+                         "a full first vote untimed, then K_ad = K/10 per step; rs: majority voting with "
+                         "random selection (Algorithm 1, S_rand-weighted), seeded Exp(1) numbers resident in HBM")
     ap.add_argument("--codec", action="store_true",
                     help="also time the sparse position code (Sec. 4.3.1) on the workers' vote lists "
                          "of the last step (untimed extra; needs worker_idx, scheme mv)")
@@ -116,6 +117,14 @@ def main():
     mask = torch.zeros(K, dtype=torch.int32, device=dev)
     agg = torch.zeros(K, dtype=torch.float32, device=dev)
     ad = args.scheme == "ad"
+    rs = args.scheme == "rs"
+    r_dev, r_host0 = [], None
+    if rs:
+        for s in range(max(1, args.grad_sets)):
+            rh = W.selection_clocks(w, s)
+            if s == 0:
+                r_host0 = rh
+            r_dev.append(torch.from_numpy(rh).to(dev))
     ctx = B.mv_begin(B.make_config(N, d, K, B.MV_BF16 if bf16 else B.MV_F32,
                                    flags=B.MV_FLAG_ADD_DROP if ad else 0))
     stream = torch.cuda.current_stream(dev)
@@ -132,6 +141,9 @@ def main():
         if ad:   # step 0 is a full vote from the empty state, every later step changes at most K/10 votes
             B.mv_ad_vote_step(ctx, g_dev[i % len(g_dev)], e_dev, K if i == 0 else k_ad, vote_bits, msum,
                               add_idx, drop_idx, counts, mask, agg, stream=stream, ld_g=ld_g, ld_e=ld_e)
+        elif rs:
+            B.mv_rs_vote_step(ctx, g_dev[i % len(g_dev)], e_dev, r_dev[i % len(r_dev)], widx, votes, mask, agg,
+                              stream=stream, ld_g=ld_g, ld_e=ld_e)
         else:
             B.mv_vote_step(ctx, g_dev[i % len(g_dev)], e_dev, widx, votes, mask, agg, stream=stream,
                            ld_g=ld_g, ld_e=ld_e)
@@ -273,6 +285,8 @@ def main():
         if ad:
             ref = mv_oracle.ad_vote_step(g_host0, e0, K, K, np.zeros((N, d), np.uint8), np.zeros(d, np.uint8),
                                          threads=threads)
+        elif rs:
+            ref = mv_oracle.rs_vote_step(g_host0, e0, K, r_host0, threads=threads)
         else:
             ref = mv_oracle.vote_step(g_host0, e0, K, threads=threads)
         t_or = time.perf_counter() - t1
@@ -281,13 +295,15 @@ def main():
         cpu_baseline = {"value": round(coords / t_or, 1), "unit": "coords/s", "cores": threads,
                         "kind": "oracle", "seconds": round(t_or, 2),
                         "sample": "one full %s of %s (all %d rows, d=%d), step-0 inputs" %
-                                  ("add-drop step (first, full vote)" if ad else "vote step", w.name, N, d)}
+                                  ("add-drop step (first, full vote)" if ad else
+                                   "vote step with random selection" if rs else "vote step", w.name, N, d)}
 
     B.mv_end(ctx)
     B.mv_release(ctx)
 
     out = {
-        "metric": "vote-step throughput (N*d coords/sec), 1 GPU" + (", add-drop voting" if ad else ""),
+        "metric": "vote-step throughput (N*d coords/sec), 1 GPU" +
+                  (", add-drop voting" if ad else ", random selection" if rs else ""),
         "value": round(value, 1),
         "unit": "coords/s",
         "n_gpus": 1,
@@ -302,7 +318,8 @@ def main():
         "config": {"workload": "%s: N=%d d=%d K=%d grads=%s, %s, error feedback carried" %
                                (w.name, N, d, K, w.grad_dtype, w.kind),
                    "N": N, "d": d, "K": K, "grad_sets_cycled": len(g_dev),
-                   "scheme": "majority voting with add-drop, K_ad=%d" % k_ad if ad else "majority voting",
+                   "scheme": "majority voting with add-drop, K_ad=%d" % k_ad if ad else
+                             "majority voting with random selection" if rs else "majority voting",
                    "outputs": "mask_idx, agg_vals, add/drop lists, standing votes, vote sum" if ad else
                               "mask_idx, agg_vals, votes" + ("" if args.no_worker_idx else ", worker_idx")},
         "step_hbm_frac_algorithmic": round(step_frac, 4),

@@ -109,6 +109,35 @@ mv_status mv_vote_step(mv_ctx* ctx,
                        void* stream);
 
 /*
+ * One iteration of majority voting with random selection (paper: Algorithm 1, the
+ * line with S_rand-weighted; Sec. 2, paragraph after Algorithm 1; Sec. 4.2),
+ * enqueued on `stream` like mv_vote_step and with the same arguments, outputs and
+ * error behaviour, except for how the mask is chosen: the winning coordinates are
+ * drawn with probabilities proportional to their votes until K distinct ones are
+ * selected.  The paper names no sampler; here every voted coordinate j gets the
+ * time rand_exp[j] / votes[j] (one correctly rounded fp32 division) and the K
+ * soonest win, equal times going to the lowest coordinate.  With rand_exp[j]
+ * independent Exp(1) variates this is that law (successive sampling without
+ * replacement); the random numbers are the caller's, so a step is reproducible.
+ *
+ *   rand_exp   device, d fp32, non-negative and finite, 4-byte aligned; in.  Only the
+ *              entries of voted coordinates are read.  Use fresh numbers every step.
+ *   mask_idx   device, K uint32, ascending; out.  Every coordinate in it has a vote.
+ *
+ * worker_idx and votes (both optional) are those of mv_vote_step.  MV_ERR_INVALID_ARG
+ * also for a null or misaligned rand_exp.
+ */
+mv_status mv_rs_vote_step(mv_ctx* ctx,
+                          const void* grads, int64_t ld_g,
+                          float* err, int64_t ld_e,
+                          const float* rand_exp,
+                          uint32_t* worker_idx,
+                          uint8_t* votes,
+                          uint32_t* mask_idx,
+                          float* agg_vals,
+                          void* stream);
+
+/*
  * One iteration of majority voting with add-drop (paper: Algorithm 2, Sec. 3),
  * enqueued on `stream` like mv_vote_step.  The context must have been begun with
  * MV_FLAG_ADD_DROP (else MV_ERR_STATE).  Every worker keeps a standing vote

@@ -20,7 +20,7 @@ MV_FLAG_ADD_DROP = 1
 
 # every symbol include/mv.h declares
 ABI_SYMBOLS = (
-    "mv_workspace_bytes", "mv_begin", "mv_vote_step", "mv_ad_vote_step", "mv_end", "mv_release", "mv_status_string",
+    "mv_workspace_bytes", "mv_begin", "mv_vote_step", "mv_ad_vote_step", "mv_rs_vote_step", "mv_end", "mv_release", "mv_status_string",
     "mv_kernel_count", "mv_kernel_name", "mv_set_profiling", "mv_step_kernel_ms",
     "mv_last_step_row_stats", "mv_probe_copy",
     "mv_codec_stream_bits", "mv_codec_scratch_bytes", "mv_codec_encode", "mv_codec_decode",
@@ -71,6 +71,8 @@ def load() -> ctypes.CDLL:
     L.mv_vote_step.restype = i32
     L.mv_ad_vote_step.argtypes = [vp, vp, i64, vp, i64, i64, vp, i64, vp, vp, vp, vp, vp, vp, vp]
     L.mv_ad_vote_step.restype = i32
+    L.mv_rs_vote_step.argtypes = [vp, vp, i64, vp, i64, vp, vp, vp, vp, vp, vp]
+    L.mv_rs_vote_step.restype = i32
     L.mv_end.argtypes = [vp]
     L.mv_end.restype = i32
     L.mv_release.argtypes = [vp]
@@ -151,6 +153,23 @@ def mv_vote_step(ctx: int, grads, err, worker_idx, votes, mask_idx, agg_vals, st
         stream.cuda_stream)
     if st != MV_OK:
         raise MvError(st, "mv_vote_step")
+
+
+def mv_rs_vote_step(ctx: int, grads, err, rand_exp, worker_idx, votes, mask_idx, agg_vals, stream=None,
+                    ld_g: Optional[int] = None, ld_e: Optional[int] = None) -> None:
+    """Enqueues one step of majority voting with random selection: as mv_vote_step,
+    the mask drawn in proportion to the votes with the caller's Exp(1) numbers
+    `rand_exp` (d float32 on the device)."""
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream(err.device)
+    st = load().mv_rs_vote_step(
+        ctx, _dev_ptr(grads), grads.stride(0) if ld_g is None else ld_g,
+        _dev_ptr(err), err.stride(0) if ld_e is None else ld_e, _dev_ptr(rand_exp),
+        _dev_ptr(worker_idx), _dev_ptr(votes), _dev_ptr(mask_idx), _dev_ptr(agg_vals),
+        stream.cuda_stream)
+    if st != MV_OK:
+        raise MvError(st, "mv_rs_vote_step")
 
 
 def mv_ad_vote_step(ctx: int, grads, err, k_ad: int, vote_bits, msum, add_idx, drop_idx, counts, mask_idx,

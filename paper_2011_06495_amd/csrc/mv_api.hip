@@ -29,12 +29,18 @@ enum KernelId {
     KID_AD_COMPACT_COUNT,
     KID_AD_COMPACT_EMIT,
     KID_AD_LEVELS,
+    // random selection only
+    KID_RS_KEYS,
+    KID_RS_HIST,
+    KID_RS_SPLIT,
+    KID_RS_RANK,
     KID_COUNT
 };
 const char* const kKernelNames[KID_COUNT] = {
     "mv_sample_hist",    "mv_pick_threshold",  "mv_stream_collect",   "mv_row_select",      "mv_row_votes",
     "mv_mask_count",     "mv_mask_emit",       "mv_gather_update",    "mv_ad_collect_add",  "mv_ad_collect_drop",
-    "mv_ad_select",      "mv_ad_apply",        "mv_ad_compact_count", "mv_ad_compact_emit", "mv_ad_levels"};
+    "mv_ad_select",      "mv_ad_apply",        "mv_ad_compact_count", "mv_ad_compact_emit", "mv_ad_levels",
+    "mv_rs_keys",        "mv_rs_hist",         "mv_rs_split",         "mv_rs_rank"};
 
 constexpr size_t kAlign = 256;
 constexpr int kEventRing = 64;   // steps whose kernel durations stay readable
@@ -58,6 +64,9 @@ struct Plan {
     uint32_t nwords, nwords_pad;  // 32-bit words of a row's vote bitmap, and padded to a multiple of 4
     uint32_t cap_d;               // capacity of a row's list of removal candidates
     uint32_t bit_blocks;          // workgroups of 1024 bitmap words per row
+    // random selection
+    uint32_t rs_cap;              // most coordinates that can hold a vote: min(N K, d)
+    size_t   off_rshist, off_rscount, off_rsbits, off_rsblk, off_rslist, off_rslist2;
     // scratch offsets (bytes)
     size_t off_hist, off_tau, off_rowcnt, off_slow, off_kth, off_tiecut, off_cntge, off_seg, off_segsel,
         off_segpre,
@@ -148,6 +157,14 @@ Plan make_plan(const mv_config* c)
         p.off_adbits = off;  off += align_up((size_t)p.N * 2 * p.nwords_pad * 4);
         p.off_adblk = off;   off += align_up((size_t)p.N * 2 * p.bit_blocks * 4);
     }
+    const uint64_t voted_max = (uint64_t)p.N * p.K;
+    p.rs_cap = (uint32_t)(voted_max < (uint64_t)p.d ? voted_max : (uint64_t)p.d);
+    p.off_rshist = off;  off += align_up((size_t)mvk::kSelBins * 4);
+    p.off_rscount = off; off += align_up(4 * 4);
+    p.off_rsbits = off;  off += align_up((size_t)p.nwords_pad * 4);
+    p.off_rsblk = off;   off += align_up((size_t)p.bit_blocks * 4);
+    p.off_rslist = off;  off += align_up((size_t)p.rs_cap * 8);
+    p.off_rslist2 = off; off += align_up((size_t)p.rs_cap * 8);
     p.total_bytes = off;
     return p;
 }
@@ -237,6 +254,8 @@ mv_status mv_begin(const mv_config* cfg, mv_ctx** out_ctx)
               hipMemset(c->ws + plan.off_tau, 0, plan.off_seg - plan.off_tau) == hipSuccess;
     if (ok && plan.add_drop)   // the scratch bitmaps start at zero and are left at zero by every step
         ok = hipMemset(c->ws + plan.off_adcount, 0, plan.off_adblk - plan.off_adcount) == hipSuccess;
+    // random selection: histogram, counters and bitmap start at zero and are left at zero
+    ok = ok && hipMemset(c->ws + plan.off_rshist, 0, plan.off_rsblk - plan.off_rshist) == hipSuccess;
     ok = ok && hipDeviceSynchronize() == hipSuccess;
     if (!ok) {
         (void)hipGetLastError();
@@ -267,6 +286,8 @@ struct StepArgs {
     uint32_t* add_idx;
     uint32_t* drop_idx;
     uint32_t* counts;
+    // random selection (null: the mask is the K most voted coordinates)
+    const float* rand_exp;
 };
 
 mv_status check_common(mv_ctx* c, const StepArgs& a)
@@ -274,6 +295,7 @@ mv_status check_common(mv_ctx* c, const StepArgs& a)
     if (!c) return MV_ERR_INVALID_ARG;
     if (c->ended) return MV_ERR_STATE;
     if (!a.grads || !a.err || !a.mask_idx || !a.agg_vals) return MV_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(a.rand_exp) & 3) return MV_ERR_INVALID_ARG;
     const Plan& p = c->plan;
     const bool bf16 = c->cfg.grad_dtype == MV_BF16;
     if (a.ld_g < p.d || a.ld_e < p.d) return MV_ERR_INVALID_ARG;
@@ -294,6 +316,7 @@ mv_status enqueue_step(mv_ctx* c, const StepArgs& a, void* stream_v)
     const Plan& p = c->plan;
     const bool bf16 = c->cfg.grad_dtype == MV_BF16;
     const bool add_drop = a.k_ad > 0;
+    const bool random_sel = a.rand_exp != nullptr;
     DeviceGuard guard(c->cfg.device);
     if (!guard.ok) return MV_ERR_DEVICE;
     hipStream_t st = static_cast<hipStream_t>(stream_v);
@@ -423,7 +446,45 @@ mv_status enqueue_step(mv_ctx* c, const StepArgs& a, void* stream_v)
         after(KID_AD_LEVELS);
         mask_votes32 = msum32;
     }
+    if (random_sel) {
+        // 4''. random selection: keys of the voted coordinates, their histogram, split at the bin of the K-th
+        // soonest, exact ranking inside that bin, ordered compaction of the winners' bitmap
+        uint32_t* rshist = ws_ptr<uint32_t>(c, p.off_rshist);
+        uint32_t* rscount = ws_ptr<uint32_t>(c, p.off_rscount);
+        uint32_t* rsbits = ws_ptr<uint32_t>(c, p.off_rsbits);
+        uint32_t* rsblk = ws_ptr<uint32_t>(c, p.off_rsblk);
+        mvk::u32x2* rslist = ws_ptr<mvk::u32x2>(c, p.off_rslist);
+        mvk::u32x2* rslist2 = ws_ptr<mvk::u32x2>(c, p.off_rslist2);
+        before(KID_RS_KEYS);
+        hipLaunchKernelGGL(mvk::mv_rs_keys, dim3(p.n_vote_blocks), dim3(mvk::kVoteThreads), 0, st, votes32, p.d,
+                           a.rand_exp, rslist, p.rs_cap, rscount);
+        after(KID_RS_KEYS);
+        const uint32_t per_wg = mvk::kRowThreads * mvk::kRsPerThread;
+        before(KID_RS_HIST);
+        hipLaunchKernelGGL(mvk::mv_rs_hist, dim3((p.rs_cap + per_wg - 1) / per_wg), dim3(mvk::kRowThreads), 0, st,
+                           rslist, p.rs_cap, rscount, rshist);
+        after(KID_RS_HIST);
+        before(KID_RS_SPLIT);
+        hipLaunchKernelGGL(mvk::mv_rs_split, dim3((p.rs_cap + per_wg - 1) / per_wg), dim3(mvk::kRowThreads), 0, st,
+                           rslist, p.rs_cap, p.K, rscount, rshist, rslist2, rsbits);
+        after(KID_RS_SPLIT);
+        before(KID_RS_RANK);
+        hipLaunchKernelGGL(mvk::mv_rs_rank, dim3(1), dim3(mvk::kRowThreads), 0, st, rslist2, p.rs_cap, rscount,
+                           rshist, rsbits);
+        after(KID_RS_RANK);
+        before(KID_AD_COMPACT_COUNT);
+        hipLaunchKernelGGL(mvk::mv_ad_compact_count, dim3(p.bit_blocks, 1), dim3(mvk::kVoteThreads), 0, st, rsbits,
+                           p.nwords_pad, p.bit_blocks, rsblk);
+        after(KID_AD_COMPACT_COUNT);
+        before(KID_AD_COMPACT_EMIT);
+        hipLaunchKernelGGL(mvk::mv_ad_compact_emit, dim3(p.bit_blocks, 1), dim3(mvk::kVoteThreads), 0, st, rsbits,
+                           p.nwords_pad, p.bit_blocks, rsblk, p.K, a.mask_idx, (uint32_t*)nullptr,
+                           (uint32_t*)nullptr, (int64_t)0);
+        after(KID_AD_COMPACT_EMIT);
+    }
     // 5. global mask; in plain voting extra workgroups scan the tallies / write the sorted vote lists
+    // (with random selection the mask is already written: only the lists, the copy of the
+    // votes and the clearing of the vote words remain)
     const bool lists = sorted && !add_drop;
     before(KID_MASK_COUNT);
     hipLaunchKernelGGL(mvk::mv_mask_count, dim3(p.n_vote_blocks + (lists ? p.N * p.scan_blocks : 0)),
@@ -433,7 +494,8 @@ mv_status enqueue_step(mv_ctx* c, const StepArgs& a, void* stream_v)
     after(KID_MASK_COUNT);
     before(KID_MASK_EMIT);
     hipLaunchKernelGGL(mvk::mv_mask_emit, dim3(p.n_vote_blocks + (lists ? p.N * p.emit_blocks : 0)),
-                       dim3(mvk::kVoteThreads), 0, st, mask_votes32, p.d, p.K, votethr, blockcnt, a.mask_idx,
+                       dim3(mvk::kVoteThreads), 0, st, mask_votes32, p.d, p.K, votethr, blockcnt,
+                       random_sel ? (uint32_t*)nullptr : a.mask_idx,
                        p.n_vote_blocks, p.emit_blocks, cand, p.cap, rowcnt, seg, p.nseg, segpre, blktotal, p.scan_blocks,
                        kth, tiecut, slow, a.worker_idx, add_drop ? 0 : 1);
     after(KID_MASK_EMIT);
@@ -492,6 +554,21 @@ mv_status mv_ad_vote_step(mv_ctx* c, const void* grads, int64_t ld_g, float* err
     if ((reinterpret_cast<uintptr_t>(add_idx) & 3) || (reinterpret_cast<uintptr_t>(drop_idx) & 3) ||
         (reinterpret_cast<uintptr_t>(counts) & 3))
         return MV_ERR_INVALID_ARG;
+    return enqueue_step(c, a, stream_v);
+}
+
+mv_status mv_rs_vote_step(mv_ctx* c, const void* grads, int64_t ld_g, float* err, int64_t ld_e,
+                          const float* rand_exp, uint32_t* worker_idx, uint8_t* votes, uint32_t* mask_idx,
+                          float* agg_vals, void* stream_v)
+{
+    StepArgs a;
+    memset(&a, 0, sizeof a);
+    a.grads = grads; a.ld_g = ld_g; a.err = err; a.ld_e = ld_e;
+    a.worker_idx = worker_idx; a.votes = votes; a.mask_idx = mask_idx; a.agg_vals = agg_vals;
+    a.rand_exp = rand_exp;
+    if (!rand_exp) return MV_ERR_INVALID_ARG;
+    const mv_status st = check_common(c, a);
+    if (st != MV_OK) return st;
     return enqueue_step(c, a, stream_v);
 }
 

@@ -1218,7 +1218,7 @@ __global__ __launch_bounds__(kVoteThreads) void mv_mask_emit(uint32_t* __restric
                 const bool is_gt = inside && v > vstar, is_eq = inside && v == vstar;
                 if (is_gt || (is_eq && e0 < take_eq)) {
                     const uint32_t pos = g0 + min(e0, take_eq);
-                    if (pos < K) mask_idx[pos] = (uint32_t)(j + q);
+                    if (mask_idx && pos < K) mask_idx[pos] = (uint32_t)(j + q);
                 }
                 g0 += is_gt;
                 e0 += is_eq;
@@ -1528,14 +1528,16 @@ __global__ __launch_bounds__(kVoteThreads) void mv_ad_compact_emit(uint32_t* __r
     uint64_t total;
     uint32_t pos = (uint32_t)(before + block_excl_scan64<kVoteThreads>(n, scan_lds, total));
     uint32_t* out = (which ? drop_idx : add_idx) + (size_t)row * k_ad;
-    uint32_t* vrow = vote_bits + (int64_t)row * ld_bits;
+    uint32_t* vrow = vote_bits ? vote_bits + (int64_t)row * ld_bits : nullptr;   // null: compaction only
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
         uint32_t m = w[q];
         if (m) {
             // additions and removals never touch the same bit, but may share a word
-            if (which) atomicAnd(&vrow[w0 + q], ~m);
-            else       atomicOr(&vrow[w0 + q], m);
+            if (vote_bits) {
+                if (which) atomicAnd(&vrow[w0 + q], ~m);
+                else       atomicOr(&vrow[w0 + q], m);
+            }
         }
         while (m) {
             const uint32_t b = __ffs((int)m) - 1;
@@ -1575,6 +1577,218 @@ __global__ __launch_bounds__(kVoteThreads) void mv_ad_levels(const uint32_t* __r
     __syncthreads();
     const uint32_t c = h[threadIdx.x];
     if (c) atomicAdd(&lvl_cnt[threadIdx.x], c);
+}
+
+// ----------------------------------------------------------------------------
+// 8. majority voting with random selection (Algorithm 1, the S_rand-weighted line;
+//    Sec. 2, paragraph after Algorithm 1; Sec. 4.2)
+// ----------------------------------------------------------------------------
+// Winners are drawn in proportion to their votes until K distinct ones are
+// selected.  Stated without an order of draws: every voted coordinate j gets an
+// exponential clock of rate votes[j], i.e. the time rand_exp[j] / votes[j] with
+// rand_exp[j] ~ Exp(1) from the caller, and the K clocks that ring first win
+// (equal times: lowest coordinate first).  The time is one correctly rounded fp32
+// division; its bit pattern, complemented, is a key for the same exact select
+// that serves the rows: list of (key, coordinate), a histogram of the key's 11
+// leading bits, the members of the bin that holds the K-th, their exact ranking.
+// Selected coordinates are marked in a bitmap that an ordered compaction turns
+// into the ascending mask.
+
+// Scan of the packed vote bytes (grid as for the mask kernels): every voted
+// coordinate is appended to the list with its key.  rs_count[0] = list length.
+constexpr int kRsStage = 4096;   // voted coordinates of one workgroup staged in LDS
+__device__ __forceinline__ u32x2 rs_entry(const float* __restrict__ rand_exp, uint32_t j, uint32_t v)
+{
+    const float time = __fdiv_rn(rand_exp[j], (float)v);
+    u32x2 c;
+    c.x = kAbsMask - (__float_as_uint(time) & kAbsMask);            // sooner = larger key
+    c.y = j;
+    return c;
+}
+__global__ __launch_bounds__(kVoteThreads) void mv_rs_keys(const uint32_t* __restrict__ votes32, int64_t d,
+                                                           const float* __restrict__ rand_exp,
+                                                           u32x2* __restrict__ list, uint32_t list_cap,
+                                                           uint32_t* __restrict__ rs_count)
+{
+    __shared__ uint32_t stage[kRsStage];
+    __shared__ uint64_t scan_lds[kVoteThreads / kWave + 1];
+    __shared__ uint32_t base_sh;
+    constexpr int kIt = kVoteBlock / (kVoteThreads * 16);
+    const int64_t base = (int64_t)blockIdx.x * kVoteBlock;
+    u32x4 w[kIt];
+    uint32_t n = 0;
+#pragma unroll
+    for (int it = 0; it < kIt; ++it) {
+        const int64_t j = base + ((int64_t)it * kVoteThreads + threadIdx.x) * 16;
+        const u32x4 z = {0u, 0u, 0u, 0u};
+        w[it] = (j < d) ? *reinterpret_cast<const u32x4*>(votes32 + (j >> 2)) : z;   // bytes past d are zero
+    }
+#pragma unroll
+    for (int it = 0; it < kIt; ++it) {
+        const uint32_t ww[4] = {w[it].x, w[it].y, w[it].z, w[it].w};
+#pragma unroll
+        for (int q = 0; q < 16; ++q) n += ((ww[q >> 2] >> (8 * (q & 3))) & 255u) != 0u;
+    }
+    uint64_t total;
+    const uint64_t ex = block_excl_scan64<kVoteThreads>(n, scan_lds, total);
+    if (total == 0) return;                                        // whole workgroup
+    if (threadIdx.x == 0) base_sh = atomicAdd(&rs_count[0], (uint32_t)total);
+    const bool staged = total <= (uint64_t)kRsStage;               // uniform
+    uint32_t pos = (uint32_t)ex;                                   // position among the workgroup's entries
+    if (n) {
+#pragma unroll
+        for (int it = 0; it < kIt; ++it) {
+            if ((w[it].x | w[it].y | w[it].z | w[it].w) == 0u) continue;
+            const uint32_t off0 = ((uint32_t)it * kVoteThreads + threadIdx.x) * 16;   // offset in the block
+            const uint32_t ww[4] = {w[it].x, w[it].y, w[it].z, w[it].w};
+            for (int q = 0; q < 16; ++q) {
+                const uint32_t v = (ww[q >> 2] >> (8 * (q & 3))) & 255u;
+                if (v) {
+                    // usual case: park (offset, votes); the random numbers are then fetched
+                    // by all lanes together instead of one dependent load per entry here
+                    if (staged) stage[pos] = ((off0 + (uint32_t)q) << 8) | v;
+                    ++pos;
+                }
+            }
+        }
+    }
+    __syncthreads();
+    const uint32_t first = base_sh;
+    if (staged) {
+        for (uint32_t i = threadIdx.x; i < (uint32_t)total; i += kVoteThreads) {
+            const uint32_t s = stage[i];
+            if (first + i < list_cap) list[first + i] = rs_entry(rand_exp, (uint32_t)base + (s >> 8), s & 255u);
+        }
+        return;
+    }
+    // a block dense with votes: entry by entry
+    pos = first + (uint32_t)ex;
+    if (n) {
+#pragma unroll
+        for (int it = 0; it < kIt; ++it) {
+            if ((w[it].x | w[it].y | w[it].z | w[it].w) == 0u) continue;
+            const int64_t j0 = base + ((int64_t)it * kVoteThreads + threadIdx.x) * 16;
+            const uint32_t ww[4] = {w[it].x, w[it].y, w[it].z, w[it].w};
+            for (int q = 0; q < 16; ++q) {
+                const uint32_t v = (ww[q >> 2] >> (8 * (q & 3))) & 255u;
+                if (v) {
+                    if (pos < list_cap) list[pos] = rs_entry(rand_exp, (uint32_t)(j0 + q), v);
+                    ++pos;
+                }
+            }
+        }
+    }
+}
+
+// Histogram of the 11 leading key bits over the list (few, large workgroups: the
+// merge into the global histogram costs one atomic per occupied bin and workgroup).
+constexpr int kRsPerThread = 4;
+__global__ __launch_bounds__(kRowThreads) void mv_rs_hist(const u32x2* __restrict__ list, uint32_t list_cap,
+                                                          const uint32_t* __restrict__ rs_count,
+                                                          uint32_t* __restrict__ rs_hist)
+{
+    __shared__ uint32_t hist[kSelBins];
+    const uint32_t t = threadIdx.x;
+    const uint32_t n = min(rs_count[0], list_cap);
+    const uint32_t i0 = blockIdx.x * (uint32_t)(kRowThreads * kRsPerThread);
+    if (i0 >= n) return;                                             // whole workgroup
+    uint32_t k[kRsPerThread];
+#pragma unroll
+    for (int u = 0; u < kRsPerThread; ++u) {
+        const uint32_t i = i0 + (uint32_t)u * kRowThreads + t;
+        k[u] = (i < n) ? list[i].x : 0xFFFFFFFFu;                   // keys are at most 0x7FFFFFFF
+    }
+    for (int b = t; b < kSelBins; b += kRowThreads) hist[b] = 0;
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < kRsPerThread; ++u)
+        if (k[u] != 0xFFFFFFFFu) atomicAdd(&hist[k[u] >> 20], 1u);
+    __syncthreads();
+    for (int b = t; b < kSelBins; b += kRowThreads) {
+        const uint32_t c = hist[b];
+        if (c) atomicAdd(&rs_hist[b], c);
+    }
+}
+
+// Every workgroup finds, from the histogram, the bin that holds the K-th soonest
+// clock; list entries in sooner bins are winners (their bit is set), the members
+// of that bin go to list2 for the exact ranking.  rs_count[1] = length of list2,
+// rs_count[2] = the bin, rs_count[3] = how many of its members win.
+__global__ __launch_bounds__(kRowThreads) void mv_rs_split(const u32x2* __restrict__ list, uint32_t list_cap,
+                                                           uint32_t K, uint32_t* __restrict__ rs_count,
+                                                           const uint32_t* __restrict__ rs_hist,
+                                                           u32x2* __restrict__ list2,
+                                                           uint32_t* __restrict__ rs_bits)
+{
+    __shared__ uint32_t hist[kSelBins];
+    __shared__ uint64_t scan_lds[kRowThreads / kWave + 1];
+    __shared__ uint32_t bcast[3];
+    __shared__ uint32_t base_sh;
+    const uint32_t t = threadIdx.x;
+    const uint32_t n = min(rs_count[0], list_cap);
+    const uint32_t i0 = blockIdx.x * (uint32_t)(kRowThreads * kRsPerThread);
+    if (i0 >= n && blockIdx.x != 0) return;                         // whole workgroup
+    u32x2 c[kRsPerThread];
+#pragma unroll
+    for (int u = 0; u < kRsPerThread; ++u) {
+        const uint32_t i = i0 + (uint32_t)u * kRowThreads + t;
+        const u32x2 none = {0u, 0xFFFFFFFFu};
+        c[u] = (i < n) ? list[i] : none;
+    }
+    for (int b = t; b < kSelBins; b += kRowThreads) hist[b] = rs_hist[b];
+    __syncthreads();
+    uint32_t bin, want, in_bin;
+    find_rank_bin<kSelBins>(hist, scan_lds, bcast, K, bin, want, in_bin);   // n >= K: every worker voted K coordinates
+    if (blockIdx.x == 0 && t == 0) {
+        rs_count[2] = bin;
+        rs_count[3] = want;
+    }
+    uint32_t mine = 0;
+#pragma unroll
+    for (int u = 0; u < kRsPerThread; ++u) {
+        const bool valid = c[u].y != 0xFFFFFFFFu;
+        const uint32_t b = c[u].x >> 20;
+        if (valid && b > bin) atomicOr(&rs_bits[c[u].y >> 5], 1u << (c[u].y & 31u));
+        mine += (valid && b == bin);
+    }
+    uint64_t total;
+    const uint64_t ex = block_excl_scan64<kRowThreads>(mine, scan_lds, total);
+    if (total == 0) return;                                          // whole workgroup
+    if (t == 0) base_sh = atomicAdd(&rs_count[1], (uint32_t)total);
+    __syncthreads();
+    uint32_t pos = base_sh + (uint32_t)ex;
+#pragma unroll
+    for (int u = 0; u < kRsPerThread; ++u) {
+        const bool valid = c[u].y != 0xFFFFFFFFu;
+        if (valid && (c[u].x >> 20) == bin) {
+            if (pos < list_cap) list2[pos] = c[u];
+            ++pos;
+        }
+    }
+}
+
+// One workgroup: exact ranking of the bin's members, marks the winners among
+// them, and leaves the histogram and the counters at zero for the next step.
+__global__ __launch_bounds__(kRowThreads) void mv_rs_rank(const u32x2* __restrict__ list2, uint32_t list_cap,
+                                                          uint32_t* __restrict__ rs_count,
+                                                          uint32_t* __restrict__ rs_hist,
+                                                          uint32_t* __restrict__ rs_bits)
+{
+    __shared__ SelectLds lds;
+    const uint32_t t = threadIdx.x;
+    const uint32_t C = min(rs_count[1], list_cap), bin = rs_count[2], want = rs_count[3];
+    __syncthreads();                                                  // everyone has read the counters
+    for (int b = t; b < kSelBins; b += kRowThreads) rs_hist[b] = 0;
+    if (t < 4) rs_count[t] = 0;
+    if (C == 0 || want == 0 || want > C) return;                      // cannot happen after mv_rs_split
+    uint32_t kth, tie_cut, path;
+    auto at = [list2](uint64_t i) { return list2[i].x; };
+    const KeysInMemory<decltype(at)> src{at, C};
+    select_among_candidates(src, list2, C, want, bin << 20, lds, kth, tie_cut, path);
+    for (uint32_t i = t; i < C; i += kRowThreads) {
+        const u32x2 c = list2[i];
+        if (is_taken(c, kth, tie_cut)) atomicOr(&rs_bits[c.y >> 5], 1u << (c.y & 31u));
+    }
 }
 
 // ----------------------------------------------------------------------------

@@ -127,7 +127,7 @@ LATTICE_LEVELS = 256
 
 
 def _rng(w: Workload, step: int, stream: int) -> np.random.Generator:
-    # stream: -2 = scales, -1 = common component, n >= 0 = worker n
+    # stream: -2 = scales, -1 = common component, n >= 0 = worker n, 1000000 = selection clocks
     return np.random.Generator(np.random.PCG64([w.seed, 1000 * w.index + step, stream + 2]))
 
 
@@ -195,6 +195,12 @@ def gradients(w: Workload, step: int, threads: int = 1) -> np.ndarray:
         for n in range(w.N):
             one(n)
     return out
+
+
+def selection_clocks(w: Workload, step: int) -> np.ndarray:
+    """The d Exp(1) numbers (fp32) that majority voting with random selection consumes
+    in one step: plain random draws from a stream of their own."""
+    return _rng(w, step, 1_000_000).standard_exponential(w.d, dtype=np.float32)
 
 
 def zero_error(w: Workload) -> np.ndarray:

@@ -71,6 +71,14 @@ class GpuStepper:
         B.mv_vote_step(self.ctx, self.g, self.e, self.widx, self.votes, self.mask, self.agg,
                        stream=stream, ld_g=self.ld_g, ld_e=self.ld_e)
 
+    def step_rs(self, rand_exp_host: np.ndarray, stream=None) -> None:
+        """One step of majority voting with random selection with the given Exp(1) numbers."""
+        r = torch.from_numpy(np.ascontiguousarray(rand_exp_host, np.float32)).to(self.dev)
+        assert r.numel() == self.d
+        B.mv_rs_vote_step(self.ctx, self.g, self.e, r, self.widx, self.votes, self.mask, self.agg,
+                          stream=stream, ld_g=self.ld_g, ld_e=self.ld_e)
+        torch.cuda.synchronize()          # r must outlive the step
+
     def fetch(self, check_guards: bool = True) -> GpuOut:
         torch.cuda.synchronize()
         N, d, K = self.N, self.d, self.K

@@ -114,3 +114,43 @@ def test_add_drop_paper_regime_full(oracle):
     # the paper's setting: ResNet-18 size, N = 10 workers, phi = 1e-2, phi_ad = 1e-3 (Sec. 4.1, 4.2)
     w = W.C2.with_size(W.C2.d, K=111740)
     run_full_ad(oracle, w, [w.K, 11174, 11174])
+
+
+# ---- majority voting with random selection (Algorithm 1, S_rand-weighted) at full size
+
+def run_full_rs(oracle, w, steps):
+    threads = min(16, oracle.max_threads())
+    e_ref = W.zero_error(w)
+    with GpuStepper(w.N, w.d, w.K, bf16=(w.grad_dtype == "bf16")) as gs:
+        gs.set_error(e_ref)
+        for t in range(steps):
+            t0 = time.time()
+            g = W.gradients(w, t, threads=threads)
+            r = W.selection_clocks(w, t)
+            gs.set_grads(g)
+            gs.step_rs(r)
+            got = gs.fetch()
+            ref = oracle.rs_vote_step(g, e_ref, w.K, r, threads=threads)
+            assert_matches_oracle(got, ref, "%s random selection full size, step %d" % (w.name, t))
+            # what holds at any size: winners have votes, and more votes win more often
+            v = ref.votes
+            assert np.all(v[got.mask_idx] >= 1)
+            inside = np.zeros(w.d, bool)
+            inside[got.mask_idx] = True
+            rate = [inside[v == lvl].mean() for lvl in (1, 2, 3) if np.count_nonzero(v == lvl) > 2000]
+            assert all(a < b for a, b in zip(rate, rate[1:])), "selection rate does not grow with the votes: %s" % rate
+            e_ref = ref.err
+            say("%s random selection step %d ok (%.1f s), voted coordinates %d, rate by votes %s" %
+                (w.name, t, time.time() - t0, int(np.count_nonzero(v)), ["%.3f" % x for x in rate]))
+
+
+@pytest.mark.timeout(1200)
+def test_random_selection_c4_full(oracle):
+    run_full_rs(oracle, W.C4, 3)
+
+
+@pytest.mark.timeout(1200)
+def test_random_selection_paper_regime_full(oracle):
+    # ResNet-18 size, N = 10 workers, phi = 1e-2 (Sec. 4.1, 4.2)
+    w = W.C2.with_size(W.C2.d, K=111740)
+    run_full_rs(oracle, w, 2)

@@ -9,33 +9,10 @@ the sequential draws and the exponential clocks -- are checked against it, and
 against each other on a larger case.  Hand-worked draws, special cases (equal votes,
 K = number of voted positions, unvoted positions) and the composition of the whole
 step complete the pins."""
-import itertools
-
 import numpy as np
 import pytest
 
-
-def successive_sampling_law(w, K):
-    """P(selected set) when positions are drawn in proportion to w, repeats discarded."""
-    W = float(sum(w))
-    law = {}
-    voted = [j for j, x in enumerate(w) if x > 0]
-    for order in itertools.permutations(voted, K):
-        p, rest = 1.0, W
-        for j in order:
-            p *= w[j] / rest
-            rest -= w[j]
-        key = tuple(sorted(order))
-        law[key] = law.get(key, 0.0) + p
-    return law
-
-
-def assert_follows_law(counts, trials, law, what):
-    assert set(counts) <= set(law), "%s selected a set of probability zero" % what
-    for key, p in law.items():
-        f = counts.get(key, 0) / trials
-        sigma = np.sqrt(p * (1 - p) / trials)
-        assert abs(f - p) <= 5 * sigma + 1e-9, "%s: set %s frequency %.4f, law %.4f" % (what, key, f, p)
+from tests.rs_law import assert_follows_law, successive_sampling_law
 
 
 def test_hand_worked_draws(oracle):
