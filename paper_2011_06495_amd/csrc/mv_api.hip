@@ -362,17 +362,17 @@ mv_status enqueue_step(mv_ctx* c, const StepArgs& a, void* stream_v)
     // 1. sample histogram, then the threshold estimate per row and the counters' reset
     {
         const uint64_t nquads = (uint64_t)p.n_sampled_chunks * (mvk::kChunk / 4);
-        uint32_t bx = (uint32_t)((nquads + 511) / 512);
+        uint32_t bx = (uint32_t)((nquads + 2 * mvk::kSampleThreads - 1) / (2 * mvk::kSampleThreads));
         if (bx > 16) bx = 16;
         if (bx < 1) bx = 1;
         dim3 grid(bx, p.N);
         before(KID_SAMPLE);
         if (bf16)
-            hipLaunchKernelGGL(mvk::mv_sample_hist<uint16_t>, grid, dim3(256), 0, st,
+            hipLaunchKernelGGL(mvk::mv_sample_hist<uint16_t>, grid, dim3(mvk::kSampleThreads), 0, st,
                                static_cast<const uint16_t*>(a.grads), a.ld_g, a.err, a.ld_e, p.d, p.stride,
                                p.n_sampled_chunks, hist);
         else
-            hipLaunchKernelGGL(mvk::mv_sample_hist<float>, grid, dim3(256), 0, st,
+            hipLaunchKernelGGL(mvk::mv_sample_hist<float>, grid, dim3(mvk::kSampleThreads), 0, st,
                                static_cast<const float*>(a.grads), a.ld_g, a.err, a.ld_e, p.d, p.stride,
                                p.n_sampled_chunks, hist);
         after(KID_SAMPLE);

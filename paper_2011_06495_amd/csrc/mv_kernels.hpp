@@ -141,41 +141,59 @@ __device__ __forceinline__ float load1_grad(const uint16_t* p) { return __uint_a
 // Chunk c of a row is the coordinates [32c, 32c+32); chunk c is sampled when
 // c % stride == 0.  bin = (bits(|g+e|)) >> kHistShift.  Workgroups of a row add
 // their LDS histograms into the row's global one.
+constexpr int kSampleThreads = 1024;
 template <typename GT>
-__global__ __launch_bounds__(256) void mv_sample_hist(const GT* __restrict__ g, int64_t ld_g,
-                                                      const float* __restrict__ e, int64_t ld_e,
-                                                      int64_t d, uint32_t stride,
-                                                      uint32_t n_sampled_chunks,
-                                                      uint32_t* __restrict__ hist)
+__global__ __launch_bounds__(kSampleThreads) void mv_sample_hist(const GT* __restrict__ g, int64_t ld_g,
+                                                                 const float* __restrict__ e, int64_t ld_e,
+                                                                 int64_t d, uint32_t stride,
+                                                                 uint32_t n_sampled_chunks,
+                                                                 uint32_t* __restrict__ hist)
 {
     __shared__ uint32_t h[kHistBins];
     const uint32_t row = blockIdx.y, t = threadIdx.x;
-    for (int b = t; b < kHistBins; b += 256) h[b] = 0;
+    for (int b = t; b < kHistBins; b += kSampleThreads) h[b] = 0;
     __syncthreads();
 
     const GT*    grow = g + (int64_t)row * ld_g;
     const float* erow = e + (int64_t)row * ld_e;
     const uint64_t nquads = (uint64_t)n_sampled_chunks * (kChunk / 4);
-    for (uint64_t q = (uint64_t)blockIdx.x * 256 + t; q < nquads; q += (uint64_t)gridDim.x * 256) {
-        const int64_t j = (int64_t)(q / (kChunk / 4)) * stride * kChunk + (int64_t)(q % (kChunk / 4)) * 4;
-        if (j + 4 <= d) {
-            f32x4 gv = load4_grad(grow + j);
-            f32x4 ev = *reinterpret_cast<const f32x4*>(erow + j);
-            f32x4 a = gv + ev;
-            atomicAdd(&h[(__float_as_uint(a.x) & kAbsMask) >> kHistShift], 1u);
-            atomicAdd(&h[(__float_as_uint(a.y) & kAbsMask) >> kHistShift], 1u);
-            atomicAdd(&h[(__float_as_uint(a.z) & kAbsMask) >> kHistShift], 1u);
-            atomicAdd(&h[(__float_as_uint(a.w) & kAbsMask) >> kHistShift], 1u);
-        } else {
-            for (int64_t jj = j; jj < d; ++jj) {
-                float a = load1_grad(grow + jj) + erow[jj];
-                atomicAdd(&h[(__float_as_uint(a) & kAbsMask) >> kHistShift], 1u);
+    const uint64_t step = (uint64_t)gridDim.x * kSampleThreads;
+    auto start_of = [stride](uint64_t q) {
+        return (int64_t)(q / (kChunk / 4)) * stride * kChunk + (int64_t)(q % (kChunk / 4)) * 4;
+    };
+    auto tally = [&](float a) { atomicAdd(&h[(__float_as_uint(a) & kAbsMask) >> kHistShift], 1u); };
+    // The samples lie far apart in memory and every load pays the full latency: two
+    // quads' loads are in flight per thread and the grid is sized for one or two rounds.
+    for (uint64_t q0 = (uint64_t)blockIdx.x * kSampleThreads + t; q0 < nquads; q0 += 2 * step) {
+        f32x4 gv[2], ev[2];
+        bool  full[2];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const uint64_t q = q0 + (uint64_t)u * step;
+            const int64_t j = start_of(q);
+            full[u] = q < nquads && j + 4 <= d;
+            if (full[u]) {
+                gv[u] = load4_grad(grow + j);
+                ev[u] = *reinterpret_cast<const f32x4*>(erow + j);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const uint64_t q = q0 + (uint64_t)u * step;
+            if (full[u]) {
+                const f32x4 a = gv[u] + ev[u];
+                tally(a.x);
+                tally(a.y);
+                tally(a.z);
+                tally(a.w);
+            } else if (q < nquads) {
+                for (int64_t jj = start_of(q); jj < d; ++jj) tally(load1_grad(grow + jj) + erow[jj]);
             }
         }
     }
     __syncthreads();
     uint32_t* hrow = hist + (size_t)row * kHistBins;
-    for (int b = t; b < kHistBins; b += 256) {
+    for (int b = t; b < kHistBins; b += kSampleThreads) {
         uint32_t c = h[b];
         if (c) atomicAdd(&hrow[b], c);
     }
