@@ -60,6 +60,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="C4", choices=["C1", "C2", "C3", "C4", "C5"])
     ap.add_argument("--grad-sets", type=int, default=2, help="distinct gradient matrices cycled over")
+    ap.add_argument("--k", type=int, default=0,
+                    help="override the workload's K (e.g. 111740 = the paper's phi = 1e-2 on ResNet-18's size); "
+                         "the headline figure is the workload's own K")
     ap.add_argument("--scheme", default="mv", choices=["mv", "ad", "rs"],
                     help="mv: majority voting (Algorithm 1); ad: majority voting with add-drop (Algorithm 2), "
                          "a full first vote untimed, then K_ad = K/10 per step; rs: majority voting with "
@@ -92,6 +95,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
     w = W.WORKLOADS[args.workload]
+    if args.k > 0:
+        w = w.with_size(w.d, K=args.k)
     bf16 = w.grad_dtype == "bf16"
     N, d, K = w.N, w.d, w.K
     ld_g = (d + (7 if bf16 else 3)) // (8 if bf16 else 4) * (8 if bf16 else 4)

@@ -29,6 +29,10 @@ enum KernelId {
     KID_AD_COMPACT_COUNT,
     KID_AD_COMPACT_EMIT,
     KID_AD_LEVELS,
+    // rows' select with many workgroups (large K only)
+    KID_SEL_HIST,
+    KID_SEL_SPLIT,
+    KID_SEL_RANK,
     // random selection only
     KID_RS_KEYS,
     KID_RS_HIST,
@@ -40,6 +44,7 @@ const char* const kKernelNames[KID_COUNT] = {
     "mv_sample_hist",    "mv_pick_threshold",  "mv_stream_collect",   "mv_row_select",      "mv_row_votes",
     "mv_mask_count",     "mv_mask_emit",       "mv_gather_update",    "mv_ad_collect_add",  "mv_ad_collect_drop",
     "mv_ad_select",      "mv_ad_apply",        "mv_ad_compact_count", "mv_ad_compact_emit", "mv_ad_levels",
+    "mv_sel_hist",       "mv_sel_split",       "mv_sel_rank",
     "mv_rs_keys",        "mv_rs_hist",         "mv_rs_split",         "mv_rs_rank"};
 
 constexpr size_t kAlign = 256;
@@ -64,6 +69,9 @@ struct Plan {
     uint32_t nwords, nwords_pad;  // 32-bit words of a row's vote bitmap, and padded to a multiple of 4
     uint32_t cap_d;               // capacity of a row's list of removal candidates
     uint32_t bit_blocks;          // workgroups of 1024 bitmap words per row
+    // rows' select with many workgroups: when about 2K candidates are far more than one workgroup keeps in registers
+    bool     multi_select;
+    size_t   off_selhist, off_selcount2, off_selbinwant, off_sellist2;
     // random selection
     uint32_t rs_cap;              // most coordinates that can hold a vote: min(N K, d)
     size_t   off_rshist, off_rscount, off_rsbits, off_rsblk, off_rslist, off_rslist2;
@@ -156,6 +164,15 @@ Plan make_plan(const mv_config* c)
         p.off_adthr = off;   off += align_up((size_t)p.N * 4 * 4);
         p.off_adbits = off;  off += align_up((size_t)p.N * 2 * p.nwords_pad * 4);
         p.off_adblk = off;   off += align_up((size_t)p.N * 2 * p.bit_blocks * 4);
+    }
+    // (measured: one workgroup per row takes 20 us at 24K candidates, 38 us at 55K, 89 us at 230K; the three
+    // kernels of the many-workgroup select about 40 us)
+    p.multi_select = 2ull * p.K > 2ull * mvk::kKeep * mvk::kRowThreads;
+    if (p.multi_select) {
+        p.off_selhist = off;    off += align_up((size_t)p.N * mvk::kSelBins * 4);
+        p.off_selcount2 = off;  off += align_up((size_t)p.N * 4);
+        p.off_selbinwant = off; off += align_up((size_t)p.N * 2 * 4);
+        p.off_sellist2 = off;   off += align_up((size_t)p.N * p.cap * 8);
     }
     const uint64_t voted_max = (uint64_t)p.N * p.K;
     p.rs_cap = (uint32_t)(voted_max < (uint64_t)p.d ? voted_max : (uint64_t)p.d);
@@ -254,6 +271,8 @@ mv_status mv_begin(const mv_config* cfg, mv_ctx** out_ctx)
               hipMemset(c->ws + plan.off_tau, 0, plan.off_seg - plan.off_tau) == hipSuccess;
     if (ok && plan.add_drop)   // the scratch bitmaps start at zero and are left at zero by every step
         ok = hipMemset(c->ws + plan.off_adcount, 0, plan.off_adblk - plan.off_adcount) == hipSuccess;
+    if (ok && plan.multi_select)   // histograms and counters of the many-workgroup select start at zero
+        ok = hipMemset(c->ws + plan.off_selhist, 0, plan.off_selbinwant - plan.off_selhist) == hipSuccess;
     // random selection: histogram, counters and bitmap start at zero and are left at zero
     ok = ok && hipMemset(c->ws + plan.off_rshist, 0, plan.off_rsblk - plan.off_rshist) == hipSuccess;
     ok = ok && hipDeviceSynchronize() == hipSuccess;
@@ -398,8 +417,29 @@ mv_status enqueue_step(mv_ctx* c, const StepArgs& a, void* stream_v)
     // 3. exact per-row select
     before(KID_ROW_SELECT);
     hipLaunchKernelGGL(mvk::mv_row_select, dim3(p.N), dim3(mvk::kRowThreads), 0, st, a.err, a.ld_e, p.d, p.K, cand,
-                       p.cap, rowcnt, tau, kth, tiecut, a.worker_idx, votes32, cntge, slow, add_drop ? 1 : 0);
+                       p.cap, rowcnt, tau, kth, tiecut, a.worker_idx, votes32, cntge, slow, add_drop ? 1 : 0,
+                       p.multi_select ? 1 : 0);
     after(KID_ROW_SELECT);
+    if (p.multi_select) {
+        // long candidate lists: histogram, split at the bin of the K-th largest, exact rank
+        mvk::ListSelect ls;
+        ls.list = cand;  ls.cap = p.cap;  ls.count = rowcnt;  ls.base = tau;  ls.shift = mvk::kFineShift;
+        ls.want = p.K;
+        ls.hist = ws_ptr<uint32_t>(c, p.off_selhist);
+        ls.list2 = ws_ptr<mvk::u32x2>(c, p.off_sellist2);
+        ls.count2 = ws_ptr<uint32_t>(c, p.off_selcount2);
+        ls.bin_want = ws_ptr<uint32_t>(c, p.off_selbinwant);
+        const dim3 grid((p.cap + mvk::kListPerBlock - 1) / mvk::kListPerBlock, p.N);
+        before(KID_SEL_HIST);
+        hipLaunchKernelGGL(mvk::mv_sel_hist, grid, dim3(mvk::kRowThreads), 0, st, ls);
+        after(KID_SEL_HIST);
+        before(KID_SEL_SPLIT);
+        hipLaunchKernelGGL(mvk::mv_sel_split, grid, dim3(mvk::kRowThreads), 0, st, ls);
+        after(KID_SEL_SPLIT);
+        before(KID_SEL_RANK);
+        hipLaunchKernelGGL(mvk::mv_sel_rank, dim3(p.N), dim3(mvk::kRowThreads), 0, st, ls, kth, tiecut, slow);
+        after(KID_SEL_RANK);
+    }
 
     const bool sorted = a.worker_idx != nullptr;
     uint32_t* mask_votes32 = votes32;     // the packed vote bytes the mask is selected from
@@ -459,18 +499,19 @@ mv_status enqueue_step(mv_ctx* c, const StepArgs& a, void* stream_v)
         hipLaunchKernelGGL(mvk::mv_rs_keys, dim3(p.n_vote_blocks), dim3(mvk::kVoteThreads), 0, st, votes32, p.d,
                            a.rand_exp, rslist, p.rs_cap, rscount);
         after(KID_RS_KEYS);
-        const uint32_t per_wg = mvk::kRowThreads * mvk::kRsPerThread;
+        mvk::ListSelect ls;
+        ls.list = rslist;  ls.cap = p.rs_cap;  ls.count = rscount;  ls.base = nullptr;  ls.shift = 20;
+        ls.want = p.K;
+        ls.hist = rshist;  ls.list2 = rslist2;  ls.count2 = rscount + 1;  ls.bin_want = rscount + 2;
+        const dim3 grid((p.rs_cap + mvk::kListPerBlock - 1) / mvk::kListPerBlock);
         before(KID_RS_HIST);
-        hipLaunchKernelGGL(mvk::mv_rs_hist, dim3((p.rs_cap + per_wg - 1) / per_wg), dim3(mvk::kRowThreads), 0, st,
-                           rslist, p.rs_cap, rscount, rshist);
+        hipLaunchKernelGGL(mvk::mv_rs_hist, grid, dim3(mvk::kRowThreads), 0, st, ls);
         after(KID_RS_HIST);
         before(KID_RS_SPLIT);
-        hipLaunchKernelGGL(mvk::mv_rs_split, dim3((p.rs_cap + per_wg - 1) / per_wg), dim3(mvk::kRowThreads), 0, st,
-                           rslist, p.rs_cap, p.K, rscount, rshist, rslist2, rsbits);
+        hipLaunchKernelGGL(mvk::mv_rs_split, grid, dim3(mvk::kRowThreads), 0, st, ls, rsbits);
         after(KID_RS_SPLIT);
         before(KID_RS_RANK);
-        hipLaunchKernelGGL(mvk::mv_rs_rank, dim3(1), dim3(mvk::kRowThreads), 0, st, rslist2, p.rs_cap, rscount,
-                           rshist, rsbits);
+        hipLaunchKernelGGL(mvk::mv_rs_rank, dim3(1), dim3(mvk::kRowThreads), 0, st, ls, rscount, rsbits);
         after(KID_RS_RANK);
         before(KID_AD_COMPACT_COUNT);
         hipLaunchKernelGGL(mvk::mv_ad_compact_count, dim3(p.bit_blocks, 1), dim3(mvk::kVoteThreads), 0, st, rsbits,

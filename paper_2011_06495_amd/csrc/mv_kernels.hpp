@@ -752,10 +752,14 @@ __global__ __launch_bounds__(kRowThreads) void mv_row_select(
     const uint32_t* __restrict__ tau_bits,
     uint32_t* __restrict__ kth_out, uint32_t* __restrict__ tie_cut_out,
     uint32_t* __restrict__ worker_idx, uint32_t* __restrict__ votes32,
-    uint32_t* __restrict__ cnt_ge, uint32_t* __restrict__ slow_flag, int thresholds_only)
+    uint32_t* __restrict__ cnt_ge, uint32_t* __restrict__ slow_flag, int thresholds_only, int slow_rows_only)
 {
     __shared__ SelectLds lds;
     const uint32_t row = blockIdx.x, t = threadIdx.x;
+    if (slow_rows_only) {                         // the candidate lists are selected by the mv_sel_* kernels
+        const uint32_t C0 = row_count[row];
+        if (C0 >= K && C0 <= cap) return;         // whole workgroup
+    }
     // The first kKeep * kRowThreads list entries are fetched before the row's
     // candidate count is known (the list's storage holds cap entries; what lies at
     // or beyond the count is ignored later), so the two loads do not queue up.
@@ -1698,112 +1702,213 @@ __global__ __launch_bounds__(kVoteThreads) void mv_rs_keys(const uint32_t* __res
     }
 }
 
-// Histogram of the 11 leading key bits over the list (few, large workgroups: the
-// merge into the global histogram costs one atomic per occupied bin and workgroup).
-constexpr int kRsPerThread = 4;
-__global__ __launch_bounds__(kRowThreads) void mv_rs_hist(const u32x2* __restrict__ list, uint32_t list_cap,
-                                                          const uint32_t* __restrict__ rs_count,
-                                                          uint32_t* __restrict__ rs_hist)
+// ---- exact select over a long list with many workgroups ----------------------
+// Three kernels find the `want` largest keys of lists too long for one workgroup
+// to read more than once: (1) a histogram of kSelBins bins of (key - base) >> shift
+// over the list, (2) every workgroup locates the bin of the want-th largest and
+// moves that bin's members to a second list (and, with a bitmap, marks the
+// entries of higher bins), (3) one workgroup per list ranks the second list
+// exactly.  They serve the random selection (one list, base 0, shift 20: the 11
+// leading key bits) and the rows' top-K when K is large (one list per row, base =
+// the row's threshold estimate, shift = kFineShift).
+constexpr int kListPerThread = 4;
+constexpr int kListPerBlock = kRowThreads * kListPerThread;
+
+struct ListSelect {
+    const u32x2* list;        // rows of `cap` entries
+    uint32_t     cap;
+    const uint32_t* count;    // entries per row (clamped to cap)
+    const uint32_t* base;     // per row, or null: 0
+    uint32_t     shift;
+    uint32_t     want;        // K
+    uint32_t*    hist;        // rows of kSelBins counters, zero between steps
+    u32x2*       list2;       // rows of `cap` entries: members of the want-th largest's bin
+    uint32_t*    count2;      // per row, zero between steps
+    uint32_t*    bin_want;    // per row: the bin, and how many of its members are wanted
+};
+
+__device__ __forceinline__ uint32_t list_bin(uint32_t key, uint32_t base, uint32_t shift)
 {
-    __shared__ uint32_t hist[kSelBins];
+    return min((key - base) >> shift, (uint32_t)(kSelBins - 1));
+}
+// a row takes part when its list holds at least `want` entries and did not overflow
+__device__ __forceinline__ bool list_row_ok(const ListSelect& a, uint32_t row, uint32_t& n)
+{
+    n = a.count[row];
+    return n >= a.want && n <= a.cap;
+}
+
+__device__ __forceinline__ void list_hist_body(const ListSelect& a, uint32_t row, uint32_t* hist_lds)
+{
     const uint32_t t = threadIdx.x;
-    const uint32_t n = min(rs_count[0], list_cap);
-    const uint32_t i0 = blockIdx.x * (uint32_t)(kRowThreads * kRsPerThread);
+    uint32_t n;
+    if (!list_row_ok(a, row, n)) return;                             // whole workgroup
+    const uint32_t i0 = blockIdx.x * (uint32_t)kListPerBlock;
     if (i0 >= n) return;                                             // whole workgroup
-    uint32_t k[kRsPerThread];
+    const u32x2* list = a.list + (size_t)row * a.cap;
+    const uint32_t base = a.base ? a.base[row] : 0u;
+    uint32_t k[kListPerThread];
 #pragma unroll
-    for (int u = 0; u < kRsPerThread; ++u) {
+    for (int u = 0; u < kListPerThread; ++u) {
         const uint32_t i = i0 + (uint32_t)u * kRowThreads + t;
         k[u] = (i < n) ? list[i].x : 0xFFFFFFFFu;                   // keys are at most 0x7FFFFFFF
     }
-    for (int b = t; b < kSelBins; b += kRowThreads) hist[b] = 0;
+    for (int b = t; b < kSelBins; b += kRowThreads) hist_lds[b] = 0;
     __syncthreads();
+    const uint32_t lane = lane_id();
 #pragma unroll
-    for (int u = 0; u < kRsPerThread; ++u)
-        if (k[u] != 0xFFFFFFFFu) atomicAdd(&hist[k[u] >> 20], 1u);
+    for (int u = 0; u < kListPerThread; ++u) tally_digit(hist_lds, k[u] != 0xFFFFFFFFu, list_bin(k[u], base, a.shift), lane);
     __syncthreads();
+    uint32_t* hrow = a.hist + (size_t)row * kSelBins;
     for (int b = t; b < kSelBins; b += kRowThreads) {
-        const uint32_t c = hist[b];
-        if (c) atomicAdd(&rs_hist[b], c);
+        const uint32_t c = hist_lds[b];
+        if (c) atomicAdd(&hrow[b], c);
     }
 }
 
-// Every workgroup finds, from the histogram, the bin that holds the K-th soonest
-// clock; list entries in sooner bins are winners (their bit is set), the members
-// of that bin go to list2 for the exact ranking.  rs_count[1] = length of list2,
-// rs_count[2] = the bin, rs_count[3] = how many of its members win.
-__global__ __launch_bounds__(kRowThreads) void mv_rs_split(const u32x2* __restrict__ list, uint32_t list_cap,
-                                                           uint32_t K, uint32_t* __restrict__ rs_count,
-                                                           const uint32_t* __restrict__ rs_hist,
-                                                           u32x2* __restrict__ list2,
-                                                           uint32_t* __restrict__ rs_bits)
+struct ListSplitLds {
+    uint32_t hist[kSelBins];
+    uint64_t scan[kRowThreads / kWave + 1];
+    uint32_t bcast[3];
+    uint32_t base_sh;
+};
+
+__device__ __forceinline__ void list_split_body(const ListSelect& a, uint32_t row, ListSplitLds& lds,
+                                                uint32_t* __restrict__ bits)
 {
-    __shared__ uint32_t hist[kSelBins];
-    __shared__ uint64_t scan_lds[kRowThreads / kWave + 1];
-    __shared__ uint32_t bcast[3];
-    __shared__ uint32_t base_sh;
     const uint32_t t = threadIdx.x;
-    const uint32_t n = min(rs_count[0], list_cap);
-    const uint32_t i0 = blockIdx.x * (uint32_t)(kRowThreads * kRsPerThread);
-    if (i0 >= n && blockIdx.x != 0) return;                         // whole workgroup
-    u32x2 c[kRsPerThread];
+    uint32_t n;
+    if (!list_row_ok(a, row, n)) return;                             // whole workgroup
+    const uint32_t i0 = blockIdx.x * (uint32_t)kListPerBlock;
+    if (i0 >= n && blockIdx.x != 0) return;                          // whole workgroup
+    const u32x2* list = a.list + (size_t)row * a.cap;
+    const uint32_t base = a.base ? a.base[row] : 0u;
+    u32x2 c[kListPerThread];
 #pragma unroll
-    for (int u = 0; u < kRsPerThread; ++u) {
+    for (int u = 0; u < kListPerThread; ++u) {
         const uint32_t i = i0 + (uint32_t)u * kRowThreads + t;
         const u32x2 none = {0u, 0xFFFFFFFFu};
         c[u] = (i < n) ? list[i] : none;
     }
-    for (int b = t; b < kSelBins; b += kRowThreads) hist[b] = rs_hist[b];
+    const uint32_t* hrow = a.hist + (size_t)row * kSelBins;
+    for (int b = t; b < kSelBins; b += kRowThreads) lds.hist[b] = hrow[b];
     __syncthreads();
     uint32_t bin, want, in_bin;
-    find_rank_bin<kSelBins>(hist, scan_lds, bcast, K, bin, want, in_bin);   // n >= K: every worker voted K coordinates
+    find_rank_bin<kSelBins>(lds.hist, lds.scan, lds.bcast, a.want, bin, want, in_bin);
     if (blockIdx.x == 0 && t == 0) {
-        rs_count[2] = bin;
-        rs_count[3] = want;
+        a.bin_want[2 * row] = bin;
+        a.bin_want[2 * row + 1] = want;
     }
     uint32_t mine = 0;
 #pragma unroll
-    for (int u = 0; u < kRsPerThread; ++u) {
+    for (int u = 0; u < kListPerThread; ++u) {
         const bool valid = c[u].y != 0xFFFFFFFFu;
-        const uint32_t b = c[u].x >> 20;
-        if (valid && b > bin) atomicOr(&rs_bits[c[u].y >> 5], 1u << (c[u].y & 31u));
+        const uint32_t b = list_bin(c[u].x, base, a.shift);
+        if (bits && valid && b > bin) atomicOr(&bits[c[u].y >> 5], 1u << (c[u].y & 31u));
         mine += (valid && b == bin);
     }
     uint64_t total;
-    const uint64_t ex = block_excl_scan64<kRowThreads>(mine, scan_lds, total);
+    const uint64_t ex = block_excl_scan64<kRowThreads>(mine, lds.scan, total);
     if (total == 0) return;                                          // whole workgroup
-    if (t == 0) base_sh = atomicAdd(&rs_count[1], (uint32_t)total);
+    if (t == 0) lds.base_sh = atomicAdd(&a.count2[row], (uint32_t)total);
     __syncthreads();
-    uint32_t pos = base_sh + (uint32_t)ex;
+    uint32_t pos = lds.base_sh + (uint32_t)ex;
+    u32x2* list2 = a.list2 + (size_t)row * a.cap;
 #pragma unroll
-    for (int u = 0; u < kRsPerThread; ++u) {
+    for (int u = 0; u < kListPerThread; ++u) {
         const bool valid = c[u].y != 0xFFFFFFFFu;
-        if (valid && (c[u].x >> 20) == bin) {
-            if (pos < list_cap) list2[pos] = c[u];
+        if (valid && list_bin(c[u].x, base, a.shift) == bin) {
+            if (pos < a.cap) list2[pos] = c[u];
             ++pos;
         }
     }
 }
 
-// One workgroup: exact ranking of the bin's members, marks the winners among
-// them, and leaves the histogram and the counters at zero for the next step.
-__global__ __launch_bounds__(kRowThreads) void mv_rs_rank(const u32x2* __restrict__ list2, uint32_t list_cap,
-                                                          uint32_t* __restrict__ rs_count,
-                                                          uint32_t* __restrict__ rs_hist,
+// Ranks the second list exactly: kth / tie_cut as for a row's candidate list.
+// Leaves the row's histogram and count2 at zero.  Returns false when the row does
+// not take part.
+__device__ __forceinline__ bool list_rank_body(const ListSelect& a, uint32_t row, SelectLds& lds, uint32_t& kth,
+                                               uint32_t& tie_cut, uint32_t& path)
+{
+    const uint32_t t = threadIdx.x;
+    uint32_t n;
+    if (!list_row_ok(a, row, n)) return false;                       // whole workgroup
+    const uint32_t C = min(a.count2[row], a.cap), bin = a.bin_want[2 * row], want = a.bin_want[2 * row + 1];
+    __syncthreads();                                                  // everyone has read the counters
+    uint32_t* hrow = a.hist + (size_t)row * kSelBins;
+    for (int b = t; b < kSelBins; b += kRowThreads) hrow[b] = 0;
+    if (t == 0) a.count2[row] = 0;
+    if (C == 0 || want == 0 || want > C) return false;                // cannot happen after the split
+    const u32x2* list2 = a.list2 + (size_t)row * a.cap;
+    const uint32_t base = (a.base ? a.base[row] : 0u) + (bin << a.shift);
+    if (C <= (uint32_t)kKeep * kRowThreads) {
+        uint32_t k[kKeep];
+        const uint32_t last = C - 1;
+#pragma unroll
+        for (int q = 0; q < kKeep; ++q) {
+            k[q] = list2[min((uint32_t)q * kRowThreads + t, last)].x;
+            if ((q & 7) == 7) __builtin_amdgcn_sched_barrier(0);
+        }
+        const KeysInRegs src{k, C};
+        select_among_candidates(src, list2, C, want, base, lds, kth, tie_cut, path);
+    } else {
+        auto at = [list2](uint64_t i) { return list2[i].x; };
+        const KeysInMemory<decltype(at)> src{at, C};
+        select_among_candidates(src, list2, C, want, base, lds, kth, tie_cut, path);
+    }
+    return true;
+}
+
+// ---- the rows' top-K when K is large (grid: blocks of the candidate list x rows)
+__global__ __launch_bounds__(kRowThreads) void mv_sel_hist(ListSelect a)
+{
+    __shared__ uint32_t hist[kSelBins];
+    list_hist_body(a, blockIdx.y, hist);
+}
+__global__ __launch_bounds__(kRowThreads) void mv_sel_split(ListSelect a)
+{
+    __shared__ ListSplitLds lds;
+    list_split_body(a, blockIdx.y, lds, nullptr);
+}
+__global__ __launch_bounds__(kRowThreads) void mv_sel_rank(ListSelect a, uint32_t* __restrict__ kth_out,
+                                                           uint32_t* __restrict__ tie_cut_out,
+                                                           uint32_t* __restrict__ slow_flag)
+{
+    __shared__ SelectLds lds;
+    const uint32_t row = blockIdx.x;
+    uint32_t kth, tie_cut, path;
+    if (!list_rank_body(a, row, lds, kth, tie_cut, path)) return;
+    if (threadIdx.x == 0) {
+        kth_out[row] = kth;
+        tie_cut_out[row] = tie_cut;
+        if (path) slow_flag[row] = path;          // diagnostic only
+    }
+}
+
+// ---- random selection: one list (row 0); winners are marked in the bitmap
+__global__ __launch_bounds__(kRowThreads) void mv_rs_hist(ListSelect a)
+{
+    __shared__ uint32_t hist[kSelBins];
+    list_hist_body(a, 0, hist);
+}
+__global__ __launch_bounds__(kRowThreads) void mv_rs_split(ListSelect a, uint32_t* __restrict__ rs_bits)
+{
+    __shared__ ListSplitLds lds;
+    list_split_body(a, 0, lds, rs_bits);
+}
+// Also leaves the list's length at zero for the next step.
+__global__ __launch_bounds__(kRowThreads) void mv_rs_rank(ListSelect a, uint32_t* __restrict__ rs_count,
                                                           uint32_t* __restrict__ rs_bits)
 {
     __shared__ SelectLds lds;
-    const uint32_t t = threadIdx.x;
-    const uint32_t C = min(rs_count[1], list_cap), bin = rs_count[2], want = rs_count[3];
-    __syncthreads();                                                  // everyone has read the counters
-    for (int b = t; b < kSelBins; b += kRowThreads) rs_hist[b] = 0;
-    if (t < 4) rs_count[t] = 0;
-    if (C == 0 || want == 0 || want > C) return;                      // cannot happen after mv_rs_split
     uint32_t kth, tie_cut, path;
-    auto at = [list2](uint64_t i) { return list2[i].x; };
-    const KeysInMemory<decltype(at)> src{at, C};
-    select_among_candidates(src, list2, C, want, bin << 20, lds, kth, tie_cut, path);
-    for (uint32_t i = t; i < C; i += kRowThreads) {
+    const uint32_t C = min(a.count2[0], a.cap);
+    const bool ranked = list_rank_body(a, 0, lds, kth, tie_cut, path);
+    __syncthreads();
+    if (threadIdx.x == 0) rs_count[0] = 0;
+    if (!ranked) return;
+    const u32x2* list2 = a.list2;
+    for (uint32_t i = threadIdx.x; i < C; i += kRowThreads) {
         const u32x2 c = list2[i];
         if (is_taken(c, kth, tie_cut)) atomicOr(&rs_bits[c.y >> 5], 1u << (c.y & 31u));
     }

@@ -154,3 +154,12 @@ def test_random_selection_paper_regime_full(oracle):
     # ResNet-18 size, N = 10 workers, phi = 1e-2 (Sec. 4.1, 4.2)
     w = W.C2.with_size(W.C2.d, K=111740)
     run_full_rs(oracle, w, 2)
+
+
+@pytest.mark.timeout(1200)
+def test_paper_regime_full(oracle):
+    # the paper's own setting for plain majority voting: ResNet-18 size, N = 10, phi = 1e-2 (Sec. 4.1, 4.2);
+    # about 2K = 223,000 candidates per row: the select spread over many workgroups
+    w = W.C2.with_size(W.C2.d, K=111740)
+    paths = run_full(oracle, w, 2)
+    assert all(p != 1 for step in paths for p in step)

@@ -261,7 +261,7 @@ def test_every_route_of_the_row_select(oracle, case):
     histogram bins (equal magnitudes), tie groups small / large / larger than the
     LDS list, a K-th magnitude more than an octave above the estimate, and a
     candidate list longer than the register file holds."""
-    rng = np.random.default_rng(hash(case) % 1000)
+    rng = np.random.default_rng(sum(map(ord, case)))
     N, d, K = 3, 300007, 3000
     if case == "ties_in_lds_by_counting":
         groups = [(2600, 2.0, 3.0), (900, 1.0, 1.0)]            # 900 ties, 400 taken
@@ -293,6 +293,31 @@ def test_every_route_of_the_row_select(oracle, case):
         assert all(p == 2 for p in path)
     if case == "more_candidates_than_registers":
         assert min(cand) > 32768
+
+
+@pytest.mark.parametrize("case", ["normal", "lattice_ties", "kth_far_above_threshold"])
+def test_long_candidate_lists_are_selected_by_many_workgroups(oracle, case):
+    """K above 32768: about 2K candidates per row, selected by the histogram / split /
+    rank kernels instead of one workgroup per row."""
+    rng = np.random.default_rng(sum(map(ord, case)))
+    N, d, K = 3, 600011, 40000
+    if case == "normal":
+        g = rng.standard_normal((N, d)).astype(np.float32)
+    elif case == "lattice_ties":
+        g = (np.round(rng.standard_normal((N, d)) * 24.0) / 64.0).astype(np.float32)   # about 200 distinct magnitudes
+    else:
+        g = np.stack([_levels_row(rng, d, [(45000, 8.0, 16.0), (30000, 1.0, 1.1)]) for _ in range(N)])
+    e = np.zeros_like(g)
+    say("many-workgroup select %s N=%d d=%d K=%d" % (case, N, d, K))
+    with GpuStepper(N, d, K) as gs:
+        gs.set_error(e)
+        gs.set_grads(g)
+        gs.step()
+        got = gs.fetch()
+        cand, _, path = gs.row_stats()
+    say("  candidates %s path %s" % (cand, path))
+    assert_matches_oracle(got, oracle.vote_step(g, e, K), case)
+    assert all(p != 1 for p in path), "these rows are meant for the candidate-list routes"
 
 
 def test_tie_cut_inside_a_run_of_neighbouring_ties(oracle):
