@@ -319,8 +319,16 @@ def main():
         t_or = time.perf_counter() - t1
         oracle_agrees = bool(np.array_equal(ref.mask_idx, mask0) and
                              np.array_equal(ref.agg.view(np.uint32), agg0.view(np.uint32)))
+        # one thread, on a bounded sample: the plain vote step of the first two workers' rows
+        n1 = min(N, 2)
+        t1 = time.perf_counter()
+        mv_oracle.vote_step(g_host0[:n1], e0[:n1], K, threads=1)
+        t_one = time.perf_counter() - t1
         cpu_baseline = {"value": round(coords / t_or, 1), "unit": "coords/s", "cores": threads,
                         "kind": "oracle", "seconds": round(t_or, 2),
+                        "single_thread": {"value": round(n1 * d / t_one, 1), "unit": "coords/s", "cores": 1,
+                                          "seconds": round(t_one, 2),
+                                          "sample": "plain vote step of rows 0..%d only" % (n1 - 1)},
                         "sample": "one full %s of %s (all %d rows, d=%d), step-0 inputs" %
                                   ("add-drop step (first, full vote)" if ad else
                                    "vote step with random selection" if rs else "vote step", w.name, N, d)}
