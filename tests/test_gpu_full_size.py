@@ -163,3 +163,54 @@ def test_paper_regime_full(oracle):
     w = W.C2.with_size(W.C2.d, K=111740)
     paths = run_full(oracle, w, 2)
     assert all(p != 1 for step in paths for p in step)
+
+
+@pytest.mark.timeout(900)
+def test_rows_longer_than_2_30_coordinates():
+    """Two rows of 2^30 + 4099 coordinates: byte offsets inside a row pass 2^32 and
+    coordinates pass 2^30.  A full sort on the host would take minutes, so the check
+    is by construction: 64 planted values far above a floor of small noise must be
+    each worker's vote, the mask, the aggregate, and the only coordinates the error
+    buffers lose.  Row 0's noise is uniform (one histogram bin then holds far more
+    coordinates than a candidate list: the exact path from memory), row 1's is
+    exponential (the candidate-list route)."""
+    d, K, N = (1 << 30) + 4099, 64, 2
+    rng = np.random.default_rng(99)
+    say("two rows of %d coordinates" % d)
+    t0 = time.time()
+    fixed = np.array([0, 1, 1023, 1024, (1 << 20) + 1, (1 << 30) - 1, 1 << 30, (1 << 30) + 1, d - 1])
+    others = np.setdiff1d(np.unique(rng.integers(0, d, 200)), fixed)[:K - fixed.size]
+    planted = np.sort(np.concatenate([fixed, others]))
+    assert planted.size == K and np.unique(planted).size == K
+    sign = np.where(np.arange(K) % 2 == 0, 1.0, -1.0).astype(np.float32)
+    vals = [(2.0 + np.arange(K)).astype(np.float32) * sign, (100.0 - np.arange(K)).astype(np.float32) * sign]
+    with GpuStepper(N, d, K) as gs:
+        gs.e[:, :d].zero_()
+        rows = []
+        for n in range(N):
+            if n == 0:
+                g = rng.random(d, dtype=np.float32)
+            else:
+                g = rng.standard_exponential(d, dtype=np.float32)
+            g *= np.float32(1e-3)                       # exponential: the largest of 2^30 is about 0.021
+            g[planted] = vals[n]
+            gs.g[n, :d].copy_(torch_from(g))
+            g[planted] = 0.0
+            rows.append(g)
+        gs.step()
+        got = gs.fetch()
+        cand, _, path = gs.row_stats()
+    say("  step done after %.1f s, candidates %s path %s" % (time.time() - t0, cand, path))
+    assert path[0] == 1 and path[1] != 1, "row 0 is meant for the exact path, row 1 for its candidate list"
+    for n in range(N):
+        assert np.array_equal(got.worker_idx[n], planted.astype(np.uint32))
+        assert np.array_equal(got.err[n], rows[n])
+    assert np.array_equal(got.mask_idx, planted.astype(np.uint32))
+    assert np.array_equal(np.flatnonzero(got.votes), planted)
+    assert np.all(got.votes[planted] == N)
+    assert np.array_equal(got.agg, (vals[0] + vals[1]) * np.float32(0.5))
+
+
+def torch_from(a):
+    import torch
+    return torch.from_numpy(a)
