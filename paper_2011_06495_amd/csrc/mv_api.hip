@@ -22,13 +22,12 @@ enum KernelId {
     KID_MASK_EMIT,
     KID_GATHER,
     // add-drop voting only
-    KID_AD_COLLECT_ADD,
-    KID_AD_COLLECT_DROP,
+    KID_AD_COLLECT,
     KID_AD_SELECT,
     KID_AD_APPLY,
-    KID_AD_COMPACT_COUNT,
+    KID_AD_COUNT_LEVELS,
+    KID_AD_COMPACT_COUNT,      // random selection's bitmap only
     KID_AD_COMPACT_EMIT,
-    KID_AD_LEVELS,
     // rows' select with many workgroups (large K only)
     KID_SEL_HIST,
     KID_SEL_SPLIT,
@@ -42,8 +41,8 @@ enum KernelId {
 };
 const char* const kKernelNames[KID_COUNT] = {
     "mv_sample_hist",    "mv_pick_threshold",  "mv_stream_collect",   "mv_row_select",      "mv_row_votes",
-    "mv_mask_count",     "mv_mask_emit",       "mv_gather_update",    "mv_ad_collect_add",  "mv_ad_collect_drop",
-    "mv_ad_select",      "mv_ad_apply",        "mv_ad_compact_count", "mv_ad_compact_emit", "mv_ad_levels",
+    "mv_mask_count",     "mv_mask_emit",       "mv_gather_update",    "mv_ad_collect",      "mv_ad_select",
+    "mv_ad_apply",       "mv_ad_count_levels", "mv_ad_compact_count", "mv_ad_compact_emit",
     "mv_sel_hist",       "mv_sel_split",       "mv_sel_rank",
     "mv_rs_keys",        "mv_rs_hist",         "mv_rs_split",         "mv_rs_rank"};
 
@@ -68,7 +67,7 @@ struct Plan {
     bool     add_drop;
     uint32_t nwords, nwords_pad;  // 32-bit words of a row's vote bitmap, and padded to a multiple of 4
     uint32_t cap_d;               // capacity of a row's list of removal candidates
-    uint32_t bit_blocks;          // workgroups of 1024 bitmap words per row
+    uint32_t bit_blocks;          // workgroups of kBitBlockWords bitmap words per row
     // rows' select with many workgroups: when about 2K candidates are far more than one workgroup keeps in registers
     bool     multi_select;
     size_t   off_selhist, off_selcount2, off_selbinwant, off_sellist2;
@@ -156,7 +155,7 @@ Plan make_plan(const mv_config* c)
     p.nwords = (uint32_t)((p.d + 31) / 32);
     p.nwords_pad = (p.nwords + 3) / 4 * 4;
     p.cap_d = p.K;
-    p.bit_blocks = (p.nwords_pad + 1023) / 1024;
+    p.bit_blocks = (p.nwords_pad + mvk::kBitBlockWords - 1) / mvk::kBitBlockWords;
     if (p.add_drop) {
         p.off_alist = off;   off += align_up((size_t)p.N * p.cap * 8);
         p.off_dlist = off;   off += align_up((size_t)p.N * p.cap_d * 8);
@@ -454,15 +453,11 @@ mv_status enqueue_step(mv_ctx* c, const StepArgs& a, void* stream_v)
         // update of msum and of the standing votes, sorted add / drop lists
         const uint32_t k_ad = (uint32_t)a.k_ad;
         uint32_t* msum32 = reinterpret_cast<uint32_t*>(a.msum);
-        before(KID_AD_COLLECT_ADD);
-        hipLaunchKernelGGL(mvk::mv_ad_collect_add, dim3(p.emit_blocks, p.N), dim3(mvk::kVoteThreads), 0, st, a.err,
-                           a.ld_e, p.d, cand, p.cap, rowcnt, kth, tiecut, slow, a.vote_bits, a.ld_bits, alist,
-                           adcount);
-        after(KID_AD_COLLECT_ADD);
-        before(KID_AD_COLLECT_DROP);
-        hipLaunchKernelGGL(mvk::mv_ad_collect_drop, dim3(p.bit_blocks, p.N), dim3(mvk::kVoteThreads), 0, st, a.err,
-                           a.ld_e, p.d, kth, tiecut, a.vote_bits, a.ld_bits, p.nwords_pad, dlist, p.cap_d, adcount);
-        after(KID_AD_COLLECT_DROP);
+        before(KID_AD_COLLECT);
+        hipLaunchKernelGGL(mvk::mv_ad_collect, dim3(p.emit_blocks + p.bit_blocks, p.N), dim3(mvk::kVoteThreads), 0,
+                           st, a.err, a.ld_e, p.d, cand, p.cap, rowcnt, kth, tiecut, slow, a.vote_bits, a.ld_bits,
+                           p.nwords_pad, alist, dlist, p.cap_d, adcount, p.emit_blocks);
+        after(KID_AD_COLLECT);
         before(KID_AD_SELECT);
         hipLaunchKernelGGL(mvk::mv_ad_select, dim3(2, p.N), dim3(mvk::kRowThreads), 0, st, alist, p.cap, dlist,
                            p.cap_d, adcount, k_ad, tau, slow, adthr, a.counts);
@@ -471,19 +466,16 @@ mv_status enqueue_step(mv_ctx* c, const StepArgs& a, void* stream_v)
         hipLaunchKernelGGL(mvk::mv_ad_apply, dim3(p.emit_blocks, p.N), dim3(mvk::kVoteThreads), 0, st, alist, p.cap,
                            dlist, p.cap_d, adcount, adthr, adbits, p.nwords_pad, msum32);
         after(KID_AD_APPLY);
-        before(KID_AD_COMPACT_COUNT);
-        hipLaunchKernelGGL(mvk::mv_ad_compact_count, dim3(p.bit_blocks, 2 * p.N), dim3(mvk::kVoteThreads), 0, st,
-                           adbits, p.nwords_pad, p.bit_blocks, adblk);
-        after(KID_AD_COMPACT_COUNT);
+        before(KID_AD_COUNT_LEVELS);
+        hipLaunchKernelGGL(mvk::mv_ad_count_levels, dim3(2 * p.N * p.bit_blocks + p.n_vote_blocks),
+                           dim3(mvk::kVoteThreads), 0, st, adbits, p.nwords_pad, p.bit_blocks, adblk,
+                           2 * p.N * p.bit_blocks, msum32, p.d, cntge);
+        after(KID_AD_COUNT_LEVELS);
         before(KID_AD_COMPACT_EMIT);
         hipLaunchKernelGGL(mvk::mv_ad_compact_emit, dim3(p.bit_blocks, 2 * p.N), dim3(mvk::kVoteThreads), 0, st,
                            adbits, p.nwords_pad, p.bit_blocks, adblk, k_ad, a.add_idx, a.drop_idx, a.vote_bits,
                            a.ld_bits);
         after(KID_AD_COMPACT_EMIT);
-        before(KID_AD_LEVELS);
-        hipLaunchKernelGGL(mvk::mv_ad_levels, dim3(p.n_vote_blocks), dim3(mvk::kVoteThreads), 0, st, msum32, p.d,
-                           cntge);
-        after(KID_AD_LEVELS);
         mask_votes32 = msum32;
     }
     if (random_sel) {

@@ -1330,15 +1330,14 @@ __device__ __forceinline__ bool vote_bit(const uint32_t* __restrict__ bits_row, 
 
 // A-lists.  Rows whose top-K came from the candidate list: one thread per candidate.
 // Rows selected from memory (slow_flag == 1): the whole row is read.
-__global__ __launch_bounds__(kVoteThreads) void mv_ad_collect_add(
+__device__ __forceinline__ void ad_collect_add_block(
+    uint32_t bx, uint32_t nbx, uint64_t* scan_lds, uint32_t* bcast,
     const float* __restrict__ e, int64_t ld_e, int64_t d,
     const u32x2* __restrict__ cand, uint32_t cap, const uint32_t* __restrict__ row_count,
     const uint32_t* __restrict__ kth_in, const uint32_t* __restrict__ tie_cut_in,
     const uint32_t* __restrict__ slow_flag, const uint32_t* __restrict__ vote_bits, int64_t ld_bits,
     u32x2* __restrict__ a_list, uint32_t* __restrict__ ad_count)
 {
-    __shared__ uint64_t scan_lds[kVoteThreads / kWave + 1];
-    __shared__ uint32_t bcast[1];
     const uint32_t row = blockIdx.y, t = threadIdx.x;
     const uint32_t kth = kth_in[row], tie_cut = tie_cut_in[row];
     const uint32_t* bits = vote_bits + (int64_t)row * ld_bits;
@@ -1346,7 +1345,7 @@ __global__ __launch_bounds__(kVoteThreads) void mv_ad_collect_add(
     uint32_t* counter = ad_count + 2 * row;
     if (slow_flag[row] == 1u) {
         const float* xrow = e + (int64_t)row * ld_e;
-        for (int64_t j0 = (int64_t)blockIdx.x * kVoteThreads; j0 < d; j0 += (int64_t)gridDim.x * kVoteThreads) {
+        for (int64_t j0 = (int64_t)bx * kVoteThreads; j0 < d; j0 += (int64_t)nbx * kVoteThreads) {
             const int64_t j = j0 + t;
             u32x2 c = {0u, 0u};
             bool in_a = false;
@@ -1362,7 +1361,7 @@ __global__ __launch_bounds__(kVoteThreads) void mv_ad_collect_add(
     }
     const uint32_t C = row_count[row];
     const u32x2* crow = cand + (size_t)row * cap;
-    for (uint64_t i0 = (uint64_t)blockIdx.x * kVoteThreads; i0 < C; i0 += (uint64_t)gridDim.x * kVoteThreads) {
+    for (uint64_t i0 = (uint64_t)bx * kVoteThreads; i0 < C; i0 += (uint64_t)nbx * kVoteThreads) {
         const uint64_t i = i0 + t;
         u32x2 c = {0u, 0u};
         bool in_a = false;
@@ -1378,60 +1377,154 @@ __global__ __launch_bounds__(kVoteThreads) void mv_ad_collect_add(
 // D-lists: the standing vote's bitmap is scanned, 4 words per thread; a set
 // coordinate that is not in the row's top-K goes to the list with the
 // complemented magnitude, so that "largest first" selects the smallest magnitudes.
-__global__ __launch_bounds__(kVoteThreads) void mv_ad_collect_drop(
+constexpr int kDropStage = 4096;   // set bits of one workgroup's stretch staged in LDS
+constexpr int kBitIt = 1;          // quads of bitmap words per thread in the bitmap kernels (more per thread measured no faster)
+constexpr int kBitBlockWords = kVoteThreads * 4 * kBitIt;   // bitmap words per workgroup
+__device__ __forceinline__ void ad_collect_drop_block(
+    uint32_t bx, uint64_t* scan_lds, uint32_t* bcast, uint32_t* stage,
     const float* __restrict__ e, int64_t ld_e, int64_t d,
     const uint32_t* __restrict__ kth_in, const uint32_t* __restrict__ tie_cut_in,
     const uint32_t* __restrict__ vote_bits, int64_t ld_bits, uint32_t nwords,
     u32x2* __restrict__ d_list, uint32_t cap_d, uint32_t* __restrict__ ad_count)
 {
-    __shared__ uint64_t scan_lds[kVoteThreads / kWave + 1];
-    __shared__ uint32_t bcast[1];
     const uint32_t row = blockIdx.y, t = threadIdx.x;
     const uint32_t kth = kth_in[row], tie_cut = tie_cut_in[row];
     const float* xrow = e + (int64_t)row * ld_e;
-    const uint32_t w0 = (blockIdx.x * kVoteThreads + t) * 4;
-    uint32_t w[4] = {0, 0, 0, 0};
-    if (w0 < nwords) {                            // rows are padded to a multiple of 4 words
-        const u32x4 v = *reinterpret_cast<const u32x4*>(vote_bits + (int64_t)row * ld_bits + w0);
-        w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
+    // the workgroup's stretch of the bitmap: kBitIt quads of words per thread
+    uint32_t w[kBitIt][4];
+    uint32_t n_bits = 0;
+#pragma unroll
+    for (int it = 0; it < kBitIt; ++it) {
+        const uint32_t w0 = bx * kBitBlockWords + ((uint32_t)it * kVoteThreads + t) * 4;
+        w[it][0] = w[it][1] = w[it][2] = w[it][3] = 0;
+        if (w0 < nwords) {                        // rows are padded to a multiple of 4 words
+            const u32x4 v = *reinterpret_cast<const u32x4*>(vote_bits + (int64_t)row * ld_bits + w0);
+            w[it][0] = v.x; w[it][1] = v.y; w[it][2] = v.z; w[it][3] = v.w;
+            if ((uint64_t)w0 * 32 + 128 > (uint64_t)d) {        // bits at or beyond d do not exist
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    for (int b = 0; b < 32; ++b)
+                        if ((int64_t)(w0 + q) * 32 + b >= d) w[it][q] &= ~(1u << b);
+            }
+        }
+        n_bits += __popc(w[it][0]) + __popc(w[it][1]) + __popc(w[it][2]) + __popc(w[it][3]);
     }
+    uint64_t total;
+    const uint64_t ex = block_excl_scan64<kVoteThreads>(n_bits, scan_lds, total);
+    if (total == 0) return;                                  // whole workgroup
+    u32x2* drow = d_list + (size_t)row * cap_d;
+    if (total <= (uint64_t)kDropStage) {                     // uniform
+        // Usual case (few members of the standing vote in this stretch): their coordinates
+        // are parked in LDS and the values then fetched by all lanes together, instead of
+        // one dependent load per set bit inside each thread's own loop.
+        uint32_t sp = (uint32_t)ex;
+#pragma unroll
+        for (int it = 0; it < kBitIt; ++it) {
+            const uint32_t w0 = bx * kBitBlockWords + ((uint32_t)it * kVoteThreads + t) * 4;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                uint32_t m = w[it][q];
+                while (m) {
+                    const uint32_t b = __ffs((int)m) - 1;
+                    m &= m - 1;
+                    stage[sp++] = (w0 + q) * 32 + b;
+                }
+            }
+        }
+        __syncthreads();
+        constexpr int kRounds = kDropStage / kVoteThreads;
+        u32x2 c[kRounds];
+        uint32_t n_keep = 0, keep = 0;
+#pragma unroll
+        for (int r = 0; r < kRounds; ++r) {
+            const uint32_t i = (uint32_t)r * kVoteThreads + t;
+            if (i < (uint32_t)total) {
+                const uint32_t j = stage[i];
+                c[r].x = __float_as_uint(xrow[j]) & kAbsMask;
+                c[r].y = j;
+                if (!is_taken(c[r], kth, tie_cut)) {         // left the top-K: a drop candidate
+                    keep |= 1u << r;
+                    ++n_keep;
+                }
+            }
+        }
+        uint32_t pos = reserve_in_list(n_keep, ad_count + 2 * row + 1, scan_lds, bcast);
+#pragma unroll
+        for (int r = 0; r < kRounds; ++r) {
+            if (keep & (1u << r)) {
+                if (pos < cap_d) {
+                    u32x2 o;
+                    o.x = kAbsMask - c[r].x;
+                    o.y = c[r].y;
+                    drow[pos] = o;
+                }
+                ++pos;
+            }
+        }
+        return;
+    }
+    __syncthreads();                                         // scan_lds is reused below
+    // a stretch dense with votes: bit by bit
     uint32_t n_mine = 0;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        uint32_t m = w[q];
-        while (m) {
-            const uint32_t b = __ffs((int)m) - 1;
-            m &= m - 1;
-            const uint32_t j = (w0 + q) * 32 + b;
-            if ((int64_t)j < d) {
+    for (int it = 0; it < kBitIt; ++it) {
+        const uint32_t w0 = bx * kBitBlockWords + ((uint32_t)it * kVoteThreads + t) * 4;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            uint32_t m = w[it][q];
+            while (m) {
+                const uint32_t b = __ffs((int)m) - 1;
+                m &= m - 1;
                 u32x2 c;
-                c.x = __float_as_uint(xrow[j]) & kAbsMask;
-                c.y = j;
-                if (is_taken(c, kth, tie_cut)) w[q] &= ~(1u << b);   // stays in the vote: not a drop candidate
-            } else {
-                w[q] &= ~(1u << b);
+                c.y = (w0 + q) * 32 + b;
+                c.x = __float_as_uint(xrow[c.y]) & kAbsMask;
+                if (is_taken(c, kth, tie_cut)) w[it][q] &= ~(1u << b);   // stays in the vote: not a drop candidate
             }
+            n_mine += __popc(w[it][q]);
         }
-        n_mine += __popc(w[q]);
     }
     uint32_t pos = reserve_in_list(n_mine, ad_count + 2 * row + 1, scan_lds, bcast);
-    u32x2* drow = d_list + (size_t)row * cap_d;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        uint32_t m = w[q];
-        while (m) {
-            const uint32_t b = __ffs((int)m) - 1;
-            m &= m - 1;
-            const uint32_t j = (w0 + q) * 32 + b;
-            if (pos < cap_d) {
-                u32x2 c;
-                c.x = kAbsMask - (__float_as_uint(xrow[j]) & kAbsMask);
-                c.y = j;
-                drow[pos] = c;
+    for (int it = 0; it < kBitIt; ++it) {
+        const uint32_t w0 = bx * kBitBlockWords + ((uint32_t)it * kVoteThreads + t) * 4;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            uint32_t m = w[it][q];
+            while (m) {
+                const uint32_t b = __ffs((int)m) - 1;
+                m &= m - 1;
+                const uint32_t j = (w0 + q) * 32 + b;
+                if (pos < cap_d) {
+                    u32x2 c;
+                    c.x = kAbsMask - (__float_as_uint(xrow[j]) & kAbsMask);
+                    c.y = j;
+                    drow[pos] = c;
+                }
+                ++pos;
             }
-            ++pos;
         }
     }
+}
+
+// One launch for both lists: the first add_blocks workgroups of a row walk its
+// candidate list (A-list), the others its standing vote's bitmap (D-list).
+__global__ __launch_bounds__(kVoteThreads) void mv_ad_collect(
+    const float* __restrict__ e, int64_t ld_e, int64_t d,
+    const u32x2* __restrict__ cand, uint32_t cap, const uint32_t* __restrict__ row_count,
+    const uint32_t* __restrict__ kth_in, const uint32_t* __restrict__ tie_cut_in,
+    const uint32_t* __restrict__ slow_flag, const uint32_t* __restrict__ vote_bits, int64_t ld_bits,
+    uint32_t nwords, u32x2* __restrict__ a_list, u32x2* __restrict__ d_list, uint32_t cap_d,
+    uint32_t* __restrict__ ad_count, uint32_t add_blocks)
+{
+    __shared__ uint64_t scan_lds[kVoteThreads / kWave + 1];
+    __shared__ uint32_t bcast[1];
+    __shared__ uint32_t stage[kDropStage];
+    if (blockIdx.x < add_blocks)
+        ad_collect_add_block(blockIdx.x, add_blocks, scan_lds, bcast, e, ld_e, d, cand, cap, row_count, kth_in,
+                             tie_cut_in, slow_flag, vote_bits, ld_bits, a_list, ad_count);
+    else
+        ad_collect_drop_block(blockIdx.x - add_blocks, scan_lds, bcast, stage, e, ld_e, d, kth_in, tie_cut_in,
+                              vote_bits, ld_bits, nwords, d_list, cap_d, ad_count);
 }
 
 // Workgroup (0, n): the K_ad first of row n's A-list under (magnitude desc,
@@ -1499,24 +1592,32 @@ __global__ __launch_bounds__(kVoteThreads) void mv_ad_apply(
 }
 
 // Ordered compaction of the 2N scratch bitmaps, in two kernels: set bits per block of
-// 1024 words, then (prefix over the blocks before + scan inside the block) each
+// kBitBlockWords words, then (prefix over the blocks before + scan inside the block) each
 // thread writes its set coordinates in ascending order.  The second kernel also
 // clears the scratch words and folds them into the standing vote.
+__device__ __forceinline__ void compact_count_block(const uint32_t* __restrict__ ad_bits, uint32_t nwords_pad,
+                                                    uint32_t nblk, uint32_t* __restrict__ blk_cnt, uint32_t r,
+                                                    uint32_t bx, uint64_t* scan_lds)
+{
+    uint32_t n = 0;
+#pragma unroll
+    for (int it = 0; it < kBitIt; ++it) {
+        const uint32_t w0 = bx * kBitBlockWords + ((uint32_t)it * kVoteThreads + threadIdx.x) * 4;
+        if (w0 < nwords_pad) {
+            const u32x4 v = *reinterpret_cast<const u32x4*>(ad_bits + (size_t)r * nwords_pad + w0);
+            n += __popc(v.x) + __popc(v.y) + __popc(v.z) + __popc(v.w);
+        }
+    }
+    uint64_t total;
+    (void)block_excl_scan64<kVoteThreads>(n, scan_lds, total);
+    if (threadIdx.x == 0) blk_cnt[(size_t)r * nblk + bx] = (uint32_t)total;
+}
 __global__ __launch_bounds__(kVoteThreads) void mv_ad_compact_count(const uint32_t* __restrict__ ad_bits,
                                                                     uint32_t nwords_pad, uint32_t nblk,
                                                                     uint32_t* __restrict__ blk_cnt)
 {
     __shared__ uint64_t scan_lds[kVoteThreads / kWave + 1];
-    const uint32_t r = blockIdx.y;
-    const uint32_t w0 = (blockIdx.x * kVoteThreads + threadIdx.x) * 4;
-    uint32_t n = 0;
-    if (w0 < nwords_pad) {
-        const u32x4 v = *reinterpret_cast<const u32x4*>(ad_bits + (size_t)r * nwords_pad + w0);
-        n = __popc(v.x) + __popc(v.y) + __popc(v.z) + __popc(v.w);
-    }
-    uint64_t total;
-    (void)block_excl_scan64<kVoteThreads>(n, scan_lds, total);
-    if (threadIdx.x == 0) blk_cnt[(size_t)r * nblk + blockIdx.x] = (uint32_t)total;
+    compact_count_block(ad_bits, nwords_pad, nblk, blk_cnt, blockIdx.y, blockIdx.x, scan_lds);
 }
 
 __global__ __launch_bounds__(kVoteThreads) void mv_ad_compact_emit(uint32_t* __restrict__ ad_bits,
@@ -1530,55 +1631,64 @@ __global__ __launch_bounds__(kVoteThreads) void mv_ad_compact_emit(uint32_t* __r
 {
     __shared__ uint64_t scan_lds[kVoteThreads / kWave + 1];
     const uint32_t r = blockIdx.y, row = r >> 1, which = r & 1u;
+    // the block's words first (cleared behind): their latency overlaps the prefix's loads
+    uint32_t w[kBitIt][4];
+#pragma unroll
+    for (int it = 0; it < kBitIt; ++it) {
+        const uint32_t w0 = blockIdx.x * kBitBlockWords + ((uint32_t)it * kVoteThreads + threadIdx.x) * 4;
+        w[it][0] = w[it][1] = w[it][2] = w[it][3] = 0;
+        if (w0 < nwords_pad) {
+            u32x4* p = reinterpret_cast<u32x4*>(ad_bits + (size_t)r * nwords_pad + w0);
+            const u32x4 v = *p;
+            w[it][0] = v.x; w[it][1] = v.y; w[it][2] = v.z; w[it][3] = v.w;
+            if ((v.x | v.y | v.z | v.w) != 0u) {
+                const u32x4 z = {0u, 0u, 0u, 0u};
+                *p = z;
+            }
+        }
+    }
     uint64_t mine = 0;
     for (uint32_t b = threadIdx.x; b < blockIdx.x; b += kVoteThreads) mine += blk_cnt[(size_t)r * nblk + b];
     uint64_t before;
     (void)block_excl_scan64<kVoteThreads>(mine, scan_lds, before);
     __syncthreads();
-    const uint32_t w0 = (blockIdx.x * kVoteThreads + threadIdx.x) * 4;
-    uint32_t w[4] = {0, 0, 0, 0};
-    if (w0 < nwords_pad) {
-        u32x4* p = reinterpret_cast<u32x4*>(ad_bits + (size_t)r * nwords_pad + w0);
-        const u32x4 v = *p;
-        w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
-        if ((v.x | v.y | v.z | v.w) != 0u) {
-            const u32x4 z = {0u, 0u, 0u, 0u};
-            *p = z;
-        }
-    }
-    const uint32_t n = __popc(w[0]) + __popc(w[1]) + __popc(w[2]) + __popc(w[3]);
-    uint64_t total;
-    uint32_t pos = (uint32_t)(before + block_excl_scan64<kVoteThreads>(n, scan_lds, total));
     uint32_t* out = (which ? drop_idx : add_idx) + (size_t)row * k_ad;
     uint32_t* vrow = vote_bits ? vote_bits + (int64_t)row * ld_bits : nullptr;   // null: compaction only
+    uint32_t done = (uint32_t)before;             // set bits before the current quad row
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        uint32_t m = w[q];
-        if (m) {
-            // additions and removals never touch the same bit, but may share a word
-            if (vote_bits) {
+    for (int it = 0; it < kBitIt; ++it) {
+        const uint32_t w0 = blockIdx.x * kBitBlockWords + ((uint32_t)it * kVoteThreads + threadIdx.x) * 4;
+        const uint32_t n = __popc(w[it][0]) + __popc(w[it][1]) + __popc(w[it][2]) + __popc(w[it][3]);
+        uint64_t total;
+        uint32_t pos = done + (uint32_t)block_excl_scan64<kVoteThreads>(n, scan_lds, total);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            uint32_t m = w[it][q];
+            if (m && vrow) {
+                // additions and removals never touch the same bit, but may share a word
                 if (which) atomicAnd(&vrow[w0 + q], ~m);
                 else       atomicOr(&vrow[w0 + q], m);
             }
+            while (m) {
+                const uint32_t b = __ffs((int)m) - 1;
+                m &= m - 1;
+                if (pos < k_ad) out[pos] = (w0 + q) * 32 + b;
+                ++pos;
+            }
         }
-        while (m) {
-            const uint32_t b = __ffs((int)m) - 1;
-            m &= m - 1;
-            if (pos < k_ad) out[pos] = (w0 + q) * 32 + b;
-            ++pos;
-        }
+        done += (uint32_t)total;
+        __syncthreads();
     }
 }
 
 // Histogram of the vote levels of msum (one byte per coordinate, values 0..N):
 // lvl_cnt[v] = number of coordinates with exactly v votes.
-__global__ __launch_bounds__(kVoteThreads) void mv_ad_levels(const uint32_t* __restrict__ msum32, int64_t d,
-                                                             uint32_t* __restrict__ lvl_cnt)
+__device__ __forceinline__ void ad_levels_block(const uint32_t* __restrict__ msum32, int64_t d,
+                                                uint32_t* __restrict__ lvl_cnt, uint32_t bx, uint32_t* h /*256*/)
 {
-    __shared__ uint32_t h[256];
     h[threadIdx.x] = 0;
     __syncthreads();
-    const int64_t base = (int64_t)blockIdx.x * kVoteBlock;
+    const int64_t base = (int64_t)bx * kVoteBlock;
     uint32_t zeros = 0;                           // most coordinates have no vote
 #pragma unroll
     for (int it = 0; it < kVoteBlock / (kVoteThreads * 16); ++it) {
@@ -1590,8 +1700,13 @@ __global__ __launch_bounds__(kVoteThreads) void mv_ad_levels(const uint32_t* __r
                 zeros += (uint32_t)min((int64_t)16, d - j);
             } else {
 #pragma unroll
-                for (int q = 0; q < 16; ++q)
-                    if (j + q < d) atomicAdd(&h[(ww[q >> 2] >> (8 * (q & 3))) & 255u], 1u);
+                for (int q = 0; q < 16; ++q) {
+                    const uint32_t v = (ww[q >> 2] >> (8 * (q & 3))) & 255u;
+                    if (j + q < d) {
+                        if (v) atomicAdd(&h[v], 1u);
+                        else   ++zeros;
+                    }
+                }
             }
         }
     }
@@ -1599,6 +1714,23 @@ __global__ __launch_bounds__(kVoteThreads) void mv_ad_levels(const uint32_t* __r
     __syncthreads();
     const uint32_t c = h[threadIdx.x];
     if (c) atomicAdd(&lvl_cnt[threadIdx.x], c);
+}
+
+// One launch after mv_ad_apply: the first n_count_blocks workgroups count the set bits
+// of the 2N scratch bitmaps per block, the others take the histogram of msum's levels.
+__global__ __launch_bounds__(kVoteThreads) void mv_ad_count_levels(const uint32_t* __restrict__ ad_bits,
+                                                                   uint32_t nwords_pad, uint32_t nblk,
+                                                                   uint32_t* __restrict__ blk_cnt,
+                                                                   uint32_t n_count_blocks,
+                                                                   const uint32_t* __restrict__ msum32, int64_t d,
+                                                                   uint32_t* __restrict__ lvl_cnt)
+{
+    __shared__ uint64_t scan_lds[kVoteThreads / kWave + 1];
+    __shared__ uint32_t h[256];
+    if (blockIdx.x < n_count_blocks)
+        compact_count_block(ad_bits, nwords_pad, nblk, blk_cnt, blockIdx.x / nblk, blockIdx.x % nblk, scan_lds);
+    else
+        ad_levels_block(msum32, d, lvl_cnt, blockIdx.x - n_count_blocks, h);
 }
 
 // ----------------------------------------------------------------------------
@@ -1841,7 +1973,7 @@ __device__ __forceinline__ bool list_rank_body(const ListSelect& a, uint32_t row
     if (C == 0 || want == 0 || want > C) return false;                // cannot happen after the split
     const u32x2* list2 = a.list2 + (size_t)row * a.cap;
     const uint32_t base = (a.base ? a.base[row] : 0u) + (bin << a.shift);
-    if (C <= (uint32_t)kKeep * kRowThreads) {
+    if (C > 8u * kRowThreads && C <= (uint32_t)kKeep * kRowThreads) {   // short lists: a few loads per pass are cheaper
         uint32_t k[kKeep];
         const uint32_t last = C - 1;
 #pragma unroll
