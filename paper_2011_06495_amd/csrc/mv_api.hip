@@ -159,10 +159,10 @@ Plan make_plan(const mv_config* c)
     if (p.add_drop) {
         p.off_alist = off;   off += align_up((size_t)p.N * p.cap * 8);
         p.off_dlist = off;   off += align_up((size_t)p.N * p.cap_d * 8);
-        p.off_adcount = off; off += align_up((size_t)p.N * 2 * 4);
+        p.off_adcount = off; off += align_up((size_t)p.N * 2 * mvk::kCounterStride * 4);
         p.off_adthr = off;   off += align_up((size_t)p.N * 4 * 4);
-        p.off_adbits = off;  off += align_up((size_t)p.N * 2 * p.nwords_pad * 4);
-        p.off_adblk = off;   off += align_up((size_t)p.N * 2 * p.bit_blocks * 4);
+        p.off_adbits = off;  off += align_up((size_t)p.N * p.nwords_pad * 4);
+        p.off_adblk = off;   off += align_up((size_t)p.N * p.bit_blocks * 8);
     }
     // (measured: one workgroup per row takes 20 us at 24K candidates, 38 us at 55K, 89 us at 230K; the three
     // kernels of the many-workgroup select about 40 us)
@@ -178,7 +178,7 @@ Plan make_plan(const mv_config* c)
     p.off_rshist = off;  off += align_up((size_t)mvk::kSelBins * 4);
     p.off_rscount = off; off += align_up(4 * 4);
     p.off_rsbits = off;  off += align_up((size_t)p.nwords_pad * 4);
-    p.off_rsblk = off;   off += align_up((size_t)p.bit_blocks * 4);
+    p.off_rsblk = off;   off += align_up((size_t)p.bit_blocks * 8);
     p.off_rslist = off;  off += align_up((size_t)p.rs_cap * 8);
     p.off_rslist2 = off; off += align_up((size_t)p.rs_cap * 8);
     p.total_bytes = off;
@@ -359,7 +359,7 @@ mv_status enqueue_step(mv_ctx* c, const StepArgs& a, void* stream_v)
     uint32_t* adcount = p.add_drop ? ws_ptr<uint32_t>(c, p.off_adcount) : nullptr;
     uint32_t* adthr = p.add_drop ? ws_ptr<uint32_t>(c, p.off_adthr) : nullptr;
     uint32_t* adbits = p.add_drop ? ws_ptr<uint32_t>(c, p.off_adbits) : nullptr;
-    uint32_t* adblk = p.add_drop ? ws_ptr<uint32_t>(c, p.off_adblk) : nullptr;
+    mvk::u32x2* adblk = p.add_drop ? ws_ptr<mvk::u32x2>(c, p.off_adblk) : nullptr;
 
     const int slot = (int)(c->steps_done % kEventRing);
     for (int i = 0; i < KID_COUNT; ++i) c->ev_recorded[slot][i] = false;
@@ -467,12 +467,12 @@ mv_status enqueue_step(mv_ctx* c, const StepArgs& a, void* stream_v)
                            dlist, p.cap_d, adcount, adthr, adbits, p.nwords_pad, msum32);
         after(KID_AD_APPLY);
         before(KID_AD_COUNT_LEVELS);
-        hipLaunchKernelGGL(mvk::mv_ad_count_levels, dim3(2 * p.N * p.bit_blocks + p.n_vote_blocks),
+        hipLaunchKernelGGL(mvk::mv_ad_count_levels, dim3(p.N * p.bit_blocks + p.n_vote_blocks),
                            dim3(mvk::kVoteThreads), 0, st, adbits, p.nwords_pad, p.bit_blocks, adblk,
-                           2 * p.N * p.bit_blocks, msum32, p.d, cntge);
+                           a.vote_bits, a.ld_bits, p.N * p.bit_blocks, msum32, p.d, cntge, p.N);
         after(KID_AD_COUNT_LEVELS);
         before(KID_AD_COMPACT_EMIT);
-        hipLaunchKernelGGL(mvk::mv_ad_compact_emit, dim3(p.bit_blocks, 2 * p.N), dim3(mvk::kVoteThreads), 0, st,
+        hipLaunchKernelGGL(mvk::mv_ad_compact_emit, dim3(p.bit_blocks, p.N), dim3(mvk::kVoteThreads), 0, st,
                            adbits, p.nwords_pad, p.bit_blocks, adblk, k_ad, a.add_idx, a.drop_idx, a.vote_bits,
                            a.ld_bits);
         after(KID_AD_COMPACT_EMIT);
@@ -484,7 +484,7 @@ mv_status enqueue_step(mv_ctx* c, const StepArgs& a, void* stream_v)
         uint32_t* rshist = ws_ptr<uint32_t>(c, p.off_rshist);
         uint32_t* rscount = ws_ptr<uint32_t>(c, p.off_rscount);
         uint32_t* rsbits = ws_ptr<uint32_t>(c, p.off_rsbits);
-        uint32_t* rsblk = ws_ptr<uint32_t>(c, p.off_rsblk);
+        mvk::u32x2* rsblk = ws_ptr<mvk::u32x2>(c, p.off_rsblk);
         mvk::u32x2* rslist = ws_ptr<mvk::u32x2>(c, p.off_rslist);
         mvk::u32x2* rslist2 = ws_ptr<mvk::u32x2>(c, p.off_rslist2);
         before(KID_RS_KEYS);
@@ -507,7 +507,7 @@ mv_status enqueue_step(mv_ctx* c, const StepArgs& a, void* stream_v)
         after(KID_RS_RANK);
         before(KID_AD_COMPACT_COUNT);
         hipLaunchKernelGGL(mvk::mv_ad_compact_count, dim3(p.bit_blocks, 1), dim3(mvk::kVoteThreads), 0, st, rsbits,
-                           p.nwords_pad, p.bit_blocks, rsblk);
+                           p.nwords_pad, p.bit_blocks, rsblk, (const uint32_t*)nullptr, (int64_t)0);
         after(KID_AD_COMPACT_COUNT);
         before(KID_AD_COMPACT_EMIT);
         hipLaunchKernelGGL(mvk::mv_ad_compact_emit, dim3(p.bit_blocks, 1), dim3(mvk::kVoteThreads), 0, st, rsbits,

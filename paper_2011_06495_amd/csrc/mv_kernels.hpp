@@ -199,6 +199,15 @@ __global__ __launch_bounds__(kSampleThreads) void mv_sample_hist(const GT* __res
     }
 }
 
+// The add-drop lists' length counters: many workgroups bump them with returning
+// atomics, which complete one after the other per cache line, so every counter has a
+// 128-byte line of its own.
+constexpr uint32_t kCounterStride = 32;
+__device__ __forceinline__ uint32_t ad_counter(uint32_t row, uint32_t which)
+{
+    return (2u * row + which) * kCounterStride;
+}
+
 // One workgroup per row:
 //   tau_bits[row] = lower edge of the highest bin such that at least m_target
 //                   sampled coordinates lie in that bin or above (0 if fewer).
@@ -215,7 +224,7 @@ __global__ __launch_bounds__(kRowThreads) void mv_pick_threshold(uint32_t* __res
     __shared__ uint64_t scan_lds[kRowThreads / kWave + 1];
     __shared__ uint32_t found;
     const uint32_t row = blockIdx.x, t = threadIdx.x;
-    if (ad_count && t < 2) ad_count[2 * row + t] = 0;    // lengths of the row's add / drop candidate lists
+    if (ad_count && t < 2) ad_count[ad_counter(row, t)] = 0;   // lengths of the row's add / drop candidate lists
     uint32_t* hrow = hist + (size_t)row * kHistBins;
     constexpr int per = kHistBins / kRowThreads;   // bins per thread, descending bin order
     uint32_t c[per];
@@ -924,25 +933,9 @@ __device__ __forceinline__ void vote_threshold(const uint32_t* __restrict__ cnt_
                                                uint32_t K, uint32_t* lds_lvl /*256*/, uint32_t* lds2,
                                                uint32_t& vstar, uint32_t& take_eq, int exact_levels)
 {
-    if (exact_levels) {
-        // cnt_ge[v] = number of coordinates with EXACTLY v votes, v = 0..N (one set of
-        // counters): walk down from N until K coordinates are covered
-        if (threadIdx.x == 0) {
-            uint32_t above = 0, v = N;
-            while (v > 0 && above + cnt_ge[v] < K) {
-                above += cnt_ge[v];
-                --v;
-            }
-            lds2[0] = v;
-            lds2[1] = K - above;
-        }
-        __syncthreads();
-        vstar = lds2[0];
-        take_eq = lds2[1];
-        return;
-    }
-    // cnt_ge holds one set of 256 level counters per worker row; add the rows up
-    // (levels 1..N matter), all loads of a thread in flight together
+    // cnt_ge holds one set of 256 level counters per worker row (the rows only spread the
+    // atomics that filled them over as many cache lines); add the rows up (levels 0..N),
+    // all loads of a thread in flight together
     for (uint32_t v = threadIdx.x; v < 256; v += blockDim.x) lds_lvl[v] = 0;
     __syncthreads();
     const uint32_t per_row = N + 1, n_vals = N * per_row;
@@ -961,10 +954,22 @@ __device__ __forceinline__ void vote_threshold(const uint32_t* __restrict__ cnt_
     }
     __syncthreads();
     if (threadIdx.x == 0) {
-        uint32_t v = N;
-        while (v > 1 && lds_lvl[v] < K) --v;
-        lds2[0] = v;
-        lds2[1] = K - ((v < N) ? lds_lvl[v + 1] : 0u);
+        if (exact_levels) {
+            // the sums are the numbers of coordinates with EXACTLY v votes, v = 0..N:
+            // walk down from N until K coordinates are covered
+            uint32_t above = 0, v = N;
+            while (v > 0 && above + lds_lvl[v] < K) {
+                above += lds_lvl[v];
+                --v;
+            }
+            lds2[0] = v;
+            lds2[1] = K - above;
+        } else {
+            uint32_t v = N;
+            while (v > 1 && lds_lvl[v] < K) --v;
+            lds2[0] = v;
+            lds2[1] = K - ((v < N) ? lds_lvl[v + 1] : 0u);
+        }
     }
     __syncthreads();
     vstar = lds2[0];
@@ -1342,7 +1347,7 @@ __device__ __forceinline__ void ad_collect_add_block(
     const uint32_t kth = kth_in[row], tie_cut = tie_cut_in[row];
     const uint32_t* bits = vote_bits + (int64_t)row * ld_bits;
     u32x2* arow = a_list + (size_t)row * cap;
-    uint32_t* counter = ad_count + 2 * row;
+    uint32_t* counter = ad_count + ad_counter(row, 0);
     if (slow_flag[row] == 1u) {
         const float* xrow = e + (int64_t)row * ld_e;
         for (int64_t j0 = (int64_t)bx * kVoteThreads; j0 < d; j0 += (int64_t)nbx * kVoteThreads) {
@@ -1448,7 +1453,7 @@ __device__ __forceinline__ void ad_collect_drop_block(
                 }
             }
         }
-        uint32_t pos = reserve_in_list(n_keep, ad_count + 2 * row + 1, scan_lds, bcast);
+        uint32_t pos = reserve_in_list(n_keep, ad_count + ad_counter(row, 1), scan_lds, bcast);
 #pragma unroll
         for (int r = 0; r < kRounds; ++r) {
             if (keep & (1u << r)) {
@@ -1483,7 +1488,7 @@ __device__ __forceinline__ void ad_collect_drop_block(
             n_mine += __popc(w[it][q]);
         }
     }
-    uint32_t pos = reserve_in_list(n_mine, ad_count + 2 * row + 1, scan_lds, bcast);
+    uint32_t pos = reserve_in_list(n_mine, ad_count + ad_counter(row, 1), scan_lds, bcast);
 #pragma unroll
     for (int it = 0; it < kBitIt; ++it) {
         const uint32_t w0 = bx * kBitBlockWords + ((uint32_t)it * kVoteThreads + t) * 4;
@@ -1540,7 +1545,7 @@ __global__ __launch_bounds__(kRowThreads) void mv_ad_select(
     __shared__ SelectLds lds;
     const uint32_t which = blockIdx.x, row = blockIdx.y, t = threadIdx.x;
     const u32x2* list = which ? d_list + (size_t)row * cap_d : a_list + (size_t)row * cap_a;
-    const uint32_t len = min(ad_count[2 * row + which], which ? cap_d : cap_a);
+    const uint32_t len = min(ad_count[ad_counter(row, which)], which ? cap_d : cap_a);
     uint32_t kth, tie_cut;
     if (len == 0) {
         kth = 0xFFFFFFFFu;                        // nothing passes the membership test
@@ -1564,9 +1569,10 @@ __global__ __launch_bounds__(kRowThreads) void mv_ad_select(
     }
 }
 
-// Applies the selected additions and removals: marks them in the scratch bitmaps
-// (add: row 2n, drop: row 2n+1) and moves msum by +1 / -1 (bytes packed four to a
-// word; a byte never carries because 0 <= msum <= N <= 255 holds before and after).
+// Applies the selected additions and removals: marks them in the row's scratch
+// bitmap (one bitmap for both: a marked coordinate that is in the standing vote is a
+// removal, one that is not is an addition) and moves msum by +1 / -1 (bytes packed four
+// to a word; a byte never carries because 0 <= msum <= N <= 255 holds before and after).
 __global__ __launch_bounds__(kVoteThreads) void mv_ad_apply(
     const u32x2* __restrict__ a_list, uint32_t cap_a, const u32x2* __restrict__ d_list, uint32_t cap_d,
     const uint32_t* __restrict__ ad_count, const uint32_t* __restrict__ ad_thr,
@@ -1576,9 +1582,9 @@ __global__ __launch_bounds__(kVoteThreads) void mv_ad_apply(
 #pragma unroll
     for (int which = 0; which < 2; ++which) {
         const u32x2* list = which ? d_list + (size_t)row * cap_d : a_list + (size_t)row * cap_a;
-        const uint32_t len = min(ad_count[2 * row + which], which ? cap_d : cap_a);
+        const uint32_t len = min(ad_count[ad_counter(row, which)], which ? cap_d : cap_a);
         const uint32_t kth = ad_thr[4 * row + 2 * which], tie_cut = ad_thr[4 * row + 2 * which + 1];
-        uint32_t* bits = ad_bits + (size_t)(2 * row + which) * nwords_pad;
+        uint32_t* bits = ad_bits + (size_t)row * nwords_pad;   // additions and removals share the row's bitmap
         for (uint32_t i = blockIdx.x * kVoteThreads + threadIdx.x; i < len; i += gridDim.x * kVoteThreads) {
             const u32x2 c = list[i];
             if (is_taken(c, kth, tie_cut)) {
@@ -1591,38 +1597,57 @@ __global__ __launch_bounds__(kVoteThreads) void mv_ad_apply(
     }
 }
 
-// Ordered compaction of the 2N scratch bitmaps, in two kernels: set bits per block of
-// kBitBlockWords words, then (prefix over the blocks before + scan inside the block) each
-// thread writes its set coordinates in ascending order.  The second kernel also
-// clears the scratch words and folds them into the standing vote.
+// Ordered compaction of the N scratch bitmaps, in two kernels: marked additions and
+// removals per block of kBitBlockWords words, then (prefix over the blocks before + scan
+// inside the block) each thread writes its marked coordinates in ascending order to the
+// add list or the drop list.  The second kernel also clears the scratch words and folds
+// them into the standing vote.  Without a standing vote (vote_bits == nullptr) every
+// marked coordinate counts as an addition: a plain ordered compaction.
 __device__ __forceinline__ void compact_count_block(const uint32_t* __restrict__ ad_bits, uint32_t nwords_pad,
-                                                    uint32_t nblk, uint32_t* __restrict__ blk_cnt, uint32_t r,
-                                                    uint32_t bx, uint64_t* scan_lds)
+                                                    uint32_t nblk, u32x2* __restrict__ blk_cnt,
+                                                    const uint32_t* __restrict__ vote_bits, int64_t ld_bits,
+                                                    uint32_t r, uint32_t bx, uint64_t* scan_lds)
 {
-    uint32_t n = 0;
+    const uint32_t* vrow = vote_bits ? vote_bits + (int64_t)r * ld_bits : nullptr;
+    uint32_t n_add = 0, n_drop = 0;
 #pragma unroll
     for (int it = 0; it < kBitIt; ++it) {
         const uint32_t w0 = bx * kBitBlockWords + ((uint32_t)it * kVoteThreads + threadIdx.x) * 4;
         if (w0 < nwords_pad) {
             const u32x4 v = *reinterpret_cast<const u32x4*>(ad_bits + (size_t)r * nwords_pad + w0);
-            n += __popc(v.x) + __popc(v.y) + __popc(v.z) + __popc(v.w);
+            const uint32_t m[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                if (m[q]) {                       // rare: the standing vote's word decides which is which
+                    const uint32_t in_vote = vrow ? vrow[w0 + q] : 0u;
+                    n_add += __popc(m[q] & ~in_vote);
+                    n_drop += __popc(m[q] & in_vote);
+                }
+            }
         }
     }
     uint64_t total;
-    (void)block_excl_scan64<kVoteThreads>(n, scan_lds, total);
-    if (threadIdx.x == 0) blk_cnt[(size_t)r * nblk + bx] = (uint32_t)total;
+    (void)block_excl_scan64<kVoteThreads>(pack2(n_add, n_drop), scan_lds, total);
+    if (threadIdx.x == 0) {
+        u32x2 c;
+        c.x = (uint32_t)(total >> 32);
+        c.y = (uint32_t)total;
+        blk_cnt[(size_t)r * nblk + bx] = c;
+    }
 }
 __global__ __launch_bounds__(kVoteThreads) void mv_ad_compact_count(const uint32_t* __restrict__ ad_bits,
                                                                     uint32_t nwords_pad, uint32_t nblk,
-                                                                    uint32_t* __restrict__ blk_cnt)
+                                                                    u32x2* __restrict__ blk_cnt,
+                                                                    const uint32_t* __restrict__ vote_bits,
+                                                                    int64_t ld_bits)
 {
     __shared__ uint64_t scan_lds[kVoteThreads / kWave + 1];
-    compact_count_block(ad_bits, nwords_pad, nblk, blk_cnt, blockIdx.y, blockIdx.x, scan_lds);
+    compact_count_block(ad_bits, nwords_pad, nblk, blk_cnt, vote_bits, ld_bits, blockIdx.y, blockIdx.x, scan_lds);
 }
 
 __global__ __launch_bounds__(kVoteThreads) void mv_ad_compact_emit(uint32_t* __restrict__ ad_bits,
                                                                    uint32_t nwords_pad, uint32_t nblk,
-                                                                   const uint32_t* __restrict__ blk_cnt,
+                                                                   const u32x2* __restrict__ blk_cnt,
                                                                    uint32_t k_ad,
                                                                    uint32_t* __restrict__ add_idx,
                                                                    uint32_t* __restrict__ drop_idx,
@@ -1630,53 +1655,69 @@ __global__ __launch_bounds__(kVoteThreads) void mv_ad_compact_emit(uint32_t* __r
                                                                    int64_t ld_bits)
 {
     __shared__ uint64_t scan_lds[kVoteThreads / kWave + 1];
-    const uint32_t r = blockIdx.y, row = r >> 1, which = r & 1u;
+    const uint32_t row = blockIdx.y;
+    uint32_t* vrow = vote_bits ? vote_bits + (int64_t)row * ld_bits : nullptr;   // null: compaction only, all additions
     // the block's words first (cleared behind): their latency overlaps the prefix's loads
-    uint32_t w[kBitIt][4];
+    uint32_t w[kBitIt][4], in_vote[kBitIt][4];
 #pragma unroll
     for (int it = 0; it < kBitIt; ++it) {
         const uint32_t w0 = blockIdx.x * kBitBlockWords + ((uint32_t)it * kVoteThreads + threadIdx.x) * 4;
-        w[it][0] = w[it][1] = w[it][2] = w[it][3] = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) w[it][q] = in_vote[it][q] = 0;
         if (w0 < nwords_pad) {
-            u32x4* p = reinterpret_cast<u32x4*>(ad_bits + (size_t)r * nwords_pad + w0);
+            u32x4* p = reinterpret_cast<u32x4*>(ad_bits + (size_t)row * nwords_pad + w0);
             const u32x4 v = *p;
             w[it][0] = v.x; w[it][1] = v.y; w[it][2] = v.z; w[it][3] = v.w;
             if ((v.x | v.y | v.z | v.w) != 0u) {
                 const u32x4 z = {0u, 0u, 0u, 0u};
                 *p = z;
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    if (w[it][q] && vrow) in_vote[it][q] = vrow[w0 + q];
             }
         }
     }
     uint64_t mine = 0;
-    for (uint32_t b = threadIdx.x; b < blockIdx.x; b += kVoteThreads) mine += blk_cnt[(size_t)r * nblk + b];
+    for (uint32_t b = threadIdx.x; b < blockIdx.x; b += kVoteThreads) {
+        const u32x2 c = blk_cnt[(size_t)row * nblk + b];
+        mine += pack2(c.x, c.y);
+    }
     uint64_t before;
     (void)block_excl_scan64<kVoteThreads>(mine, scan_lds, before);
     __syncthreads();
-    uint32_t* out = (which ? drop_idx : add_idx) + (size_t)row * k_ad;
-    uint32_t* vrow = vote_bits ? vote_bits + (int64_t)row * ld_bits : nullptr;   // null: compaction only
-    uint32_t done = (uint32_t)before;             // set bits before the current quad row
+    uint32_t* out_add = add_idx + (size_t)row * k_ad;
+    uint32_t* out_drop = drop_idx ? drop_idx + (size_t)row * k_ad : nullptr;
+    uint64_t done = before;                       // (additions, removals) before the current quad row
 #pragma unroll
     for (int it = 0; it < kBitIt; ++it) {
         const uint32_t w0 = blockIdx.x * kBitBlockWords + ((uint32_t)it * kVoteThreads + threadIdx.x) * 4;
-        const uint32_t n = __popc(w[it][0]) + __popc(w[it][1]) + __popc(w[it][2]) + __popc(w[it][3]);
+        uint32_t n_add = 0, n_drop = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            n_add += __popc(w[it][q] & ~in_vote[it][q]);
+            n_drop += __popc(w[it][q] & in_vote[it][q]);
+        }
         uint64_t total;
-        uint32_t pos = done + (uint32_t)block_excl_scan64<kVoteThreads>(n, scan_lds, total);
+        const uint64_t at = done + block_excl_scan64<kVoteThreads>(pack2(n_add, n_drop), scan_lds, total);
+        uint32_t pos_add = (uint32_t)(at >> 32), pos_drop = (uint32_t)at;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             uint32_t m = w[it][q];
-            if (m && vrow) {
-                // additions and removals never touch the same bit, but may share a word
-                if (which) atomicAnd(&vrow[w0 + q], ~m);
-                else       atomicOr(&vrow[w0 + q], m);
-            }
+            if (m && vrow) atomicXor(&vrow[w0 + q], m);     // additions enter the standing vote, removals leave it
             while (m) {
                 const uint32_t b = __ffs((int)m) - 1;
                 m &= m - 1;
-                if (pos < k_ad) out[pos] = (w0 + q) * 32 + b;
-                ++pos;
+                const uint32_t j = (w0 + q) * 32 + b;
+                if ((in_vote[it][q] >> b) & 1u) {
+                    if (out_drop && pos_drop < k_ad) out_drop[pos_drop] = j;
+                    ++pos_drop;
+                } else {
+                    if (pos_add < k_ad) out_add[pos_add] = j;
+                    ++pos_add;
+                }
             }
         }
-        done += (uint32_t)total;
+        done += total;
         __syncthreads();
     }
 }
@@ -1684,19 +1725,29 @@ __global__ __launch_bounds__(kVoteThreads) void mv_ad_compact_emit(uint32_t* __r
 // Histogram of the vote levels of msum (one byte per coordinate, values 0..N):
 // lvl_cnt[v] = number of coordinates with exactly v votes.
 __device__ __forceinline__ void ad_levels_block(const uint32_t* __restrict__ msum32, int64_t d,
-                                                uint32_t* __restrict__ lvl_cnt, uint32_t bx, uint32_t* h /*256*/)
+                                                uint32_t* __restrict__ lvl_cnt, uint32_t n_sets, uint32_t bx,
+                                                uint32_t* h /*256*/)
 {
+    // all of the block's words first: a load placed after the LDS atomics of the previous
+    // round would wait for its full latency every round
+    constexpr int kIt = kVoteBlock / (kVoteThreads * 16);
+    const int64_t base = (int64_t)bx * kVoteBlock;
+    u32x4 w[kIt];
+#pragma unroll
+    for (int it = 0; it < kIt; ++it) {
+        const int64_t j = base + ((int64_t)it * kVoteThreads + threadIdx.x) * 16;
+        const u32x4 z = {0u, 0u, 0u, 0u};
+        w[it] = (j < d) ? *reinterpret_cast<const u32x4*>(msum32 + (j >> 2)) : z;
+    }
     h[threadIdx.x] = 0;
     __syncthreads();
-    const int64_t base = (int64_t)bx * kVoteBlock;
     uint32_t zeros = 0;                           // most coordinates have no vote
 #pragma unroll
-    for (int it = 0; it < kVoteBlock / (kVoteThreads * 16); ++it) {
+    for (int it = 0; it < kIt; ++it) {
         const int64_t j = base + ((int64_t)it * kVoteThreads + threadIdx.x) * 16;
         if (j < d) {
-            const u32x4 w = *reinterpret_cast<const u32x4*>(msum32 + (j >> 2));
-            const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
-            if ((w.x | w.y | w.z | w.w) == 0u) {
+            const uint32_t ww[4] = {w[it].x, w[it].y, w[it].z, w[it].w};
+            if ((ww[0] | ww[1] | ww[2] | ww[3]) == 0u) {
                 zeros += (uint32_t)min((int64_t)16, d - j);
             } else {
 #pragma unroll
@@ -1712,25 +1763,29 @@ __device__ __forceinline__ void ad_levels_block(const uint32_t* __restrict__ msu
     }
     if (zeros) atomicAdd(&h[0], zeros);
     __syncthreads();
+    // the workgroups take turns over the n_sets sets of counters (the sum counts), so that
+    // their atomics do not all queue up on one cache line
     const uint32_t c = h[threadIdx.x];
-    if (c) atomicAdd(&lvl_cnt[threadIdx.x], c);
+    if (c) atomicAdd(&lvl_cnt[(size_t)(bx % n_sets) * 256 + threadIdx.x], c);
 }
 
-// One launch after mv_ad_apply: the first n_count_blocks workgroups count the set bits
-// of the 2N scratch bitmaps per block, the others take the histogram of msum's levels.
+// One launch after mv_ad_apply: the first n_count_blocks workgroups count the additions
+// and removals marked in the N scratch bitmaps per block, the others take the histogram of msum's levels.
 __global__ __launch_bounds__(kVoteThreads) void mv_ad_count_levels(const uint32_t* __restrict__ ad_bits,
                                                                    uint32_t nwords_pad, uint32_t nblk,
-                                                                   uint32_t* __restrict__ blk_cnt,
-                                                                   uint32_t n_count_blocks,
+                                                                   u32x2* __restrict__ blk_cnt,
+                                                                   const uint32_t* __restrict__ vote_bits,
+                                                                   int64_t ld_bits, uint32_t n_count_blocks,
                                                                    const uint32_t* __restrict__ msum32, int64_t d,
-                                                                   uint32_t* __restrict__ lvl_cnt)
+                                                                   uint32_t* __restrict__ lvl_cnt, uint32_t n_sets)
 {
     __shared__ uint64_t scan_lds[kVoteThreads / kWave + 1];
     __shared__ uint32_t h[256];
     if (blockIdx.x < n_count_blocks)
-        compact_count_block(ad_bits, nwords_pad, nblk, blk_cnt, blockIdx.x / nblk, blockIdx.x % nblk, scan_lds);
+        compact_count_block(ad_bits, nwords_pad, nblk, blk_cnt, vote_bits, ld_bits, blockIdx.x / nblk,
+                            blockIdx.x % nblk, scan_lds);
     else
-        ad_levels_block(msum32, d, lvl_cnt, blockIdx.x - n_count_blocks, h);
+        ad_levels_block(msum32, d, lvl_cnt, n_sets, blockIdx.x - n_count_blocks, h);
 }
 
 // ----------------------------------------------------------------------------
