@@ -138,7 +138,7 @@ Plan make_plan(const mv_config* c)
     size_t off = 0;
     p.off_hist = off;     off += align_up((size_t)p.N * mvk::kHistBins * 4);
     p.off_tau = off;      off += align_up((size_t)p.N * 4);
-    p.off_rowcnt = off;   off += align_up((size_t)p.N * 4);
+    p.off_rowcnt = off;   off += align_up((size_t)p.N * mvk::kCounterStride * 4);
     p.off_slow = off;     off += align_up((size_t)p.N * 4);
     p.off_kth = off;      off += align_up((size_t)p.N * 4);
     p.off_tiecut = off;   off += align_up((size_t)p.N * 4);
@@ -422,7 +422,8 @@ mv_status enqueue_step(mv_ctx* c, const StepArgs& a, void* stream_v)
     if (p.multi_select) {
         // long candidate lists: histogram, split at the bin of the K-th largest, exact rank
         mvk::ListSelect ls;
-        ls.list = cand;  ls.cap = p.cap;  ls.count = rowcnt;  ls.base = tau;  ls.shift = mvk::kFineShift;
+        ls.list = cand;  ls.cap = p.cap;  ls.count = rowcnt;  ls.count_stride = mvk::kCounterStride;
+        ls.base = tau;  ls.shift = mvk::kFineShift;
         ls.want = p.K;
         ls.hist = ws_ptr<uint32_t>(c, p.off_selhist);
         ls.list2 = ws_ptr<mvk::u32x2>(c, p.off_sellist2);
@@ -492,7 +493,8 @@ mv_status enqueue_step(mv_ctx* c, const StepArgs& a, void* stream_v)
                            a.rand_exp, rslist, p.rs_cap, rscount);
         after(KID_RS_KEYS);
         mvk::ListSelect ls;
-        ls.list = rslist;  ls.cap = p.rs_cap;  ls.count = rscount;  ls.base = nullptr;  ls.shift = 20;
+        ls.list = rslist;  ls.cap = p.rs_cap;  ls.count = rscount;  ls.count_stride = 1;  ls.base = nullptr;
+        ls.shift = 20;
         ls.want = p.K;
         ls.hist = rshist;  ls.list2 = rslist2;  ls.count2 = rscount + 1;  ls.bin_want = rscount + 2;
         const dim3 grid((p.rs_cap + mvk::kListPerBlock - 1) / mvk::kListPerBlock);
@@ -683,7 +685,9 @@ mv_status mv_last_step_row_stats(mv_ctx* c, uint32_t* cand_count, uint32_t* thre
     if (!guard.ok) return MV_ERR_DEVICE;
     if (hipStreamSynchronize(c->last_stream) != hipSuccess) return MV_ERR_DEVICE;
     const size_t nb = (size_t)c->plan.N * 4;
-    if (cand_count && hipMemcpy(cand_count, c->ws + c->plan.off_rowcnt, nb, hipMemcpyDeviceToHost) != hipSuccess)
+    // the candidate counters lie one per cache line
+    if (cand_count && hipMemcpy2D(cand_count, 4, c->ws + c->plan.off_rowcnt, (size_t)mvk::kCounterStride * 4, 4,
+                                  c->plan.N, hipMemcpyDeviceToHost) != hipSuccess)
         return MV_ERR_DEVICE;
     if (threshold_bits && hipMemcpy(threshold_bits, c->ws + c->plan.off_tau, nb, hipMemcpyDeviceToHost) != hipSuccess)
         return MV_ERR_DEVICE;

@@ -199,9 +199,9 @@ __global__ __launch_bounds__(kSampleThreads) void mv_sample_hist(const GT* __res
     }
 }
 
-// The add-drop lists' length counters: many workgroups bump them with returning
-// atomics, which complete one after the other per cache line, so every counter has a
-// 128-byte line of its own.
+// List length counters (the rows' candidate lists, the add-drop lists): many workgroups
+// bump them with returning atomics, which complete one after the other per cache line,
+// so every counter has a 128-byte line of its own.
 constexpr uint32_t kCounterStride = 32;
 __device__ __forceinline__ uint32_t ad_counter(uint32_t row, uint32_t which)
 {
@@ -238,7 +238,7 @@ __global__ __launch_bounds__(kRowThreads) void mv_pick_threshold(uint32_t* __res
     }
     if (t == 0) {
         found = 0;
-        row_count[row] = 0;
+        row_count[row * kCounterStride] = 0;
         slow_flag[row] = 0;
     }
     if (t < 256) cnt_ge[(size_t)row * 256 + t] = 0;   // the row's 256 vote-level counters
@@ -355,7 +355,7 @@ __global__ __launch_bounds__(kStreamThreads) void mv_stream_collect(
             wave_total[w] = sum;
             sum += t;
         }
-        block_base = sum ? atomicAdd(&row_count[row], sum) : 0u;
+        block_base = sum ? atomicAdd(&row_count[row * kCounterStride], sum) : 0u;
     }
     __syncthreads();
     const uint32_t run_start = block_base + wave_total[wave];
@@ -766,7 +766,7 @@ __global__ __launch_bounds__(kRowThreads) void mv_row_select(
     __shared__ SelectLds lds;
     const uint32_t row = blockIdx.x, t = threadIdx.x;
     if (slow_rows_only) {                         // the candidate lists are selected by the mv_sel_* kernels
-        const uint32_t C0 = row_count[row];
+        const uint32_t C0 = row_count[row * kCounterStride];
         if (C0 >= K && C0 <= cap) return;         // whole workgroup
     }
     // The first kKeep * kRowThreads list entries are fetched before the row's
@@ -779,7 +779,7 @@ __global__ __launch_bounds__(kRowThreads) void mv_row_select(
         k[q] = crow[min((uint32_t)q * kRowThreads + t, cap - 1)].x;
         if ((q & 7) == 7) __builtin_amdgcn_sched_barrier(0);   // keep address arithmetic from piling up
     }
-    const uint32_t C = row_count[row];
+    const uint32_t C = row_count[row * kCounterStride];
 
     if (C >= K && C <= cap) {
         const uint32_t tau = tau_bits[row];
@@ -881,7 +881,7 @@ __global__ __launch_bounds__(kVoteThreads) void mv_row_votes(
     __shared__ uint32_t lvl[257];
     const uint32_t row = blockIdx.y, t = threadIdx.x;
     if (slow_flag[row] == 1u) return;                              // whole workgroup
-    const uint32_t C = row_count[row];
+    const uint32_t C = row_count[row * kCounterStride];
     if ((uint64_t)blockIdx.x * kVoteThreads >= C) return;    // whole workgroup
     for (int i = t; i < 257; i += kVoteThreads) lvl[i] = 0;
     __syncthreads();
@@ -1187,7 +1187,7 @@ __global__ __launch_bounds__(kVoteThreads) void mv_mask_emit(uint32_t* __restric
         const uint32_t b = blockIdx.x - n_vote_blocks;
         const uint32_t row = b / emit_blocks;
         if (slow_flag[row] == 1u) return;
-        row_emit_block(cand + (size_t)row * cap, row_count[row], seg + (size_t)row * nseg,
+        row_emit_block(cand + (size_t)row * cap, row_count[row * kCounterStride], seg + (size_t)row * nseg,
                        seg_pre + (size_t)row * nseg, blk_total + (size_t)row * scan_blocks, scan_blocks, K,
                        kth_in[row], tie_cut_in[row], b % emit_blocks, emit_blocks,
                        worker_idx + (size_t)row * K, blk_pre, scan_lds);
@@ -1364,7 +1364,7 @@ __device__ __forceinline__ void ad_collect_add_block(
         }
         return;
     }
-    const uint32_t C = row_count[row];
+    const uint32_t C = row_count[row * kCounterStride];
     const u32x2* crow = cand + (size_t)row * cap;
     for (uint64_t i0 = (uint64_t)bx * kVoteThreads; i0 < C; i0 += (uint64_t)nbx * kVoteThreads) {
         const uint64_t i = i0 + t;
@@ -1904,7 +1904,8 @@ constexpr int kListPerBlock = kRowThreads * kListPerThread;
 struct ListSelect {
     const u32x2* list;        // rows of `cap` entries
     uint32_t     cap;
-    const uint32_t* count;    // entries per row (clamped to cap)
+    const uint32_t* count;    // entries per row (clamped to cap), row r at count[r * count_stride]
+    uint32_t     count_stride;
     const uint32_t* base;     // per row, or null: 0
     uint32_t     shift;
     uint32_t     want;        // K
@@ -1921,7 +1922,7 @@ __device__ __forceinline__ uint32_t list_bin(uint32_t key, uint32_t base, uint32
 // a row takes part when its list holds at least `want` entries and did not overflow
 __device__ __forceinline__ bool list_row_ok(const ListSelect& a, uint32_t row, uint32_t& n)
 {
-    n = a.count[row];
+    n = a.count[row * a.count_stride];
     return n >= a.want && n <= a.cap;
 }
 
