@@ -6,20 +6,22 @@
 // contraction, so no MFMA; the design goal is ONE streaming pass over g and e.
 //
 // How the per-worker top-K is found without re-reading the row:
-//   1. mv_sample_pick     histogram of the magnitude bit patterns of a strided
-//                         sample of each row (cache-line sized chunks); the last
-//                         workgroup of a row turns it into a bin edge tau that
-//                         about 2K sampled-scaled coordinates exceed (an
-//                         ESTIMATE, never trusted)
+//   1. mv_sample_hist     histogram of the magnitude bit patterns of a strided
+//      mv_pick_threshold  sample of each row (cache-line sized chunks), turned
+//                         into a bin edge tau that about 2K coordinates of the
+//                         row exceed (an ESTIMATE, never trusted); also resets
+//                         the row's per-step counters
 //   2. mv_stream_collect  the streaming pass: a = g + e is written over e, and
 //                         every coordinate with |a| >= tau is appended to the
 //                         row's candidate list; each wavefront's 1024-coordinate
 //                         segment records where its run of candidates went
-//   3. mv_row_select      per row: EXACT radix select of the K-th largest
-//                         magnitude among the candidates (their number is known
-//                         exactly; if it is < K or overflowed the list, the row
-//                         is selected exactly from memory instead), and of the
-//                         largest coordinate taken among its ties
+//   3. mv_row_select      per row: EXACT select of the K-th largest magnitude
+//                         among the candidates (their number is known exactly;
+//                         if it is < K or overflowed the list, the row is
+//                         selected exactly from memory instead), and of the
+//                         largest coordinate taken among its ties.  Long lists
+//                         (large K) go through mv_sel_hist / mv_sel_split /
+//                         mv_sel_rank, many workgroups per row
 //   4. mv_row_votes       one thread per candidate: the taken ones cast their vote
 //   5. mv_mask_count /    counting-sort selection of the K most voted
 //      mv_mask_emit       coordinates, ties to the lowest coordinate.  Extra
@@ -29,6 +31,17 @@
 //                         critical path
 //   6. mv_gather_update   masked gather, sum over workers in order, mean, and
 //                         the error update (zero on the mask)
+//   7. mv_ad_*            majority voting with add-drop (Algorithm 2): replaces
+//                         step 4 by the update of the workers' standing votes
+//   8. mv_rs_*            majority voting with random selection (Algorithm 1,
+//                         S_rand-weighted): replaces the mask of step 5
+//
+// Two things measured on this machine shape much of the code: a returning
+// atomic completes only after the previous one on the same cache line (so
+// list space is reserved once per workgroup and hot counters sit on lines of
+// their own), and a load issued inside a divergent per-thread loop pays its
+// full latency every time (so sparse work is first compacted into LDS and then
+// fetched by all lanes together).
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -49,7 +62,7 @@ constexpr int      kHistBits       = 13;     // sample histogram: exponent + 5 m
 constexpr int      kHistBins       = 1 << kHistBits;
 constexpr int      kHistShift      = 31 - kHistBits;
 constexpr int      kChunk          = 32;     // sampled chunk: 32 coordinates (one 128-byte line of fp32)
-constexpr int      kRowThreads     = 1024;   // mv_pick_threshold / mv_row_finish: one workgroup per row
+constexpr int      kRowThreads     = 1024;   // mv_pick_threshold / mv_row_select: one workgroup per row
 constexpr int      kVoteBlock      = 16384;  // coordinates per workgroup in mv_mask_count / mv_mask_emit
 constexpr int      kVoteThreads    = 256;
 constexpr int      kGatherThreads  = 256;
