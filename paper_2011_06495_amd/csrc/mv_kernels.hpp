@@ -1818,7 +1818,6 @@ __global__ __launch_bounds__(kVoteThreads) void mv_ad_count_levels(const uint32_
 
 // Scan of the packed vote bytes (grid as for the mask kernels): every voted
 // coordinate is appended to the list with its key.  rs_count[0] = list length.
-constexpr int kRsStage = 4096;   // voted coordinates of one workgroup staged in LDS
 __device__ __forceinline__ u32x2 rs_entry(const float* __restrict__ rand_exp, uint32_t j, uint32_t v)
 {
     const float time = __fdiv_rn(rand_exp[j], (float)v);
@@ -1832,10 +1831,11 @@ __global__ __launch_bounds__(kVoteThreads) void mv_rs_keys(const uint32_t* __res
                                                            u32x2* __restrict__ list, uint32_t list_cap,
                                                            uint32_t* __restrict__ rs_count)
 {
-    __shared__ uint32_t stage[kRsStage];
+    constexpr int kIt = kVoteBlock / (kVoteThreads * 16);
+    constexpr int kPerIt = kVoteThreads * 16;                      // coordinates per round: all may hold a vote
+    __shared__ uint32_t stage[kPerIt];
     __shared__ uint64_t scan_lds[kVoteThreads / kWave + 1];
     __shared__ uint32_t base_sh;
-    constexpr int kIt = kVoteBlock / (kVoteThreads * 16);
     const int64_t base = (int64_t)blockIdx.x * kVoteBlock;
     u32x4 w[kIt];
     uint32_t n = 0;
@@ -1855,50 +1855,57 @@ __global__ __launch_bounds__(kVoteThreads) void mv_rs_keys(const uint32_t* __res
     const uint64_t ex = block_excl_scan64<kVoteThreads>(n, scan_lds, total);
     if (total == 0) return;                                        // whole workgroup
     if (threadIdx.x == 0) base_sh = atomicAdd(&rs_count[0], (uint32_t)total);
-    const bool staged = total <= (uint64_t)kRsStage;               // uniform
-    uint32_t pos = (uint32_t)ex;                                   // position among the workgroup's entries
-    if (n) {
+    if (total <= (uint64_t)kPerIt) {                               // uniform; usual case: one round for the whole block
+        uint32_t sp = (uint32_t)ex;
+        if (n) {
 #pragma unroll
-        for (int it = 0; it < kIt; ++it) {
-            if ((w[it].x | w[it].y | w[it].z | w[it].w) == 0u) continue;
-            const uint32_t off0 = ((uint32_t)it * kVoteThreads + threadIdx.x) * 16;   // offset in the block
-            const uint32_t ww[4] = {w[it].x, w[it].y, w[it].z, w[it].w};
-            for (int q = 0; q < 16; ++q) {
-                const uint32_t v = (ww[q >> 2] >> (8 * (q & 3))) & 255u;
-                if (v) {
-                    // usual case: park (offset, votes); the random numbers are then fetched
-                    // by all lanes together instead of one dependent load per entry here
-                    if (staged) stage[pos] = ((off0 + (uint32_t)q) << 8) | v;
-                    ++pos;
+            for (int it = 0; it < kIt; ++it) {
+                if ((w[it].x | w[it].y | w[it].z | w[it].w) == 0u) continue;
+                const uint32_t off0 = ((uint32_t)it * kVoteThreads + threadIdx.x) * 16;
+                const uint32_t ww[4] = {w[it].x, w[it].y, w[it].z, w[it].w};
+                for (int q = 0; q < 16; ++q) {
+                    const uint32_t v = (ww[q >> 2] >> (8 * (q & 3))) & 255u;
+                    if (v) stage[sp++] = ((off0 + (uint32_t)q) << 8) | v;
                 }
             }
         }
-    }
-    __syncthreads();
-    const uint32_t first = base_sh;
-    if (staged) {
+        __syncthreads();
+        const uint32_t at = base_sh;
         for (uint32_t i = threadIdx.x; i < (uint32_t)total; i += kVoteThreads) {
             const uint32_t s = stage[i];
-            if (first + i < list_cap) list[first + i] = rs_entry(rand_exp, (uint32_t)base + (s >> 8), s & 255u);
+            if (at + i < list_cap) list[at + i] = rs_entry(rand_exp, (uint32_t)base + (s >> 8), s & 255u);
         }
         return;
     }
-    // a block dense with votes: entry by entry
-    pos = first + (uint32_t)ex;
-    if (n) {
+    __syncthreads();
+    uint32_t first = base_sh;                                      // list position of the round's first entry
+    // A block crowded with votes (the mask concentrates in few tensors), round by round of
+    // 4096 coordinates.  Either way the voted coordinates are parked in LDS as (offset,
+    // votes) and their random numbers then fetched by all lanes together: one dependent load
+    // per entry inside each thread's own loop made this kernel 2.5x slower, and 8x slower
+    // on crowded blocks.
 #pragma unroll
-        for (int it = 0; it < kIt; ++it) {
-            if ((w[it].x | w[it].y | w[it].z | w[it].w) == 0u) continue;
-            const int64_t j0 = base + ((int64_t)it * kVoteThreads + threadIdx.x) * 16;
-            const uint32_t ww[4] = {w[it].x, w[it].y, w[it].z, w[it].w};
+    for (int it = 0; it < kIt; ++it) {
+        const uint32_t ww[4] = {w[it].x, w[it].y, w[it].z, w[it].w};
+        uint32_t n_it = 0;
+#pragma unroll
+        for (int q = 0; q < 16; ++q) n_it += ((ww[q >> 2] >> (8 * (q & 3))) & 255u) != 0u;
+        uint64_t round_total;
+        uint32_t sp = (uint32_t)block_excl_scan64<kVoteThreads>(n_it, scan_lds, round_total);
+        if (n_it) {
+            const uint32_t off0 = ((uint32_t)it * kVoteThreads + threadIdx.x) * 16;   // offset in the block
             for (int q = 0; q < 16; ++q) {
                 const uint32_t v = (ww[q >> 2] >> (8 * (q & 3))) & 255u;
-                if (v) {
-                    if (pos < list_cap) list[pos] = rs_entry(rand_exp, (uint32_t)(j0 + q), v);
-                    ++pos;
-                }
+                if (v) stage[sp++] = ((off0 + (uint32_t)q) << 8) | v;
             }
         }
+        __syncthreads();
+        for (uint32_t i = threadIdx.x; i < (uint32_t)round_total; i += kVoteThreads) {
+            const uint32_t s = stage[i];
+            if (first + i < list_cap) list[first + i] = rs_entry(rand_exp, (uint32_t)base + (s >> 8), s & 255u);
+        }
+        first += (uint32_t)round_total;
+        __syncthreads();
     }
 }
 
