@@ -1395,7 +1395,7 @@ __device__ __forceinline__ void ad_collect_add_block(
 // D-lists: the standing vote's bitmap is scanned, 4 words per thread; a set
 // coordinate that is not in the row's top-K goes to the list with the
 // complemented magnitude, so that "largest first" selects the smallest magnitudes.
-constexpr int kDropStage = 4096;   // set bits of one workgroup's stretch staged in LDS
+constexpr int kDropStage = 1024;   // set bits of one workgroup's stretch staged in LDS per round
 constexpr int kBitIt = 1;          // quads of bitmap words per thread in the bitmap kernels (more per thread measured no faster)
 constexpr int kBitBlockWords = kVoteThreads * 4 * kBitIt;   // bitmap words per workgroup
 __device__ __forceinline__ void ad_collect_drop_block(
@@ -1431,10 +1431,10 @@ __device__ __forceinline__ void ad_collect_drop_block(
     const uint64_t ex = block_excl_scan64<kVoteThreads>(n_bits, scan_lds, total);
     if (total == 0) return;                                  // whole workgroup
     u32x2* drow = d_list + (size_t)row * cap_d;
-    if (total <= (uint64_t)kDropStage) {                     // uniform
-        // Usual case (few members of the standing vote in this stretch): their coordinates
-        // are parked in LDS and the values then fetched by all lanes together, instead of
-        // one dependent load per set bit inside each thread's own loop.
+    // The members' coordinates are parked in LDS (kDropStage at a time; one round unless the
+    // stretch is crowded with votes) and their values then fetched by all lanes together,
+    // instead of one dependent load per set bit inside each thread's own loop.
+    auto one_round = [&](const uint32_t c0) {
         uint32_t sp = (uint32_t)ex;
 #pragma unroll
         for (int it = 0; it < kBitIt; ++it) {
@@ -1445,18 +1445,20 @@ __device__ __forceinline__ void ad_collect_drop_block(
                 while (m) {
                     const uint32_t b = __ffs((int)m) - 1;
                     m &= m - 1;
-                    stage[sp++] = (w0 + q) * 32 + b;
+                    if (sp - c0 < (uint32_t)kDropStage) stage[sp - c0] = (w0 + q) * 32 + b;   // sp < c0 wraps: not staged
+                    ++sp;
                 }
             }
         }
         __syncthreads();
+        const uint32_t cnt = min((uint32_t)kDropStage, (uint32_t)total - c0);
         constexpr int kRounds = kDropStage / kVoteThreads;
         u32x2 c[kRounds];
         uint32_t n_keep = 0, keep = 0;
 #pragma unroll
         for (int r = 0; r < kRounds; ++r) {
             const uint32_t i = (uint32_t)r * kVoteThreads + t;
-            if (i < (uint32_t)total) {
+            if (i < cnt) {
                 const uint32_t j = stage[i];
                 c[r].x = __float_as_uint(xrow[j]) & kAbsMask;
                 c[r].y = j;
@@ -1479,48 +1481,11 @@ __device__ __forceinline__ void ad_collect_drop_block(
                 ++pos;
             }
         }
-        return;
-    }
-    __syncthreads();                                         // scan_lds is reused below
-    // a stretch dense with votes: bit by bit
-    uint32_t n_mine = 0;
-#pragma unroll
-    for (int it = 0; it < kBitIt; ++it) {
-        const uint32_t w0 = bx * kBitBlockWords + ((uint32_t)it * kVoteThreads + t) * 4;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            uint32_t m = w[it][q];
-            while (m) {
-                const uint32_t b = __ffs((int)m) - 1;
-                m &= m - 1;
-                u32x2 c;
-                c.y = (w0 + q) * 32 + b;
-                c.x = __float_as_uint(xrow[c.y]) & kAbsMask;
-                if (is_taken(c, kth, tie_cut)) w[it][q] &= ~(1u << b);   // stays in the vote: not a drop candidate
-            }
-            n_mine += __popc(w[it][q]);
-        }
-    }
-    uint32_t pos = reserve_in_list(n_mine, ad_count + ad_counter(row, 1), scan_lds, bcast);
-#pragma unroll
-    for (int it = 0; it < kBitIt; ++it) {
-        const uint32_t w0 = bx * kBitBlockWords + ((uint32_t)it * kVoteThreads + t) * 4;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            uint32_t m = w[it][q];
-            while (m) {
-                const uint32_t b = __ffs((int)m) - 1;
-                m &= m - 1;
-                const uint32_t j = (w0 + q) * 32 + b;
-                if (pos < cap_d) {
-                    u32x2 c;
-                    c.x = kAbsMask - (__float_as_uint(xrow[j]) & kAbsMask);
-                    c.y = j;
-                    drow[pos] = c;
-                }
-                ++pos;
-            }
-        }
+    };
+    if (total <= (uint64_t)kDropStage) {                     // uniform; the usual case
+        one_round(0u);
+    } else {
+        for (uint32_t c0 = 0; c0 < (uint32_t)total; c0 += kDropStage) one_round(c0);
     }
 }
 
