@@ -717,6 +717,38 @@ __device__ __forceinline__ void select_among_candidates(const Keys& keys, const 
             tie_cut = lds.bcast[1];
             return;
         }
+        if (in_bin <= (uint32_t)kKeyBins) {       // uniform
+            // A crowded bin that still fits in LDS.  Values on a lattice put hundreds of
+            // EQUAL magnitudes there: if all members share one key, that key is the K-th
+            // largest and only the tie cut is left to find, among coordinates already in LDS.
+            if (t < 2) lds.bcast[t] = t ? 0xFFFFFFFFu : 0u;          // max, min of the members' keys
+            keys.each([&](uint32_t k, uint64_t i, bool valid) {
+                if (valid && fine_bin(k, tau) == bin) {
+                    const uint32_t p = atomicAdd(&lds.n_list, 1u);
+                    lds.hist[p] = k;
+                    lds.ties[p] = crow[i].y;
+                }
+            });
+            __syncthreads();
+            for (uint32_t i = t; i < in_bin; i += kRowThreads) {
+                const uint32_t k = lds.hist[i];
+                if (k != lds.hist[0]) {                              // any writer will do: both end up != hist[0]
+                    atomicMax(&lds.bcast[0], k);
+                    atomicMin(&lds.bcast[1], k);
+                }
+            }
+            __syncthreads();
+            const bool one_key = lds.bcast[0] == 0u && lds.bcast[1] == 0xFFFFFFFFu;   // nobody differed from hist[0]
+            const uint32_t the_key = lds.hist[0];
+            __syncthreads();
+            if (one_key) {                                           // uniform
+                kth = the_key;
+                tie_cut = want < in_bin ? smallest_coordinate(lds, in_bin, want) : 0xFFFFFFFFu;
+                return;
+            }
+            if (t == 0) lds.n_list = 0;                              // distinct keys: go on below
+            __syncthreads();
+        }
         if (bin < (uint32_t)(kFineBins - 1)) {
             // a crowded bin (many equal magnitudes): it spans exactly 4096 key values,
             // so a second histogram over the exact keys inside it finds the K-th largest
