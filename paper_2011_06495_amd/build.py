@@ -9,7 +9,8 @@ CSRC = os.path.join(_HERE, "csrc")
 LIB_PATH = os.path.join(_HERE, "libmv.so")
 SOURCES = [os.path.join(CSRC, "mv_api.hip"), os.path.join(CSRC, "mv_codec.hip"),
            os.path.join(CSRC, "mv_quant.hip")]
-HEADERS = [os.path.join(CSRC, "mv_kernels.hpp"),
+HEADERS = [os.path.join(CSRC, h) for h in ("mv_kernels.hpp", "mv_common.hpp", "mv_stream.hpp", "mv_select.hpp",
+                                               "mv_mask.hpp", "mv_add_drop.hpp", "mv_random_select.hpp")] + [
            os.path.join(os.path.dirname(_HERE), "include", "mv.h")]
 
 HIPCC_FLAGS = [
