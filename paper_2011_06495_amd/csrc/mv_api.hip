@@ -131,8 +131,16 @@ Plan make_plan(const mv_config* c)
     p.cap = (uint32_t)cap;
 
     p.n_vote_blocks = (uint32_t)((p.d + mvk::kVoteBlock - 1) / mvk::kVoteBlock);
-    p.emit_blocks = (p.cap + mvk::kVoteThreads - 1) / mvk::kVoteThreads;
-    if (p.emit_blocks > 256) p.emit_blocks = 256;
+    // about 2K candidates per row are expected: one thread per candidate with some room, the kernels
+    // stride over whatever is there
+    {
+        uint64_t eb = (3ull * p.K + mvk::kVoteThreads - 1) / mvk::kVoteThreads;
+        const uint64_t eb_cap = ((uint64_t)p.cap + mvk::kVoteThreads - 1) / mvk::kVoteThreads;
+        if (eb > eb_cap) eb = eb_cap;
+        if (eb > 256) eb = 256;      // more workgroups than this only crowd the atomics (measured at K = 111,740)
+        if (eb < 1) eb = 1;
+        p.emit_blocks = (uint32_t)eb;
+    }
     p.scan_blocks = (p.nseg + 1023) / 1024;
 
     size_t off = 0;

@@ -78,6 +78,7 @@ __device__ __forceinline__ void find_rank_bin(const uint32_t* hist, uint64_t* sc
 // operations); i is the key's position in the source, valid says whether it
 // exists.
 struct KeysInRegs {                     // thread t holds key number q * kRowThreads + t in k[q]
+    static constexpr bool kCheapPasses = true;
     const uint32_t (&k)[kKeep];
     uint32_t count;
     template <typename F>
@@ -94,6 +95,7 @@ struct KeysInRegs {                     // thread t holds key number q * kRowThr
 };
 template <typename KeyAt>
 struct KeysInMemory {                   // re-read on every pass
+    static constexpr bool kCheapPasses = false;
     KeyAt    key_at;
     uint64_t count;
     template <typename F>
@@ -326,7 +328,7 @@ __device__ __forceinline__ void select_among_candidates(const Keys& keys, const 
             tie_cut = lds.bcast[1];
             return;
         }
-        if (in_bin <= (uint32_t)kKeyBins) {       // uniform
+        if (Keys::kCheapPasses && in_bin <= (uint32_t)kKeyBins) {   // uniform; an extra pass only where passes are cheap
             // A crowded bin that still fits in LDS.  Values on a lattice put hundreds of
             // EQUAL magnitudes there: if all members share one key, that key is the K-th
             // largest and only the tie cut is left to find, among coordinates already in LDS.
