@@ -21,13 +21,17 @@ __global__ __launch_bounds__(kVoteThreads) void mv_row_votes(
 {
     __shared__ uint32_t lvl[257];
     const uint32_t row = blockIdx.y, t = threadIdx.x;
+    // the thread's first list entry is fetched together with the row's counters, not after
+    // them (the list's storage holds cap entries; an entry at or beyond the count is ignored)
+    const u32x2* crow = cand + (size_t)row * cap;
+    const uint64_t i_first = (uint64_t)blockIdx.x * kVoteThreads + t;
+    const u32x2 c_first = crow[min(i_first, (uint64_t)cap - 1)];
+    const uint32_t kth = kth_in[row], tie_cut = tie_cut_in[row];
     if (slow_flag[row] == 1u) return;                              // whole workgroup
     const uint32_t C = row_count[row * kCounterStride];
     if ((uint64_t)blockIdx.x * kVoteThreads >= C) return;    // whole workgroup
     for (int i = t; i < 257; i += kVoteThreads) lvl[i] = 0;
     __syncthreads();
-    const uint32_t kth = kth_in[row], tie_cut = tie_cut_in[row];
-    const u32x2* crow = cand + (size_t)row * cap;
     uint32_t*    ssel = seg_sel ? seg_sel + (size_t)row * nseg : nullptr;
     const uint32_t lane = lane_id();
     for (uint64_t i0 = (uint64_t)blockIdx.x * kVoteThreads; i0 < C; i0 += (uint64_t)gridDim.x * kVoteThreads) {
@@ -35,7 +39,7 @@ __global__ __launch_bounds__(kVoteThreads) void mv_row_votes(
         u32x2 c = {0u, 0xFFFFFFFFu};
         bool taken = false;
         if (i < C) {
-            c = crow[i];
+            c = (i == i_first) ? c_first : crow[i];
             taken = is_taken(c, kth, tie_cut);
         }
         if (taken) cast_vote(votes32, c.y, lvl);
