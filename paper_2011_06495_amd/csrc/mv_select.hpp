@@ -438,9 +438,9 @@ __global__ __launch_bounds__(kRowThreads) void mv_row_select(
         if ((q & 7) == 7) __builtin_amdgcn_sched_barrier(0);   // keep address arithmetic from piling up
     }
     const uint32_t C = row_count[row * kCounterStride];
+    const uint32_t tau = tau_bits[row];           // with the count, not after it
 
     if (C >= K && C <= cap) {
-        const uint32_t tau = tau_bits[row];
         uint32_t kth, tie_cut, path;
         if (C <= (uint32_t)kKeep * kRowThreads) {
             const KeysInRegs src{k, C};
