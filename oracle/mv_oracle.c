@@ -24,7 +24,7 @@
  *     selection and for the selection over vote counts.  The paper does not
  *     fix a tie rule: the tie-break is "parity unpinned" by the paper and
  *     pinned only by this build's contract.
- *   - "highest absolute value" is the order of the fp32 bit pattern with the
+ *   - the order by magnitude (Sec. 2, S_top) is the order of the fp32 bit pattern with the
  *     sign bit cleared: -0 == +0, denormals are ordered (not flushed), +Inf is
  *     above every finite value, NaNs above Inf by payload.
  *   - The aggregate is a mean (Sec. 2, definition of G-tilde and the linearity
@@ -133,7 +133,7 @@ int mvo_row_topk(const float* delta_bar, int64_t d, int64_t K, uint32_t* idx_out
     return rc;
 }
 
-/* Sec. 2, "the PS counts the votes for all the positions":
+/* Sec. 2, the server tallies the supports it receives:
  * votes = sum over workers of the 0/1 local masks. */
 int mvo_votes(const uint32_t* worker_idx, int32_t N, int64_t K, int64_t d, uint8_t* votes)
 {
@@ -419,8 +419,8 @@ int mvo_rs_vote_step(const void* grads, int64_t ld_g, int32_t grad_is_bf16,
  *     among D = supp(M~_{n,t-1}) \ supp(M_n) (Sec. 3, second paragraph).  The
  *     printed formulas apply S_top / S_bot to a vector that is zero outside A
  *     (resp. D); read literally they would pick coordinates outside the set
- *     when the set has fewer than K_ad members.  Sec. 3 says "at most K_ad"
- *     indices are added / removed, so: add = the min(K_ad, |A|) members of A
+ *     when the set has fewer than K_ad members.  Sec. 3 bounds the additions
+ *     and the removals by K_ad each, so: add = the min(K_ad, |A|) members of A
  *     with the largest |Delta-bar|, drop = the min(K_ad, |D|) members of D with
  *     the smallest |Delta-bar|.
  *   - Ties: add under (magnitude desc, index asc); drop under (magnitude asc,
