@@ -279,7 +279,7 @@ int mvo_vote_step(const void* grads, int64_t ld_g, int32_t grad_is_bf16,
 /*
  * Sec. 2 (the paragraph after Algorithm 1): the winning positions are sampled
  * with probabilities proportional to the received votes; Sec. 4.2: indices are
- * selected at random "using the votes" until K distinct ones are selected.
+ * selected at random, guided by the votes, until K distinct ones are selected.
  *
  * Reading (the paper names no sampler and no random generator): positions are
  * drawn one at a time, each draw independent with P(j) = votes[j] / sum(votes),
