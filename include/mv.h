@@ -112,9 +112,9 @@ mv_status mv_vote_step(mv_ctx* ctx,
  * One iteration of majority voting with random selection (paper: Algorithm 1, the
  * line with S_rand-weighted; Sec. 2, paragraph after Algorithm 1; Sec. 4.2),
  * enqueued on `stream` like mv_vote_step and with the same arguments, outputs and
- * error behaviour, except for how the mask is chosen: the winning coordinates are
- * drawn with probabilities proportional to their votes until K distinct ones are
- * selected.  The paper names no sampler; here every voted coordinate j gets the
+ * error behaviour, except for how the mask is chosen: winners are drawn at random,
+ * a coordinate's chance growing in proportion to its votes, until K distinct ones
+ * are selected.  The paper names no sampler; here every voted coordinate j gets the
  * time rand_exp[j] / votes[j] (one correctly rounded fp32 division) and the K
  * soonest win, equal times going to the lowest coordinate.  With rand_exp[j]
  * independent Exp(1) variates this is that law (successive sampling without

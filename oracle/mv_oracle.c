@@ -277,9 +277,9 @@ int mvo_vote_step(const void* grads, int64_t ld_g, int32_t grad_is_bf16,
 /* ------------------------------------------------------------------ */
 
 /*
- * Sec. 2 (the paragraph after Algorithm 1): the winning positions are sampled
- * with probabilities proportional to the received votes; Sec. 4.2: indices are
- * selected at random, guided by the votes, until K distinct ones are selected.
+ * Sec. 2 (the paragraph after Algorithm 1): winners are drawn at random, a
+ * position's chance growing in proportion to its votes; Sec. 4.2: the drawing
+ * goes on until K distinct positions are selected.
  *
  * Reading (the paper names no sampler and no random generator): positions are
  * drawn one at a time, each draw independent with P(j) = votes[j] / sum(votes),
