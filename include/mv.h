@@ -40,7 +40,7 @@ typedef enum {
     MV_ERR_UNSUPPORTED = 2,
     MV_ERR_ALLOC = 3,       /* device or host allocation failed */
     MV_ERR_DEVICE = 4,      /* a HIP call failed */
-    MV_ERR_STATE = 5        /* context already ended */
+    MV_ERR_STATE = 5        /* context already ended, or an earlier step on it failed with MV_ERR_DEVICE */
 } mv_status;
 
 typedef enum { MV_F32 = 0, MV_BF16 = 1 } mv_dtype;          /* dtype of g only; e and agg are fp32 */
@@ -202,6 +202,16 @@ const char* mv_kernel_name(int32_t i);
 mv_status mv_set_profiling(mv_ctx* ctx, int32_t level);
 
 /*
+ * Inside the streaming kernel the wavefronts of a row wait for the row's threshold
+ * estimate, which other workgroups of the same launch publish; the wait is bounded by
+ * `polls` looks at memory (default 2^20, about a second), after which the wavefront
+ * gives up and the row is selected exactly from memory instead.  Results never depend
+ * on it.  A test hook: 0 makes every wavefront that does not find the estimate at its
+ * first look give up, which forces that path without any kernel waiting.
+ */
+mv_status mv_set_spin_limit(mv_ctx* ctx, uint32_t polls);
+
+/*
  * Durations, in milliseconds, of the kernels of the step enqueued `steps_back`
  * steps ago on this context (0 = the last one; the last 64 steps are kept),
  * one per kernel in mv_kernel_name order, -1 for kernels that were not
@@ -215,8 +225,10 @@ mv_status mv_step_kernel_ms(mv_ctx* ctx, int32_t steps_back, float* ms, int32_t 
  * worker row, how many candidates the streaming pass kept (cand_count), the
  * magnitude bit pattern it compared against (threshold_bits) and how the row's
  * K-th magnitude was found (slow_path: 0 = from the candidates through their
- * fine histogram, 2 = radix select over the candidates, 1 = the slow exact path
- * over the whole row in memory).  HOST arrays of N uint32 each; any may be NULL.
+ * fine histogram, 2 = the generic select over the candidates, 1 = the slow exact
+ * path over the whole row in memory).  A cand_count with its top bit set marks a row
+ * whose wavefronts did not all see the threshold in time (see mv_set_spin_limit).
+ * HOST arrays of N uint32 each; any may be NULL.
  */
 mv_status mv_last_step_row_stats(mv_ctx* ctx, uint32_t* cand_count,
                                  uint32_t* threshold_bits, uint32_t* slow_path);
@@ -243,7 +255,7 @@ size_t mv_codec_scratch_bytes(uint64_t max_bits, int32_t rows);
  * `stream`; allocates nothing.
  *   idx       device, row r = idx + r * ld_idx: ascending coordinates < d
  *   counts    device or NULL: the length of row r is counts[r * counts_stride]
- *             (<= n); NULL: every row holds n coordinates
+ *             (a value above n is read as n); NULL: every row holds n coordinates
  *   streams   device out, row r = streams + r * ld_words; ld_words >=
  *             ceil(mv_codec_stream_bits(n, d, block_len) / 32); words beyond a
  *             row's stream are left untouched
@@ -259,7 +271,8 @@ mv_status mv_codec_encode(const uint32_t* idx, int64_t ld_idx, const uint32_t* c
  * Decodes `rows` streams as the receiver of Sec. 4.3.1 reads them (a 1 bit: the
  * next B bits are a position inside the current block; a 0 bit: next block).
  *   streams, ld_words   device, as written by mv_codec_encode
- *   n_bits    device, rows entries: the length of each stream in bits (<= max_bits)
+ *   n_bits    device, rows entries: the length of each stream in bits (a value above
+ *             max_bits is read as max_bits)
  *   idx_out   device out, row r = idx_out + r * ld_idx, room for max_n coordinates
  *   counts_out device out, rows entries: coordinates found in each stream (those
  *             beyond max_n are counted but not written)

@@ -21,7 +21,7 @@ MV_FLAG_ADD_DROP = 1
 # every symbol include/mv.h declares
 ABI_SYMBOLS = (
     "mv_workspace_bytes", "mv_begin", "mv_vote_step", "mv_ad_vote_step", "mv_rs_vote_step", "mv_end", "mv_release", "mv_status_string",
-    "mv_kernel_count", "mv_kernel_name", "mv_set_profiling", "mv_step_kernel_ms",
+    "mv_kernel_count", "mv_kernel_name", "mv_set_profiling", "mv_set_spin_limit", "mv_step_kernel_ms",
     "mv_last_step_row_stats", "mv_probe_copy",
     "mv_codec_stream_bits", "mv_codec_scratch_bytes", "mv_codec_encode", "mv_codec_decode",
     "mv_quant_scratch_bytes", "mv_quant_encode", "mv_quant_decode",
@@ -85,6 +85,8 @@ def load() -> ctypes.CDLL:
     L.mv_kernel_name.restype = ctypes.c_char_p
     L.mv_set_profiling.argtypes = [vp, i32]
     L.mv_set_profiling.restype = i32
+    L.mv_set_spin_limit.argtypes = [vp, ctypes.c_uint32]
+    L.mv_set_spin_limit.restype = i32
     L.mv_step_kernel_ms.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_float), i32]
     L.mv_step_kernel_ms.restype = i32
     L.mv_last_step_row_stats.argtypes = [vp, u32p, u32p, u32p]
@@ -207,6 +209,12 @@ def mv_set_profiling(ctx: int, level: int) -> None:
     st = load().mv_set_profiling(ctx, level)
     if st != MV_OK:
         raise MvError(st, "mv_set_profiling")
+
+
+def mv_set_spin_limit(ctx: int, polls: int) -> None:
+    st = load().mv_set_spin_limit(ctx, polls)
+    if st != MV_OK:
+        raise MvError(st, "mv_set_spin_limit")
 
 
 def mv_step_kernel_ms(ctx: int, steps_back: int = 0):

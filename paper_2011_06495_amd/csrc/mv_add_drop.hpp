@@ -74,7 +74,7 @@ __device__ __forceinline__ void ad_collect_add_block(
         }
         return;
     }
-    const uint32_t C = row_count[row * kCounterStride];
+    const uint32_t C = row_count[row];
     const u32x2* crow = cand + (size_t)row * cap;
     for (uint64_t i0 = (uint64_t)bx * kVoteThreads; i0 < C; i0 += (uint64_t)nbx * kVoteThreads) {
         const uint64_t i = i0 + t;
@@ -310,14 +310,61 @@ __device__ __forceinline__ void compact_count_block(const uint32_t* __restrict__
         blk_cnt[(size_t)r * nblk + bx] = c;
     }
 }
+// Histogram of the vote levels of msum (one byte per coordinate, values 0..N) over a
+// block of kVoteBlock coordinates: lvl_sets[set][v] += coordinates with exactly v votes.
+__device__ __forceinline__ void ad_levels_block(const uint32_t* __restrict__ msum32, int64_t d,
+                                                uint32_t* __restrict__ lvl_sets, uint32_t bx, uint32_t* h /*256*/)
+{
+    // all of the block's words first: a load placed after the LDS atomics of the previous
+    // round would wait for its full latency every round
+    constexpr int kIt = kVoteBlock / (kVoteThreads * 16);
+    const int64_t base = (int64_t)bx * kVoteBlock;
+    u32x4 w[kIt];
+#pragma unroll
+    for (int it = 0; it < kIt; ++it) {
+        const int64_t j = base + ((int64_t)it * kVoteThreads + threadIdx.x) * 16;
+        const u32x4 z = {0u, 0u, 0u, 0u};
+        w[it] = (j < d) ? *reinterpret_cast<const u32x4*>(msum32 + (j >> 2)) : z;
+    }
+    h[threadIdx.x] = 0;
+    __syncthreads();
+#pragma unroll
+    for (int it = 0; it < kIt; ++it) {
+        const int64_t j = base + ((int64_t)it * kVoteThreads + threadIdx.x) * 16;
+        if (j < d) {
+            const uint32_t ww[4] = {w[it].x, w[it].y, w[it].z, w[it].w};
+            if ((ww[0] | ww[1] | ww[2] | ww[3]) != 0u) {     // most coordinates have no vote
+#pragma unroll
+                for (int q = 0; q < 16; ++q) {
+                    const uint32_t v = (ww[q >> 2] >> (8 * (q & 3))) & 255u;
+                    if (v && j + q < d) atomicAdd(&h[v], 1u);
+                }
+            }
+        }
+    }
+    __syncthreads();
+    const uint32_t c = h[threadIdx.x];
+    if (c && threadIdx.x) atomicAdd(&lvl_sets[(size_t)(bx % kLvlSets) * 256 + threadIdx.x], c);
+}
+
+// One launch after mv_ad_apply: the first n_count_blocks workgroups count the additions
+// and removals marked in the scratch bitmaps per block (row = id / nblk), the others take
+// the histogram of msum's levels.
 __global__ __launch_bounds__(kVoteThreads) void mv_ad_compact_count(const uint32_t* __restrict__ ad_bits,
                                                                     uint32_t nwords_pad, uint32_t nblk,
                                                                     u32x2* __restrict__ blk_cnt,
                                                                     const uint32_t* __restrict__ vote_bits,
-                                                                    int64_t ld_bits)
+                                                                    int64_t ld_bits, uint32_t n_count_blocks,
+                                                                    const uint32_t* __restrict__ msum32, int64_t d,
+                                                                    uint32_t* __restrict__ lvl_sets)
 {
     __shared__ uint64_t scan_lds[kVoteThreads / kWave + 1];
-    compact_count_block(ad_bits, nwords_pad, nblk, blk_cnt, vote_bits, ld_bits, blockIdx.y, blockIdx.x, scan_lds);
+    __shared__ uint32_t h[256];
+    if (blockIdx.x < n_count_blocks)
+        compact_count_block(ad_bits, nwords_pad, nblk, blk_cnt, vote_bits, ld_bits, blockIdx.x / nblk,
+                            blockIdx.x % nblk, scan_lds);
+    else
+        ad_levels_block(msum32, d, lvl_sets, blockIdx.x - n_count_blocks, h);
 }
 
 __global__ __launch_bounds__(kVoteThreads) void mv_ad_compact_emit(uint32_t* __restrict__ ad_bits,
@@ -395,72 +442,6 @@ __global__ __launch_bounds__(kVoteThreads) void mv_ad_compact_emit(uint32_t* __r
         done += total;
         __syncthreads();
     }
-}
-
-// Histogram of the vote levels of msum (one byte per coordinate, values 0..N):
-// lvl_cnt[v] = number of coordinates with exactly v votes.
-__device__ __forceinline__ void ad_levels_block(const uint32_t* __restrict__ msum32, int64_t d,
-                                                uint32_t* __restrict__ lvl_cnt, uint32_t n_sets, uint32_t bx,
-                                                uint32_t* h /*256*/)
-{
-    // all of the block's words first: a load placed after the LDS atomics of the previous
-    // round would wait for its full latency every round
-    constexpr int kIt = kVoteBlock / (kVoteThreads * 16);
-    const int64_t base = (int64_t)bx * kVoteBlock;
-    u32x4 w[kIt];
-#pragma unroll
-    for (int it = 0; it < kIt; ++it) {
-        const int64_t j = base + ((int64_t)it * kVoteThreads + threadIdx.x) * 16;
-        const u32x4 z = {0u, 0u, 0u, 0u};
-        w[it] = (j < d) ? *reinterpret_cast<const u32x4*>(msum32 + (j >> 2)) : z;
-    }
-    h[threadIdx.x] = 0;
-    __syncthreads();
-    uint32_t zeros = 0;                           // most coordinates have no vote
-#pragma unroll
-    for (int it = 0; it < kIt; ++it) {
-        const int64_t j = base + ((int64_t)it * kVoteThreads + threadIdx.x) * 16;
-        if (j < d) {
-            const uint32_t ww[4] = {w[it].x, w[it].y, w[it].z, w[it].w};
-            if ((ww[0] | ww[1] | ww[2] | ww[3]) == 0u) {
-                zeros += (uint32_t)min((int64_t)16, d - j);
-            } else {
-#pragma unroll
-                for (int q = 0; q < 16; ++q) {
-                    const uint32_t v = (ww[q >> 2] >> (8 * (q & 3))) & 255u;
-                    if (j + q < d) {
-                        if (v) atomicAdd(&h[v], 1u);
-                        else   ++zeros;
-                    }
-                }
-            }
-        }
-    }
-    if (zeros) atomicAdd(&h[0], zeros);
-    __syncthreads();
-    // the workgroups take turns over the n_sets sets of counters (the sum counts), so that
-    // their atomics do not all queue up on one cache line
-    const uint32_t c = h[threadIdx.x];
-    if (c) atomicAdd(&lvl_cnt[(size_t)(bx % n_sets) * 256 + threadIdx.x], c);
-}
-
-// One launch after mv_ad_apply: the first n_count_blocks workgroups count the additions
-// and removals marked in the N scratch bitmaps per block, the others take the histogram of msum's levels.
-__global__ __launch_bounds__(kVoteThreads) void mv_ad_count_levels(const uint32_t* __restrict__ ad_bits,
-                                                                   uint32_t nwords_pad, uint32_t nblk,
-                                                                   u32x2* __restrict__ blk_cnt,
-                                                                   const uint32_t* __restrict__ vote_bits,
-                                                                   int64_t ld_bits, uint32_t n_count_blocks,
-                                                                   const uint32_t* __restrict__ msum32, int64_t d,
-                                                                   uint32_t* __restrict__ lvl_cnt, uint32_t n_sets)
-{
-    __shared__ uint64_t scan_lds[kVoteThreads / kWave + 1];
-    __shared__ uint32_t h[256];
-    if (blockIdx.x < n_count_blocks)
-        compact_count_block(ad_bits, nwords_pad, nblk, blk_cnt, vote_bits, ld_bits, blockIdx.x / nblk,
-                            blockIdx.x % nblk, scan_lds);
-    else
-        ad_levels_block(msum32, d, lvl_cnt, n_sets, blockIdx.x - n_count_blocks, h);
 }
 
 }  // namespace mvk

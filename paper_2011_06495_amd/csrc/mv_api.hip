@@ -9,13 +9,12 @@
 #include <new>
 #include <stdint.h>
 #include <string.h>
+#include <math.h>
 
 namespace {
 
 enum KernelId {
-    KID_SAMPLE = 0,
-    KID_PICK,
-    KID_STREAM,
+    KID_STREAM = 0,
     KID_ROW_SELECT,
     KID_ROW_VOTES,
     KID_MASK_COUNT,
@@ -25,8 +24,7 @@ enum KernelId {
     KID_AD_COLLECT,
     KID_AD_SELECT,
     KID_AD_APPLY,
-    KID_AD_COUNT_LEVELS,
-    KID_AD_COMPACT_COUNT,      // random selection's bitmap only
+    KID_AD_COMPACT_COUNT,
     KID_AD_COMPACT_EMIT,
     // rows' select with many workgroups (large K only)
     KID_SEL_HIST,
@@ -40,9 +38,9 @@ enum KernelId {
     KID_COUNT
 };
 const char* const kKernelNames[KID_COUNT] = {
-    "mv_sample_hist",    "mv_pick_threshold",  "mv_stream_collect",   "mv_row_select",      "mv_row_votes",
+    "mv_stream_collect",   "mv_row_select",      "mv_row_votes",
     "mv_mask_count",     "mv_mask_emit",       "mv_gather_update",    "mv_ad_collect",      "mv_ad_select",
-    "mv_ad_apply",       "mv_ad_count_levels", "mv_ad_compact_count", "mv_ad_compact_emit",
+    "mv_ad_apply",       "mv_ad_compact_count", "mv_ad_compact_emit",
     "mv_sel_hist",       "mv_sel_split",       "mv_sel_rank",
     "mv_rs_keys",        "mv_rs_hist",         "mv_rs_split",         "mv_rs_rank"};
 
@@ -60,8 +58,16 @@ struct Plan {
     uint64_t n_sampled;         // sampled coordinates per row
     uint32_t m_target;          // sampled coordinates that must lie at or above the threshold bin
     uint32_t cap;               // candidate list capacity per row
-    uint32_t n_vote_blocks;
-    uint32_t emit_blocks;       // workgroups per row that walk the candidate list
+    uint32_t n_vote_blocks;     // workgroups of the mask kernels: blocks of 16384 vote_q coordinates
+    uint32_t vote_q;            // 1, 2 or 4 quads of 16 vote bytes per thread of the mask kernels
+    uint32_t rs_blocks;         // workgroups of mv_rs_keys: blocks of kVoteBlock coordinates
+    uint32_t list_blocks;       // workgroups per row that walk a candidate list, one thread per entry
+    uint32_t vote_blocks;       // workgroups per row of mv_row_votes
+    uint32_t emit_blocks;       // workgroups per row that write the sorted vote list
+    uint32_t scan_parts;        // workgroups per row that scan the segment tallies (4096 segments each)
+    uint32_t select_parts;      // workgroups per row of mv_row_select when they also cast the votes
+    uint32_t n_spec;            // list entries per thread that mv_row_select fetches ahead of the row's count
+    bool     long_lists;        // the expected lists need the instance of mv_row_select that keeps more entries
     uint32_t scan_blocks;       // workgroups per row that scan the segment tallies
     // add-drop voting (only with MV_FLAG_ADD_DROP)
     bool     add_drop;
@@ -75,9 +81,11 @@ struct Plan {
     uint32_t rs_cap;              // most coordinates that can hold a vote: min(N K, d)
     size_t   off_rshist, off_rscount, off_rsbits, off_rsblk, off_rslist, off_rslist2;
     // scratch offsets (bytes)
-    size_t off_hist, off_tau, off_rowcnt, off_slow, off_kth, off_tiecut, off_cntge, off_seg, off_segsel,
+    uint32_t sample_wgs;        // workgroups per row that sample it (the head of the streaming kernel's grid)
+    size_t off_sampledone, off_readsdone, off_taupub, off_poison, off_stepno, off_candcount;
+    size_t off_hist, off_tau, off_rowcnt, off_slow, off_kth, off_tiecut, off_lvlsets, off_seg, off_segsel,
         off_segpre,
-        off_blktotal, off_votethr, off_alist, off_dlist, off_adcount, off_adthr, off_adbits, off_adblk, off_cand, off_votes, off_blockcnt;
+        off_blktotal, off_alist, off_dlist, off_adcount, off_adthr, off_adbits, off_adblk, off_cand, off_votes, off_blockcnt, off_votethr;
     size_t total_bytes;
 };
 
@@ -115,12 +123,24 @@ Plan make_plan(const mv_config* c)
     p.n_sampled_chunks = (uint32_t)((nchunks + stride - 1) / stride);
     // all sampled chunks are full except possibly the row's last chunk
     p.n_sampled = (uint64_t)p.n_sampled_chunks * mvk::kChunk;
+    {
+        // kSampleQuads quads per thread and round; at most 16 sampling workgroups of 512 threads per row
+        const uint64_t nquads = (uint64_t)p.n_sampled_chunks * (mvk::kChunk / 4);
+        const uint64_t per_wg = (uint64_t)mvk::kSampleQuads * mvk::kStreamThreads;
+        uint64_t bx = (nquads + per_wg - 1) / per_wg;
+        if (bx > 16) bx = 16;
+        if (bx < 1) bx = 1;
+        p.sample_wgs = (uint32_t)bx;
+    }
     if (((nchunks - 1) % stride) == 0) p.n_sampled -= (uint64_t)(nchunks * mvk::kChunk - (uint64_t)p.d);
 
-    // Aim at 2K coordinates above the threshold (in expectation), never fewer than
-    // 128 sampled ones, so that falling short of K is many standard deviations away.
+    // A row with exactly K coordinates above the threshold shows K * frac of them in the
+    // sample on average.  Ask for m sampled ones with m - 7 sqrt(m) = K * frac, never fewer
+    // than 128: falling short of K is then a 7-sigma event of the sample count, and the
+    // candidates exceed K by about 7 sqrt(m) / frac (a factor 2 at K = d/1000, 1.3 at d/100).
     const double frac = (double)p.n_sampled / (double)p.d;
-    double m = 2.0 * (double)p.K * frac;
+    const double root_m = 3.5 + sqrt(12.25 + (double)p.K * frac);
+    double m = ceil(root_m * root_m);
     if (m < 128.0) m = 128.0;
     m += 1.0;
     p.m_target = (m >= 4294967295.0) ? 0xFFFFFFFFu : (uint32_t)m;
@@ -130,7 +150,16 @@ Plan make_plan(const mv_config* c)
     if (cap > (uint64_t)p.d) cap = (uint64_t)p.d;
     p.cap = (uint32_t)cap;
 
-    p.n_vote_blocks = (uint32_t)((p.d + mvk::kVoteBlock - 1) / mvk::kVoteBlock);
+    p.rs_blocks = (uint32_t)((p.d + mvk::kVoteBlock - 1) / mvk::kVoteBlock);
+    {
+        // the mask kernels: as few vote bytes per thread as keep the grid within one round of workgroups
+        // (one workgroup of 1024 threads per compute unit, some of them taken by the segment scans)
+        uint32_t q = 1;
+        while (q < 4 && (uint64_t)p.d > 440ull * mvk::kMaskThreads * 16 * q) q *= 2;
+        p.vote_q = q;
+        const uint64_t per = (uint64_t)mvk::kMaskThreads * 16 * q;
+        p.n_vote_blocks = (uint32_t)(((uint64_t)p.d + per - 1) / per);
+    }
     // about 2K candidates per row are expected: one thread per candidate with some room, the kernels
     // stride over whatever is there
     {
@@ -139,19 +168,50 @@ Plan make_plan(const mv_config* c)
         if (eb > eb_cap) eb = eb_cap;
         if (eb > 256) eb = 256;      // more workgroups than this only crowd the atomics (measured at K = 111,740)
         if (eb < 1) eb = 1;
-        p.emit_blocks = (uint32_t)eb;
+        p.list_blocks = (uint32_t)eb;
     }
     p.scan_blocks = (p.nseg + 1023) / 1024;
+    p.scan_parts = (p.nseg + 4095) / 4096;
+    {
+        // about 2K candidates are expected; fetch 3K per row ahead (never beyond the list's storage),
+        // and give every workgroup of a row about four list entries per thread to cast votes for
+        const uint64_t expect = (uint64_t)((double)p.m_target / frac * 1.25) + 1;   // candidates per row, with room
+        uint64_t slots = (expect + mvk::kRowThreads - 1) / mvk::kRowThreads;        // list entries per thread
+        const uint64_t in_cap = ((uint64_t)p.cap + mvk::kRowThreads - 1) / mvk::kRowThreads;
+        if (slots > in_cap) slots = in_cap;
+        if (slots < 1) slots = 1;
+        p.long_lists = slots > (uint64_t)mvk::kKeepShort;
+        p.n_spec = (uint32_t)(slots < (uint64_t)mvk::kSpec ? slots : (uint64_t)mvk::kSpec);
+        uint64_t parts = (slots + 3) / 4;
+        if (parts > 16) parts = 16;
+        if (parts * p.N > 240) parts = 240 / p.N;      // all of a step's workgroups at once: one per compute unit
+        if (parts < 1) parts = 1;
+        p.select_parts = (uint32_t)parts;
+        // beyond what one workgroup keeps in registers the lists go through the many-workgroup select
+        p.multi_select = slots > (uint64_t)mvk::kKeepLong;
+        // four list entries per thread in mv_row_votes, eight when writing the sorted lists
+        uint64_t vb = (slots + 3) / 4, eb2 = (slots + 3) / 4;
+        if (vb > 256) vb = 256;
+        if (eb2 * p.N > 256) eb2 = 256 / p.N;
+        if (eb2 < 1) eb2 = 1;
+        p.vote_blocks = (uint32_t)vb;
+        p.emit_blocks = (uint32_t)eb2;
+    }
 
     size_t off = 0;
     p.off_hist = off;     off += align_up((size_t)p.N * mvk::kHistBins * 4);
     p.off_tau = off;      off += align_up((size_t)p.N * 4);
-    p.off_rowcnt = off;   off += align_up((size_t)p.N * mvk::kCounterStride * 4);
+    p.off_sampledone = off; off += align_up((size_t)p.N * mvk::kCounterStride * 4);
+    p.off_readsdone = off; off += align_up((size_t)p.N * mvk::kCounterStride * 4);
+    p.off_taupub = off;   off += align_up((size_t)p.N * (mvk::kCounterStride / 2) * 8);
+    p.off_poison = off;   off += align_up((size_t)p.N * 4);
+    p.off_stepno = off;   off += align_up(4);
+    p.off_candcount = off; off += align_up((size_t)p.N * 4);
+    p.off_rowcnt = off;   off += 2 * align_up((size_t)p.N * mvk::kCounterStride * 4);   // one set per step parity
     p.off_slow = off;     off += align_up((size_t)p.N * 4);
     p.off_kth = off;      off += align_up((size_t)p.N * 4);
     p.off_tiecut = off;   off += align_up((size_t)p.N * 4);
-    p.off_cntge = off;    off += align_up((size_t)p.N * 256 * 4);
-    p.off_votethr = off;  off += align_up(2 * 4);
+    p.off_lvlsets = off;  off += align_up((size_t)mvk::kLvlSets * 256 * 4);
     p.off_seg = off;      off += align_up((size_t)p.N * p.nseg * 8);
     p.off_segsel = off;   off += align_up((size_t)p.N * p.nseg * 4);
     p.off_segpre = off;   off += align_up((size_t)p.N * p.nseg * 4);
@@ -159,6 +219,7 @@ Plan make_plan(const mv_config* c)
     p.off_cand = off;     off += align_up((size_t)p.N * p.cap * 8);
     p.off_votes = off;    off += align_up(((size_t)p.d + 15) / 16 * 16);
     p.off_blockcnt = off; off += align_up((size_t)p.n_vote_blocks * 8);
+    p.off_votethr = off;  off += align_up(2 * 4);
     p.add_drop = (c->flags & MV_FLAG_ADD_DROP) != 0;
     p.nwords = (uint32_t)((p.d + 31) / 32);
     p.nwords_pad = (p.nwords + 3) / 4 * 4;
@@ -174,7 +235,6 @@ Plan make_plan(const mv_config* c)
     }
     // (measured: one workgroup per row takes 20 us at 24K candidates, 38 us at 55K, 89 us at 230K; the three
     // kernels of the many-workgroup select about 40 us)
-    p.multi_select = 2ull * p.K > 2ull * mvk::kKeep * mvk::kRowThreads;
     if (p.multi_select) {
         p.off_selhist = off;    off += align_up((size_t)p.N * mvk::kSelBins * 4);
         p.off_selcount2 = off;  off += align_up((size_t)p.N * 4);
@@ -201,11 +261,14 @@ struct mv_ctx {
     char*      ws;          // device scratch
     bool       owns_ws;
     bool       ended;
+    bool       broken;      // a step's launch sequence failed: the scratch invariants no longer hold
     int32_t    profiling;
     // event pairs around kernels, a ring over the last kEventRing steps
     hipEvent_t ev[kEventRing][KID_COUNT][2];
     bool       ev_recorded[kEventRing][KID_COUNT];
     uint64_t   steps_done;
+    uint32_t   spin_limit;  // polls a streaming wavefront makes for its row's threshold before it gives up
+    uint32_t   head_wgs;    // streaming workgroups at the head of the grid that wait for the sampling before loading
     hipStream_t last_stream;
 };
 
@@ -252,6 +315,8 @@ mv_status mv_begin(const mv_config* cfg, mv_ctx** out_ctx)
     memset(c, 0, sizeof *c);
     c->cfg = *cfg;
     c->plan = plan;
+    c->head_wgs = 2048;         // about two rounds of resident workgroups
+    c->spin_limit = 1u << 20;   // of about a microsecond each; a threshold is normally there within ten
 
     DeviceGuard guard(cfg->device);
     if (!guard.ok) {
@@ -319,7 +384,7 @@ struct StepArgs {
 mv_status check_common(mv_ctx* c, const StepArgs& a)
 {
     if (!c) return MV_ERR_INVALID_ARG;
-    if (c->ended) return MV_ERR_STATE;
+    if (c->ended || c->broken) return MV_ERR_STATE;
     if (!a.grads || !a.err || !a.mask_idx || !a.agg_vals) return MV_ERR_INVALID_ARG;
     if (reinterpret_cast<uintptr_t>(a.rand_exp) & 3) return MV_ERR_INVALID_ARG;
     const Plan& p = c->plan;
@@ -345,23 +410,30 @@ mv_status enqueue_step(mv_ctx* c, const StepArgs& a, void* stream_v)
     const bool random_sel = a.rand_exp != nullptr;
     DeviceGuard guard(c->cfg.device);
     if (!guard.ok) return MV_ERR_DEVICE;
+    // an error the caller left pending is not this step's: nothing is enqueued and the context stays usable
+    if (hipPeekAtLastError() != hipSuccess) return MV_ERR_DEVICE;
     hipStream_t st = static_cast<hipStream_t>(stream_v);
 
     uint32_t* hist = ws_ptr<uint32_t>(c, p.off_hist);
     uint32_t* tau = ws_ptr<uint32_t>(c, p.off_tau);
-    uint32_t* rowcnt = ws_ptr<uint32_t>(c, p.off_rowcnt);
+    // the rows' candidate counters while the streaming pass runs (two sets, used in turn; the step's
+    // number on the device says which), and the counts as mv_row_select leaves them for everyone after it
+    const uint32_t rowcnt_set_words = (uint32_t)(align_up((size_t)p.N * mvk::kCounterStride * 4) / 4);
+    uint32_t* rowcnt_sets = ws_ptr<uint32_t>(c, p.off_rowcnt);
+    uint32_t* stepno = ws_ptr<uint32_t>(c, p.off_stepno);
+    uint32_t* rowcnt = ws_ptr<uint32_t>(c, p.off_candcount);
     uint32_t* slow = ws_ptr<uint32_t>(c, p.off_slow);
-    uint32_t* cntge = ws_ptr<uint32_t>(c, p.off_cntge);
+    uint32_t* lvlsets = ws_ptr<uint32_t>(c, p.off_lvlsets);
     uint32_t* kth = ws_ptr<uint32_t>(c, p.off_kth);
     uint32_t* tiecut = ws_ptr<uint32_t>(c, p.off_tiecut);
     uint32_t* segsel = ws_ptr<uint32_t>(c, p.off_segsel);
     uint32_t* segpre = ws_ptr<uint32_t>(c, p.off_segpre);
     uint32_t* blktotal = ws_ptr<uint32_t>(c, p.off_blktotal);
-    uint32_t* votethr = ws_ptr<uint32_t>(c, p.off_votethr);
     mvk::u32x2* seg = ws_ptr<mvk::u32x2>(c, p.off_seg);
     mvk::u32x2* cand = ws_ptr<mvk::u32x2>(c, p.off_cand);
     uint32_t* votes32 = ws_ptr<uint32_t>(c, p.off_votes);
     mvk::u32x2* blockcnt = ws_ptr<mvk::u32x2>(c, p.off_blockcnt);
+    uint32_t* votethr = ws_ptr<uint32_t>(c, p.off_votethr);
     mvk::u32x2* alist = p.add_drop ? ws_ptr<mvk::u32x2>(c, p.off_alist) : nullptr;
     mvk::u32x2* dlist = p.add_drop ? ws_ptr<mvk::u32x2>(c, p.off_dlist) : nullptr;
     uint32_t* adcount = p.add_drop ? ws_ptr<uint32_t>(c, p.off_adcount) : nullptr;
@@ -385,52 +457,58 @@ mv_status enqueue_step(mv_ctx* c, const StepArgs& a, void* stream_v)
         if (hipEventRecord(c->ev[slot][kid][1], st) == hipSuccess) c->ev_recorded[slot][kid] = true;
     };
 
-    // 1. sample histogram, then the threshold estimate per row and the counters' reset
+    // 1. one kernel: sample histogram and threshold estimate per row (its first workgroups, which
+    // also reset the per-step counters), and the streaming pass a = g + e over e, candidates out
+    uint32_t* sampledone = ws_ptr<uint32_t>(c, p.off_sampledone);
+    uint32_t* readsdone = ws_ptr<uint32_t>(c, p.off_readsdone);
+    unsigned long long* taupub = ws_ptr<unsigned long long>(c, p.off_taupub);
+    uint32_t* poison = ws_ptr<uint32_t>(c, p.off_poison);
     {
-        const uint64_t nquads = (uint64_t)p.n_sampled_chunks * (mvk::kChunk / 4);
-        uint32_t bx = (uint32_t)((nquads + 2 * mvk::kSampleThreads - 1) / (2 * mvk::kSampleThreads));
-        if (bx > 16) bx = 16;
-        if (bx < 1) bx = 1;
-        dim3 grid(bx, p.N);
-        before(KID_SAMPLE);
-        if (bf16)
-            hipLaunchKernelGGL(mvk::mv_sample_hist<uint16_t>, grid, dim3(mvk::kSampleThreads), 0, st,
-                               static_cast<const uint16_t*>(a.grads), a.ld_g, a.err, a.ld_e, p.d, p.stride,
-                               p.n_sampled_chunks, hist);
-        else
-            hipLaunchKernelGGL(mvk::mv_sample_hist<float>, grid, dim3(mvk::kSampleThreads), 0, st,
-                               static_cast<const float*>(a.grads), a.ld_g, a.err, a.ld_e, p.d, p.stride,
-                               p.n_sampled_chunks, hist);
-        after(KID_SAMPLE);
-        before(KID_PICK);
-        hipLaunchKernelGGL(mvk::mv_pick_threshold, dim3(p.N), dim3(mvk::kRowThreads), 0, st, hist, p.m_target,
-                           tau, rowcnt, slow, cntge, adcount);
-        after(KID_PICK);
-    }
-    // 2. streaming pass: a = g + e over e, candidates out
-    {
-        dim3 grid((p.nseg + mvk::kSegPerBlock - 1) / mvk::kSegPerBlock, p.N);
+        const uint32_t wpr = (p.nseg + mvk::kSegPerBlock - 1) / mvk::kSegPerBlock;
+        const dim3 grid(p.N * p.sample_wgs + p.N * wpr);
         before(KID_STREAM);
         if (bf16)
             hipLaunchKernelGGL(mvk::mv_stream_collect<uint16_t>, grid, dim3(mvk::kStreamThreads), 0, st,
-                               static_cast<const uint16_t*>(a.grads), a.ld_g, a.err, a.ld_e, p.d, tau, cand, p.cap,
-                               rowcnt, seg, segsel, p.nseg);
+                               static_cast<const uint16_t*>(a.grads), a.ld_g, a.err, a.ld_e, p.d, p.N, p.sample_wgs,
+                               p.stride, p.n_sampled_chunks, p.m_target, hist, sampledone, readsdone, taupub, stepno,
+                               c->spin_limit, poison, lvlsets, (uint32_t)(mvk::kLvlSets * 256), adcount, cand, p.cap,
+                               rowcnt_sets, rowcnt_set_words, seg, segsel, p.nseg, wpr, c->head_wgs);
         else
             hipLaunchKernelGGL(mvk::mv_stream_collect<float>, grid, dim3(mvk::kStreamThreads), 0, st,
-                               static_cast<const float*>(a.grads), a.ld_g, a.err, a.ld_e, p.d, tau, cand, p.cap,
-                               rowcnt, seg, segsel, p.nseg);
+                               static_cast<const float*>(a.grads), a.ld_g, a.err, a.ld_e, p.d, p.N, p.sample_wgs,
+                               p.stride, p.n_sampled_chunks, p.m_target, hist, sampledone, readsdone, taupub, stepno,
+                               c->spin_limit, poison, lvlsets, (uint32_t)(mvk::kLvlSets * 256), adcount, cand, p.cap,
+                               rowcnt_sets, rowcnt_set_words, seg, segsel, p.nseg, wpr, c->head_wgs);
         after(KID_STREAM);
     }
     // 3. exact per-row select
+    // (in plain voting with short lists every workgroup of a row also casts the votes of its share of the list)
+    const bool sorted = a.worker_idx != nullptr;
+    const bool votes_in_select = !add_drop && !p.multi_select;
     before(KID_ROW_SELECT);
-    hipLaunchKernelGGL(mvk::mv_row_select, dim3(p.N), dim3(mvk::kRowThreads), 0, st, a.err, a.ld_e, p.d, p.K, cand,
-                       p.cap, rowcnt, tau, kth, tiecut, a.worker_idx, votes32, cntge, slow, add_drop ? 1 : 0,
-                       p.multi_select ? 1 : 0);
+    {
+        const uint32_t parts = votes_in_select ? p.select_parts : 1;
+        const dim3 grid((p.N + 7) / 8 * 8 * parts);
+        if (p.long_lists)
+            hipLaunchKernelGGL(mvk::mv_row_select<mvk::kKeepLong>, grid, dim3(mvk::kRowThreads), 0, st, a.err, a.ld_e,
+                               p.d, p.N, p.K, cand, p.cap, rowcnt_sets, rowcnt_set_words, stepno, taupub, poison, rowcnt,
+                               tau, kth, tiecut,
+                               a.worker_idx, votes32,
+                               sorted ? segsel : nullptr, p.nseg, lvlsets, slow, parts, p.n_spec, add_drop ? 1 : 0,
+                               p.multi_select ? 1 : 0);
+        else
+            hipLaunchKernelGGL(mvk::mv_row_select<mvk::kKeepShort>, grid, dim3(mvk::kRowThreads), 0, st, a.err, a.ld_e,
+                               p.d, p.N, p.K, cand, p.cap, rowcnt_sets, rowcnt_set_words, stepno, taupub, poison, rowcnt,
+                               tau, kth, tiecut,
+                               a.worker_idx, votes32,
+                               sorted ? segsel : nullptr, p.nseg, lvlsets, slow, parts, p.n_spec, add_drop ? 1 : 0,
+                               p.multi_select ? 1 : 0);
+    }
     after(KID_ROW_SELECT);
     if (p.multi_select) {
         // long candidate lists: histogram, split at the bin of the K-th largest, exact rank
         mvk::ListSelect ls;
-        ls.list = cand;  ls.cap = p.cap;  ls.count = rowcnt;  ls.count_stride = mvk::kCounterStride;
+        ls.list = cand;  ls.cap = p.cap;  ls.count = rowcnt;  ls.count_stride = 1;
         ls.base = tau;  ls.shift = mvk::kFineShift;
         ls.want = p.K;
         ls.hist = ws_ptr<uint32_t>(c, p.off_selhist);
@@ -449,37 +527,36 @@ mv_status enqueue_step(mv_ctx* c, const StepArgs& a, void* stream_v)
         after(KID_SEL_RANK);
     }
 
-    const bool sorted = a.worker_idx != nullptr;
     uint32_t* mask_votes32 = votes32;     // the packed vote bytes the mask is selected from
-    if (!add_drop) {
-        // 4. votes (and segment tallies when the sorted lists are wanted)
+    if (!add_drop && p.multi_select) {
+        // 4. votes of the long lists (and segment tallies when the sorted lists are wanted)
         before(KID_ROW_VOTES);
-        hipLaunchKernelGGL(mvk::mv_row_votes, dim3(p.emit_blocks, p.N), dim3(mvk::kVoteThreads), 0, st, cand, p.cap,
-                           rowcnt, p.nseg, kth, tiecut, slow, sorted ? segsel : nullptr, votes32, cntge);
+        hipLaunchKernelGGL(mvk::mv_row_votes, dim3(p.vote_blocks, p.N), dim3(mvk::kRowThreads), 0, st, cand, p.cap,
+                           rowcnt, p.nseg, kth, tiecut, slow, sorted ? segsel : nullptr, votes32, lvlsets);
         after(KID_ROW_VOTES);
-    } else {
+    } else if (add_drop) {
         // 4'. add-drop voting: candidates for addition and removal, exact K_ad-selects,
         // update of msum and of the standing votes, sorted add / drop lists
         const uint32_t k_ad = (uint32_t)a.k_ad;
         uint32_t* msum32 = reinterpret_cast<uint32_t*>(a.msum);
         before(KID_AD_COLLECT);
-        hipLaunchKernelGGL(mvk::mv_ad_collect, dim3(p.emit_blocks + p.bit_blocks, p.N), dim3(mvk::kVoteThreads), 0,
+        hipLaunchKernelGGL(mvk::mv_ad_collect, dim3(p.list_blocks + p.bit_blocks, p.N), dim3(mvk::kVoteThreads), 0,
                            st, a.err, a.ld_e, p.d, cand, p.cap, rowcnt, kth, tiecut, slow, a.vote_bits, a.ld_bits,
-                           p.nwords_pad, alist, dlist, p.cap_d, adcount, p.emit_blocks);
+                           p.nwords_pad, alist, dlist, p.cap_d, adcount, p.list_blocks);
         after(KID_AD_COLLECT);
         before(KID_AD_SELECT);
         hipLaunchKernelGGL(mvk::mv_ad_select, dim3(2, p.N), dim3(mvk::kRowThreads), 0, st, alist, p.cap, dlist,
                            p.cap_d, adcount, k_ad, tau, slow, adthr, a.counts);
         after(KID_AD_SELECT);
         before(KID_AD_APPLY);
-        hipLaunchKernelGGL(mvk::mv_ad_apply, dim3(p.emit_blocks, p.N), dim3(mvk::kVoteThreads), 0, st, alist, p.cap,
+        hipLaunchKernelGGL(mvk::mv_ad_apply, dim3(p.list_blocks, p.N), dim3(mvk::kVoteThreads), 0, st, alist, p.cap,
                            dlist, p.cap_d, adcount, adthr, adbits, p.nwords_pad, msum32);
         after(KID_AD_APPLY);
-        before(KID_AD_COUNT_LEVELS);
-        hipLaunchKernelGGL(mvk::mv_ad_count_levels, dim3(p.N * p.bit_blocks + p.n_vote_blocks),
-                           dim3(mvk::kVoteThreads), 0, st, adbits, p.nwords_pad, p.bit_blocks, adblk,
-                           a.vote_bits, a.ld_bits, p.N * p.bit_blocks, msum32, p.d, cntge, p.N);
-        after(KID_AD_COUNT_LEVELS);
+        before(KID_AD_COMPACT_COUNT);
+        hipLaunchKernelGGL(mvk::mv_ad_compact_count, dim3(p.N * p.bit_blocks + p.rs_blocks), dim3(mvk::kVoteThreads),
+                           0, st, adbits, p.nwords_pad, p.bit_blocks, adblk, (const uint32_t*)a.vote_bits, a.ld_bits,
+                           p.N * p.bit_blocks, (const uint32_t*)msum32, p.d, lvlsets);
+        after(KID_AD_COMPACT_COUNT);
         before(KID_AD_COMPACT_EMIT);
         hipLaunchKernelGGL(mvk::mv_ad_compact_emit, dim3(p.bit_blocks, p.N), dim3(mvk::kVoteThreads), 0, st,
                            adbits, p.nwords_pad, p.bit_blocks, adblk, k_ad, a.add_idx, a.drop_idx, a.vote_bits,
@@ -497,7 +574,7 @@ mv_status enqueue_step(mv_ctx* c, const StepArgs& a, void* stream_v)
         mvk::u32x2* rslist = ws_ptr<mvk::u32x2>(c, p.off_rslist);
         mvk::u32x2* rslist2 = ws_ptr<mvk::u32x2>(c, p.off_rslist2);
         before(KID_RS_KEYS);
-        hipLaunchKernelGGL(mvk::mv_rs_keys, dim3(p.n_vote_blocks), dim3(mvk::kVoteThreads), 0, st, votes32, p.d,
+        hipLaunchKernelGGL(mvk::mv_rs_keys, dim3(p.rs_blocks), dim3(mvk::kVoteThreads), 0, st, votes32, p.d,
                            a.rand_exp, rslist, p.rs_cap, rscount);
         after(KID_RS_KEYS);
         mvk::ListSelect ls;
@@ -516,8 +593,9 @@ mv_status enqueue_step(mv_ctx* c, const StepArgs& a, void* stream_v)
         hipLaunchKernelGGL(mvk::mv_rs_rank, dim3(1), dim3(mvk::kRowThreads), 0, st, ls, rscount, rsbits);
         after(KID_RS_RANK);
         before(KID_AD_COMPACT_COUNT);
-        hipLaunchKernelGGL(mvk::mv_ad_compact_count, dim3(p.bit_blocks, 1), dim3(mvk::kVoteThreads), 0, st, rsbits,
-                           p.nwords_pad, p.bit_blocks, rsblk, (const uint32_t*)nullptr, (int64_t)0);
+        hipLaunchKernelGGL(mvk::mv_ad_compact_count, dim3(p.bit_blocks), dim3(mvk::kVoteThreads), 0, st, rsbits,
+                           p.nwords_pad, p.bit_blocks, rsblk, (const uint32_t*)nullptr, (int64_t)0, p.bit_blocks,
+                           (const uint32_t*)nullptr, p.d, (uint32_t*)nullptr);
         after(KID_AD_COMPACT_COUNT);
         before(KID_AD_COMPACT_EMIT);
         hipLaunchKernelGGL(mvk::mv_ad_compact_emit, dim3(p.bit_blocks, 1), dim3(mvk::kVoteThreads), 0, st, rsbits,
@@ -525,37 +603,51 @@ mv_status enqueue_step(mv_ctx* c, const StepArgs& a, void* stream_v)
                            (uint32_t*)nullptr, (int64_t)0);
         after(KID_AD_COMPACT_EMIT);
     }
-    // 5. global mask; in plain voting extra workgroups scan the tallies / write the sorted vote lists
-    // (with random selection the mask is already written: only the lists, the copy of the
+    // 5. global mask; in plain voting extra workgroups of the first kernel scan the segment tallies for
+    // the sorted vote lists (with random selection the mask is already written: only the copy of the
     // votes and the clearing of the vote words remain)
     const bool lists = sorted && !add_drop;
-    before(KID_MASK_COUNT);
-    hipLaunchKernelGGL(mvk::mv_mask_count, dim3(p.n_vote_blocks + (lists ? p.N * p.scan_blocks : 0)),
-                       dim3(mvk::kVoteThreads), 0, st, mask_votes32, p.d, p.N, p.K, cntge, blockcnt,
-                       add_drop ? nullptr : a.votes, p.n_vote_blocks, p.scan_blocks, p.nseg, slow, segsel, segpre,
-                       blktotal, votethr, add_drop ? 1 : 0);
-    after(KID_MASK_COUNT);
-    before(KID_MASK_EMIT);
-    hipLaunchKernelGGL(mvk::mv_mask_emit, dim3(p.n_vote_blocks + (lists ? p.N * p.emit_blocks : 0)),
-                       dim3(mvk::kVoteThreads), 0, st, mask_votes32, p.d, p.K, votethr, blockcnt,
-                       random_sel ? (uint32_t*)nullptr : a.mask_idx,
-                       p.n_vote_blocks, p.emit_blocks, cand, p.cap, rowcnt, seg, p.nseg, segpre, blktotal, p.scan_blocks,
-                       kth, tiecut, slow, a.worker_idx, add_drop ? 0 : 1);
-    after(KID_MASK_EMIT);
-    // 6. gather + mean + error update
+    {
+        const dim3 grid_c(p.n_vote_blocks + (lists ? p.N * p.scan_parts : 0)), grid_e(p.n_vote_blocks);
+        const dim3 block(mvk::kMaskThreads);
+        uint8_t* votes_out = add_drop ? nullptr : a.votes;
+        uint32_t* mask_out = random_sel ? (uint32_t*)nullptr : a.mask_idx;
+        const int clear = add_drop ? 0 : 1;
+#define MV_LAUNCH_MASK(Q)                                                                                        \
+        before(KID_MASK_COUNT);                                                                                  \
+        hipLaunchKernelGGL(mvk::mv_mask_count<Q>, grid_c, block, 0, st, mask_votes32, p.d, p.N, p.K, lvlsets,     \
+                           blockcnt, votethr, votes_out, p.n_vote_blocks, p.scan_parts, p.scan_blocks, p.nseg,   \
+                           slow, segsel, segpre, blktotal, add_drop ? 1 : 0);                                    \
+        after(KID_MASK_COUNT);                                                                                   \
+        before(KID_MASK_EMIT);                                                                                   \
+        hipLaunchKernelGGL(mvk::mv_mask_emit<Q>, grid_e, block, 0, st, mask_votes32, p.d, p.K, votethr, blockcnt, \
+                           mask_out, clear);                                                                     \
+        after(KID_MASK_EMIT);
+        if (p.vote_q == 1) { MV_LAUNCH_MASK(1) } else if (p.vote_q == 2) { MV_LAUNCH_MASK(2) } else { MV_LAUNCH_MASK(4) }
+#undef MV_LAUNCH_MASK
+    }
+    // 6. gather + mean + error update; extra workgroups write the sorted vote lists beside it
     {
         const float inv_n = 1.0f / (float)p.N;
-        const uint32_t kb = mvk::kGatherThreads / p.N;
+        const uint32_t kb = mvk::kMaskThreads / p.N;
+        const uint32_t n_gather = (p.K + kb - 1) / kb;
         before(KID_GATHER);
-        hipLaunchKernelGGL(mvk::mv_gather_update, dim3((p.K + kb - 1) / kb),
-                           dim3(mvk::kGatherThreads), 0, st, a.err, a.ld_e, p.d, p.N, p.K, a.mask_idx, inv_n,
-                           c->cfg.reduce == MV_REDUCE_MEAN ? 1 : 0, a.agg_vals);
+        hipLaunchKernelGGL(mvk::mv_gather_update, dim3(n_gather + (lists ? p.N * p.emit_blocks : 0)),
+                           dim3(mvk::kMaskThreads), 0, st, a.err, a.ld_e, p.d, p.N, p.K, a.mask_idx, inv_n,
+                           c->cfg.reduce == MV_REDUCE_MEAN ? 1 : 0, a.agg_vals, n_gather, p.emit_blocks, cand, p.cap,
+                           rowcnt, seg, p.nseg, segpre, blktotal, p.scan_blocks, kth, tiecut, slow, a.worker_idx,
+                           stepno);
         after(KID_GATHER);
     }
     c->last_stream = st;
     c->steps_done += 1;
-    if (hipGetLastError() != hipSuccess || !ev_ok) return MV_ERR_DEVICE;
-    return MV_OK;
+    if (hipGetLastError() != hipSuccess) {
+        // Some kernel of the sequence was not launched: counters that every step leaves at zero, and the
+        // step's number on the device, may be off.  The context refuses further steps.
+        c->broken = true;
+        return MV_ERR_DEVICE;
+    }
+    return ev_ok ? MV_OK : MV_ERR_DEVICE;
 }
 
 }  // namespace
@@ -665,6 +757,14 @@ mv_status mv_set_profiling(mv_ctx* c, int32_t level)
     return MV_OK;
 }
 
+mv_status mv_set_spin_limit(mv_ctx* c, uint32_t polls)
+{
+    if (!c) return MV_ERR_INVALID_ARG;
+    if (c->ended) return MV_ERR_STATE;
+    c->spin_limit = polls;
+    return MV_OK;
+}
+
 mv_status mv_step_kernel_ms(mv_ctx* c, int32_t steps_back, float* ms, int32_t n)
 {
     if (!c || !ms || n < KID_COUNT) return MV_ERR_INVALID_ARG;
@@ -693,9 +793,7 @@ mv_status mv_last_step_row_stats(mv_ctx* c, uint32_t* cand_count, uint32_t* thre
     if (!guard.ok) return MV_ERR_DEVICE;
     if (hipStreamSynchronize(c->last_stream) != hipSuccess) return MV_ERR_DEVICE;
     const size_t nb = (size_t)c->plan.N * 4;
-    // the candidate counters lie one per cache line
-    if (cand_count && hipMemcpy2D(cand_count, 4, c->ws + c->plan.off_rowcnt, (size_t)mvk::kCounterStride * 4, 4,
-                                  c->plan.N, hipMemcpyDeviceToHost) != hipSuccess)
+    if (cand_count && hipMemcpy(cand_count, c->ws + c->plan.off_candcount, nb, hipMemcpyDeviceToHost) != hipSuccess)
         return MV_ERR_DEVICE;
     if (threshold_bits && hipMemcpy(threshold_bits, c->ws + c->plan.off_tau, nb, hipMemcpyDeviceToHost) != hipSuccess)
         return MV_ERR_DEVICE;
@@ -703,6 +801,29 @@ mv_status mv_last_step_row_stats(mv_ctx* c, uint32_t* cand_count, uint32_t* thre
         return MV_ERR_DEVICE;
     return MV_OK;
 }
+
+#ifdef MV_PHASE_STAMPS
+int mv_debug_spans(unsigned long long* host)
+{
+    if (hipDeviceSynchronize() != hipSuccess) return -1;
+    if (hipMemcpyFromSymbol(host, HIP_SYMBOL(mvk::g_span), sizeof(unsigned long long) * 16 * 4096 * 2) != hipSuccess)
+        return -1;
+    void* dev = nullptr;
+    if (hipGetSymbolAddress(&dev, HIP_SYMBOL(mvk::g_span)) != hipSuccess) return -1;
+    if (hipMemset(dev, 0, sizeof(unsigned long long) * 16 * 4096 * 2) != hipSuccess) return -1;
+    return 0;
+}
+int mv_debug_stamps(unsigned long long* host, int n)
+{
+    if (n > 2 * 16 * 32) n = 2 * 16 * 32;
+    if (hipDeviceSynchronize() != hipSuccess) return -1;
+    if (hipMemcpyFromSymbol(host, HIP_SYMBOL(mvk::g_stamps), (size_t)n * 8) != hipSuccess) return -1;
+    void* dev = nullptr;
+    if (hipGetSymbolAddress(&dev, HIP_SYMBOL(mvk::g_stamps)) != hipSuccess) return -1;
+    if (hipMemset(dev, 0, sizeof(unsigned long long) * 2 * 16 * 32) != hipSuccess) return -1;
+    return n;
+}
+#endif
 
 mv_status mv_probe_copy(void* dst, const void* src, size_t bytes, void* stream)
 {

@@ -57,7 +57,8 @@ __global__ __launch_bounds__(kThreads) void codec_encode_kernel(
     unsigned long long* __restrict__ n_bits_out)
 {
     const uint32_t row = blockIdx.y;
-    const uint32_t n = counts ? counts[(int64_t)row * counts_stride] : n_fixed;
+    // a length read from device memory is wire-side data: never trusted beyond the row's storage
+    const uint32_t n = counts ? min(counts[(int64_t)row * counts_stride], n_fixed) : n_fixed;
     const uint32_t code_len = 1 + B;
     const uint64_t n_blocks = ((uint64_t)d + block_len - 1) / block_len;
     const uint64_t total = (uint64_t)n * code_len + n_blocks;
@@ -158,10 +159,11 @@ __device__ __forceinline__ MapTables row_tables(uint8_t* base, uint64_t max_chun
 
 __global__ __launch_bounds__(kThreads) void codec_chunk_maps_kernel(
     const uint32_t* __restrict__ streams, int64_t ld_words, const unsigned long long* __restrict__ n_bits,
-    uint32_t B, uint8_t* __restrict__ maps, uint64_t max_chunks)
+    uint64_t max_bits, uint32_t B, uint8_t* __restrict__ maps, uint64_t max_chunks)
 {
     const uint32_t row = blockIdx.y;
-    const uint64_t total = n_bits[row];
+    // the received length is wire-side data: clamped to what the scratch tables were sized for
+    const uint64_t total = min((uint64_t)n_bits[row], max_bits);
     const uint64_t n_chunks = (total + kChunkBits - 1) / kChunkBits;
     const uint32_t* words = streams + (int64_t)row * ld_words;
     const uint32_t n_states = B + 1;
@@ -192,8 +194,8 @@ constexpr int kExitLds = 24576;  // exit-state bytes staged in LDS when the row'
 // down the two levels, and every thread walks its range for real, counting the codes
 // and closed blocks before each chunk (a workgroup scan joins the ranges).
 __global__ __launch_bounds__(kWalkThreads) void codec_walk_kernel(
-    const unsigned long long* __restrict__ n_bits, uint32_t B, uint8_t* __restrict__ maps, uint64_t max_chunks,
-    Entry* __restrict__ entries, uint32_t* __restrict__ counts_out)
+    const unsigned long long* __restrict__ n_bits, uint64_t max_bits, uint32_t B, uint8_t* __restrict__ maps,
+    uint64_t max_chunks, Entry* __restrict__ entries, uint32_t* __restrict__ counts_out)
 {
     __shared__ uint8_t  ex_lds[kExitLds];
     __shared__ uint8_t  r_exit[kWalkThreads][kMaxB + 1];
@@ -202,7 +204,7 @@ __global__ __launch_bounds__(kWalkThreads) void codec_walk_kernel(
     __shared__ uint8_t  g_state[32];
     __shared__ unsigned long long wave_sum[kWalkThreads / 64 + 1];
     const uint32_t row = blockIdx.x, t = threadIdx.x;
-    const uint64_t total = n_bits[row];
+    const uint64_t total = min((uint64_t)n_bits[row], max_bits);
     const uint64_t n_chunks = (total + kChunkBits - 1) / kChunkBits;
     const uint64_t per = (n_chunks + kWalkThreads - 1) / kWalkThreads;
     const uint64_t c0 = min((uint64_t)t * per, n_chunks), c1 = min(c0 + per, n_chunks);
@@ -284,12 +286,12 @@ __global__ __launch_bounds__(kWalkThreads) void codec_walk_kernel(
 }
 
 __global__ __launch_bounds__(kThreads) void codec_emit_kernel(
-    const uint32_t* __restrict__ streams, int64_t ld_words, const unsigned long long* __restrict__ n_bits, int64_t d,
-    uint32_t block_len, uint32_t B, const Entry* __restrict__ entries, uint64_t max_chunks,
-    uint32_t* __restrict__ idx_out, int64_t ld_idx, uint32_t max_n)
+    const uint32_t* __restrict__ streams, int64_t ld_words, const unsigned long long* __restrict__ n_bits,
+    uint64_t max_bits, int64_t d, uint32_t block_len, uint32_t B, const Entry* __restrict__ entries,
+    uint64_t max_chunks, uint32_t* __restrict__ idx_out, int64_t ld_idx, uint32_t max_n)
 {
     const uint32_t row = blockIdx.y;
-    const uint64_t total = n_bits[row];
+    const uint64_t total = min((uint64_t)n_bits[row], max_bits);
     const uint64_t n_chunks = (total + kChunkBits - 1) / kChunkBits;
     const uint32_t* words = streams + (int64_t)row * ld_words;
     uint32_t* out = idx_out + (int64_t)row * ld_idx;
@@ -378,14 +380,14 @@ mv_status mv_codec_decode(const uint32_t* streams, int64_t ld_words, const uint6
     uint64_t bx = (max_chunks * (B + 1) + mvc::kThreads - 1) / mvc::kThreads;
     if (bx > 4096) bx = 4096;
     hipLaunchKernelGGL(mvc::codec_chunk_maps_kernel, dim3((uint32_t)bx, (uint32_t)rows), dim3(mvc::kThreads), 0, st,
-                       streams, ld_words, nb, B, maps, max_chunks);
-    hipLaunchKernelGGL(mvc::codec_walk_kernel, dim3((uint32_t)rows), dim3(mvc::kWalkThreads), 0, st, nb, B, maps,
-                       max_chunks, entries, counts_out);
+                       streams, ld_words, nb, max_bits, B, maps, max_chunks);
+    hipLaunchKernelGGL(mvc::codec_walk_kernel, dim3((uint32_t)rows), dim3(mvc::kWalkThreads), 0, st, nb, max_bits, B,
+                       maps, max_chunks, entries, counts_out);
     uint64_t bx2 = (max_chunks + mvc::kThreads - 1) / mvc::kThreads;
     if (bx2 > 4096) bx2 = 4096;
     hipLaunchKernelGGL(mvc::codec_emit_kernel, dim3((uint32_t)bx2, (uint32_t)rows), dim3(mvc::kThreads), 0, st,
-                       streams, ld_words, nb, d, (uint32_t)block_len, B, entries, max_chunks, idx_out, ld_idx,
-                       (uint32_t)max_n);
+                       streams, ld_words, nb, max_bits, d, (uint32_t)block_len, B, entries, max_chunks, idx_out,
+                       ld_idx, (uint32_t)max_n);
     return hipGetLastError() == hipSuccess ? MV_OK : MV_ERR_DEVICE;
 }
 

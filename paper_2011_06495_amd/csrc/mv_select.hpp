@@ -12,9 +12,13 @@ namespace mvk {
 
 constexpr int kSelBins = 2048;   // radix-select digit: 11, 10, 10 bits of the 31-bit key
 constexpr int kKeyBins = 4096;   // exact magnitudes inside one fine-histogram bin (1 << kFineShift)
-constexpr int kKeep    = 32;     // candidate keys a thread of mv_row_select can hold in registers
+constexpr int kKeep    = 32;     // candidate keys a thread of the generic select can hold in registers
+constexpr int kRep     = 8;      // copies of the candidates' fine histogram, one per lane % kRep
 constexpr int kTieCap  = 8192;   // ties with the K-th magnitude that fit the LDS list
 constexpr int kRankCap = 256;    // at most this many entries are ranked by counting (quadratic work)
+constexpr int kKeepShort = 32;   // list entries per thread of the two instances of mv_row_select
+constexpr int kKeepLong  = 160;
+constexpr int kSpec    = 32;     // list entries per thread that mv_row_select can fetch ahead of the row's count
 
 __device__ __forceinline__ int      sel_shift(int pass) { return pass == 0 ? 20 : pass == 1 ? 10 : 0; }
 __device__ __forceinline__ uint32_t sel_dmask(int pass) { return pass == 0 ? 2047u : 1023u; }
@@ -39,7 +43,8 @@ __device__ __forceinline__ void tally_digit(uint32_t* hist, bool active, uint32_
 // bin that holds the `want`-th largest entry.  `bin` receives it, `want_in_bin`
 // the rank inside the bin counted from its top (>= 1), `in_bin` the bin's count.
 // Requires 1 <= want <= total count.  All kRowThreads threads must call it.
-template <int BINS>
+// With REP > 1 the histogram is kept in REP copies, bin b's counters at hist[b * REP .. b * REP + REP).
+template <int BINS, int REP = 1>
 __device__ __forceinline__ void find_rank_bin(const uint32_t* hist, uint64_t* scan_lds, uint32_t* bcast,
                                               uint32_t want, uint32_t& bin, uint32_t& want_in_bin,
                                               uint32_t& in_bin)
@@ -49,7 +54,10 @@ __device__ __forceinline__ void find_rank_bin(const uint32_t* hist, uint64_t* sc
     uint32_t s = 0;
 #pragma unroll
     for (int q = 0; q < per; ++q) {
-        h[q] = hist[BINS - 1 - ((int)threadIdx.x * per + q)];
+        const int b = BINS - 1 - ((int)threadIdx.x * per + q);
+        h[q] = 0;
+#pragma unroll
+        for (int r = 0; r < REP; ++r) h[q] += hist[b * REP + r];
         s += h[q];
     }
     uint64_t total;
@@ -147,14 +155,40 @@ __device__ __forceinline__ uint32_t block_radix_select(const Keys& keys, uint32_
 }
 
 // Adds one vote for coordinate j.  Votes are bytes packed four to a word; N <= 255
-// keeps a byte from carrying into its neighbour.  lvl[v] counts coordinates that
-// just reached v votes (so that, summed over all workgroups, lvl[v] = number of
-// coordinates with at least v votes).
+// keeps a byte from carrying into its neighbour.  lvl[v] (LDS, 257 counters) counts
+// coordinates that just reached v votes, so that, summed over all workgroups, lvl[v] =
+// number of coordinates with at least v votes: the mask's vote threshold then follows
+// from N + 1 numbers, and the passes over the vote bytes do work that does not depend
+// on how the votes are spread.
 __device__ __forceinline__ void cast_vote(uint32_t* __restrict__ votes32, uint32_t j, uint32_t* lvl)
 {
     const uint32_t sh = (j & 3u) * 8u;
     const uint32_t old = atomicAdd(&votes32[j >> 2], 1u << sh);
     atomicAdd(&lvl[((old >> sh) & 255u) + 1u], 1u);
+}
+
+// The vote-level counters in memory: kLvlSets sets of 256 that the workgroups take turns
+// over, so that their atomics do not queue up on one cache line.
+constexpr int kLvlSets = 32;
+__device__ __forceinline__ void merge_levels(const uint32_t* lvl, uint32_t* __restrict__ lvl_sets, uint32_t wg)
+{
+    for (uint32_t v = threadIdx.x; v < 256u; v += blockDim.x) {
+        const uint32_t c = lvl[v];
+        if (c) atomicAdd(&lvl_sets[(size_t)(wg % kLvlSets) * 256 + v], c);
+    }
+}
+
+// One slot per lane with `want` set, consecutive within the wavefront: one LDS atomic
+// per wavefront instead of one per entry.  All lanes of the wavefront must call it.
+__device__ __forceinline__ uint32_t wave_slots(bool want, uint32_t* counter, uint32_t lane)
+{
+    const uint64_t m = __ballot(want);
+    if (m == 0ull) return 0u;                              // wave-uniform
+    const int leader = __ffsll((long long)m) - 1;
+    uint32_t base = 0;
+    if (lane == (uint32_t)leader) base = atomicAdd(counter, (uint32_t)__popcll(m));
+    base = __shfl(base, leader, kWave);
+    return base + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
 }
 
 // A candidate (magnitude bits, coordinate) is in the row's top K iff its
@@ -169,6 +203,7 @@ __device__ __forceinline__ bool is_taken(u32x2 c, uint32_t kth, uint32_t tie_cut
 struct SelectLds {
     __attribute__((aligned(16))) uint32_t hist[kKeyBins];   // histograms; then magnitudes of a bin's members
     __attribute__((aligned(16))) uint32_t ties[kTieCap];    // coordinates of a bin's members / of the ties
+    __attribute__((aligned(16))) uint32_t rhist[kFineBins * kRep];   // the candidates' fine histogram, kRep copies
     uint32_t lvl[257];
     uint32_t bcast[3];
     uint32_t n_list;
@@ -266,6 +301,28 @@ __device__ __forceinline__ uint32_t smallest_coordinate(SelectLds& lds, uint32_t
     return kAbsMask - block_radix_select(src, take, lds.hist, lds.scan, lds.bcast, t_eq, n_eq);
 }
 
+// Moves the members of fine-histogram bin `bin` into LDS: magnitude in lds.hist[p],
+// coordinate in lds.ties[p], p = 0 .. in_bin-1 in no particular order.  The slots
+// first receive the members' list positions; their coordinates are then fetched by
+// all lanes together (one round trip, not one per member).  `in_bin` <= kKeyBins.
+template <typename Keys>
+__device__ __forceinline__ void collect_bin_members(const Keys& keys, const u32x2* __restrict__ crow, uint32_t tau,
+                                                    uint32_t bin, uint32_t in_bin, SelectLds& lds)
+{
+    const uint32_t lane = lane_id(), t = threadIdx.x;
+    keys.each([&](uint32_t k, uint64_t i, bool valid) {
+        const bool mine = valid && fine_bin(k, tau) == bin;
+        const uint32_t p = wave_slots(mine, &lds.n_list, lane);
+        if (mine) {
+            lds.hist[p] = k;
+            lds.ties[p] = (uint32_t)i;
+        }
+    });
+    __syncthreads();
+    for (uint32_t p = t; p < in_bin; p += kRowThreads) lds.ties[p] = crow[lds.ties[p]].y;
+    __syncthreads();
+}
+
 // K-th largest magnitude of a row's candidate list and the tie cut.  `keys`
 // delivers the candidates' magnitudes (position i = position in the list crow).
 // Returns through kth / tie_cut; `path` = 0 when the fine histogram sufficed,
@@ -283,25 +340,28 @@ __device__ __forceinline__ void select_among_candidates(const Keys& keys, const 
     if (tau != 0) {
         // All candidates are >= tau and most lie within an octave of it: one
         // histogram of (key - tau) in 2048 bins finds the bin of the K-th largest.
-        for (int b = t; b < kFineBins; b += kRowThreads) lds.hist[b] = 0;
+        // Values on a lattice put thousands of candidates on a few dozen keys, and LDS
+        // atomics of one instruction that meet on one address are served one after the
+        // other: lane l adds to copy l % kRep of the histogram, which divides those queues.
+        {
+            const u32x4 z = {0u, 0u, 0u, 0u};
+            u32x4* rz = reinterpret_cast<u32x4*>(lds.rhist);
+            for (int b = t; b < kFineBins * kRep / 4; b += kRowThreads) rz[b] = z;
+        }
         __syncthreads();
-        // plain atomics: the candidates spread over hundreds of bins here, and the wave-wide
-        // grouping of tally_digit costs more than the few collisions it saves (measured: -2 us)
-        keys.each([&](uint32_t k, uint64_t, bool valid) { if (valid) atomicAdd(&lds.hist[fine_bin(k, tau)], 1u); });
+        MV_STAMP(3, 2);
+        keys.each([&](uint32_t k, uint64_t, bool valid) {
+            if (valid) atomicAdd(&lds.rhist[fine_bin(k, tau) * kRep + (lane & (kRep - 1))], 1u);
+        });
         __syncthreads();
+        MV_STAMP(3, 3);
         uint32_t bin, want, in_bin;
-        find_rank_bin<kFineBins>(lds.hist, lds.scan, lds.bcast, K, bin, want, in_bin);
+        find_rank_bin<kFineBins, kRep>(lds.rhist, lds.scan, lds.bcast, K, bin, want, in_bin);
+        MV_STAMP(3, 4);
         if (in_bin <= (uint32_t)kRankCap) {       // uniform
-            // few candidates in that bin: collect them (magnitude in hist[], coordinate
-            // in ties[]) and rank them by brute force under (magnitude desc, coordinate
-            // asc); the one with exactly want-1 others ahead is the last of the top K
-            keys.each([&](uint32_t k, uint64_t i, bool valid) {
-                if (valid && fine_bin(k, tau) == bin) {
-                    const uint32_t p = atomicAdd(&lds.n_list, 1u);
-                    lds.hist[p] = k;
-                    lds.ties[p] = crow[i].y;
-                }
-            });
+            // few candidates in that bin: rank them by brute force under (magnitude desc,
+            // coordinate asc); the one with exactly want-1 others ahead is the last of the top K
+            collect_bin_members(keys, crow, tau, bin, in_bin, lds);
             if (t < 4) {                          // pad to a multiple of 4 with entries ranked last
                 lds.hist[in_bin + t] = 0;
                 lds.ties[in_bin + t] = 0xFFFFFFFFu;
@@ -328,6 +388,7 @@ __device__ __forceinline__ void select_among_candidates(const Keys& keys, const 
             __syncthreads();
             kth = lds.bcast[0];
             tie_cut = lds.bcast[1];
+            MV_STAMP(3, 5);
             return;
         }
         if (Keys::kCheapPasses && in_bin <= (uint32_t)kKeyBins) {   // uniform; an extra pass only where passes are cheap
@@ -335,14 +396,7 @@ __device__ __forceinline__ void select_among_candidates(const Keys& keys, const 
             // EQUAL magnitudes there: if all members share one key, that key is the K-th
             // largest and only the tie cut is left to find, among coordinates already in LDS.
             if (t < 2) lds.bcast[t] = t ? 0xFFFFFFFFu : 0u;          // max, min of the members' keys
-            keys.each([&](uint32_t k, uint64_t i, bool valid) {
-                if (valid && fine_bin(k, tau) == bin) {
-                    const uint32_t p = atomicAdd(&lds.n_list, 1u);
-                    lds.hist[p] = k;
-                    lds.ties[p] = crow[i].y;
-                }
-            });
-            __syncthreads();
+            collect_bin_members(keys, crow, tau, bin, in_bin, lds);
             for (uint32_t i = t; i < in_bin; i += kRowThreads) {
                 const uint32_t k = lds.hist[i];
                 if (k != lds.hist[0]) {                              // any writer will do: both end up != hist[0]
@@ -354,9 +408,11 @@ __device__ __forceinline__ void select_among_candidates(const Keys& keys, const 
             const bool one_key = lds.bcast[0] == 0u && lds.bcast[1] == 0xFFFFFFFFu;   // nobody differed from hist[0]
             const uint32_t the_key = lds.hist[0];
             __syncthreads();
+            MV_STAMP(3, 6);
             if (one_key) {                                           // uniform
                 kth = the_key;
                 tie_cut = want < in_bin ? smallest_coordinate(lds, in_bin, want) : 0xFFFFFFFFu;
+                MV_STAMP(3, 7);
                 return;
             }
             if (t == 0) lds.n_list = 0;                              // distinct keys: go on below
@@ -387,8 +443,12 @@ __device__ __forceinline__ void select_among_candidates(const Keys& keys, const 
     if (take_eq < n_eq) {                         // uniform
         if (n_eq <= (uint32_t)kTieCap) {
             keys.each([&](uint32_t k, uint64_t i, bool valid) {
-                if (valid && k == kth) lds.ties[atomicAdd(&lds.n_list, 1u)] = crow[i].y;
+                const bool mine = valid && k == kth;
+                const uint32_t p = wave_slots(mine, &lds.n_list, lane);
+                if (mine) lds.ties[p] = (uint32_t)i;
             });
+            __syncthreads();
+            for (uint32_t p = t; p < n_eq; p += kRowThreads) lds.ties[p] = crow[lds.ties[p]].y;
             __syncthreads();
             tie_cut = smallest_coordinate(lds, n_eq, take_eq);
         } else {
@@ -405,56 +465,335 @@ __device__ __forceinline__ void select_among_candidates(const Keys& keys, const 
     }
 }
 
-// One workgroup per row.
-// Usual case: an exact select over the row's candidate list gives the K-th
-// largest magnitude kth[row] and tie_cut[row], the largest coordinate taken
-// among the candidates tied with it (0xFFFFFFFF: all ties taken).
-// If the candidate count is < K or overflowed the list (for instance a row of
-// equal magnitudes), the row is instead selected exactly from memory (e already
-// holds a = g + e), and its vote is emitted and cast here; slow_flag[row] = 1
-// tells the later kernels to skip the row.
-__global__ __launch_bounds__(kRowThreads) void mv_row_select(
-    const float* __restrict__ e, int64_t ld_e, int64_t d, uint32_t K,
-    const u32x2* __restrict__ cand, uint32_t cap, const uint32_t* __restrict__ row_count,
-    const uint32_t* __restrict__ tau_bits,
-    uint32_t* __restrict__ kth_out, uint32_t* __restrict__ tie_cut_out,
-    uint32_t* __restrict__ worker_idx, uint32_t* __restrict__ votes32,
-    uint32_t* __restrict__ cnt_ge, uint32_t* __restrict__ slow_flag, int thresholds_only, int slow_rows_only)
+// Casts the votes of the list entries i with (i / kRowThreads) % parts == part:
+// a taken candidate adds one to its coordinate's vote byte and, when the sorted
+// vote lists are wanted (ssel != nullptr), is tallied in its 1024-coordinate
+// segment (ssel was zeroed by the streaming pass).  Lanes of a wavefront hold
+// consecutive list entries, which mostly share a segment (they are one run): the
+// first lane of each group of equal segments adds the group's count.  All threads of
+// the workgroup must call it.
+template <int NT>
+__device__ __forceinline__ void cast_votes_of_share(const u32x2* __restrict__ crow, uint32_t C, uint32_t kth,
+                                                    uint32_t tie_cut, uint32_t part, uint32_t parts,
+                                                    uint32_t* __restrict__ votes32, uint32_t* lvl,
+                                                    uint32_t* __restrict__ ssel)
 {
-    __shared__ SelectLds lds;
-    const uint32_t row = blockIdx.x, t = threadIdx.x;
-    if (slow_rows_only) {                         // the candidate lists are selected by the mv_sel_* kernels
-        const uint32_t C0 = row_count[row * kCounterStride];
-        if (C0 >= K && C0 <= cap) return;         // whole workgroup
-    }
-    // The first kKeep * kRowThreads list entries are fetched before the row's
-    // candidate count is known (the list's storage holds cap entries; what lies at
-    // or beyond the count is ignored later), so the two loads do not queue up.
-    const u32x2* crow = cand + (size_t)row * cap;
-    uint32_t k[kKeep];
+    constexpr int kU = 4;                         // list entries per thread whose loads are in flight together
+    const uint32_t t = threadIdx.x, lane = lane_id();
+    for (uint64_t q0 = part; q0 * NT < C; q0 += (uint64_t)parts * kU) {
+        u32x2 c[kU];
 #pragma unroll
-    for (int q = 0; q < kKeep; ++q) {
-        k[q] = crow[min((uint32_t)q * kRowThreads + t, cap - 1)].x;
+        for (int u = 0; u < kU; ++u) {
+            const uint64_t i = (q0 + (uint64_t)u * parts) * NT + t;
+            const u32x2 none = {0u, 0xFFFFFFFFu};
+            c[u] = (i < C) ? crow[i] : none;
+        }
+#pragma unroll
+        for (int u = 0; u < kU; ++u) {
+            if ((q0 + (uint64_t)u * parts) * NT >= C) break;        // uniform over the workgroup
+            const bool taken = c[u].y != 0xFFFFFFFFu && is_taken(c[u], kth, tie_cut);
+            if (taken) cast_vote(votes32, c[u].y, lvl);
+            if (ssel) {
+                const uint32_t sg = c[u].y / kSeg;
+                const uint32_t prev = __shfl_up(sg, 1, kWave);
+                const uint64_t heads = __ballot(lane == 0 || sg != prev);
+                const uint64_t tk = __ballot(taken);
+                if (heads & (1ull << lane)) {
+                    const uint64_t above = (lane == kWave - 1) ? 0ull : (heads >> (lane + 1));
+                    const uint32_t len = above ? (uint32_t)__ffsll((long long)above) : (kWave - lane);
+                    const uint64_t span = (len >= 64 ? ~0ull : ((1ull << len) - 1)) << lane;
+                    const uint32_t n = (uint32_t)__popcll(tk & span);
+                    if (n) atomicAdd(&ssel[sg], n);
+                }
+            }
+        }
+    }
+}
+
+// ---- the rows' select from registers ------------------------------------------
+// A thread keeps, for each of its list entries, only the number of the entry's bin
+// in the fine histogram (16 bits, two to a register; 0xFFFF: no entry): that is all
+// the histogram pass and the search for the bin's members need, and it lets one
+// workgroup hold lists of KEEP * 1024 entries.  The members of the bin that holds
+// the K-th largest are then fetched from the list by position, all lanes together.
+template <int KEEP>
+struct PackedBins {
+    uint32_t b[KEEP / 2];
+    __device__ __forceinline__ void clear()
+    {
+#pragma unroll
+        for (int q = 0; q < KEEP / 2; ++q) b[q] = 0xFFFFFFFFu;
+    }
+    template <int Q>
+    __device__ __forceinline__ void set(uint32_t bin)
+    {
+        if (Q & 1) b[Q / 2] = (b[Q / 2] & 0x0000FFFFu) | (bin << 16);
+        else       b[Q / 2] = (b[Q / 2] & 0xFFFF0000u) | bin;
+    }
+    // f(bin, list position) for every entry slot below `count`, the same number of
+    // times in every lane of the workgroup
+    template <typename F>
+    __device__ __forceinline__ void each(uint32_t count, F f) const
+    {
+#pragma unroll
+        for (int q = 0; q < KEEP; ++q) {
+            if ((uint32_t)q * kRowThreads < count) {              // uniform over the workgroup
+                const uint32_t bin = (q & 1) ? (b[q / 2] >> 16) : (b[q / 2] & 0xFFFFu);
+                f(bin, (uint32_t)q * kRowThreads + threadIdx.x);
+            }
+        }
+    }
+};
+
+// Exact K-th largest magnitude and tie cut of a candidate list whose entries' bins
+// are in registers.  Returns false when the bin of the K-th largest holds more
+// members than the LDS lists take (the caller then runs the generic select).
+// LDS use: rhist holds the histogram, then (words [0, 4096)) the members' magnitudes,
+// ([4096, 8192)) their coordinates, ([8192, 12288)) the histogram of their exact keys.
+template <int KEEP>
+__device__ __forceinline__ bool select_from_bins(const PackedBins<KEEP>& bins, const u32x2* __restrict__ crow,
+                                                 uint32_t C, uint32_t K, uint32_t tau, SelectLds& lds,
+                                                 uint32_t& kth, uint32_t& tie_cut)
+{
+    static_assert(kFineBins * kRep >= 3 * kKeyBins, "the members' lists reuse the histogram's storage");
+    const uint32_t lane = lane_id(), t = threadIdx.x;
+    // (the caller has zeroed lds.rhist and lds.n_list, and a barrier has passed since)
+    MV_STAMP(3, 2);
+    // Values on a lattice put thousands of candidates on a few dozen keys, and LDS
+    // atomics of one instruction that meet on one address are served one after the
+    // other: lane l adds to copy l % kRep of the histogram, which divides those queues.
+    bins.each(C, [&](uint32_t bin, uint32_t) {
+        if (bin != 0xFFFFu) atomicAdd(&lds.rhist[bin * kRep + (lane & (kRep - 1))], 1u);
+    });
+    __syncthreads();
+    MV_STAMP(3, 3);
+    uint32_t bin, want, in_bin;
+    find_rank_bin<kFineBins, kRep>(lds.rhist, lds.scan, lds.bcast, K, bin, want, in_bin);
+    MV_STAMP(3, 4);
+    if (in_bin > (uint32_t)kKeyBins) return false;                  // uniform
+    // the last bin is open-ended: its members' keys do not fit the exact-key histogram
+    if (in_bin > (uint32_t)kRankCap && bin == (uint32_t)(kFineBins - 1)) return false;
+
+    uint32_t* mkey = lds.rhist;                   // find_rank_bin ended with a barrier: the histogram is free
+    uint32_t* mpos = lds.rhist + kKeyBins;
+    {
+        // the members' list positions, in no particular order: count, scan, place
+        uint32_t mine = 0;
+        bins.each(C, [&](uint32_t b, uint32_t) { mine += (b == bin); });
+        uint64_t total;
+        uint32_t p = (uint32_t)block_excl_scan64<kRowThreads>(mine, lds.scan, total);
+        if (mine) bins.each(C, [&](uint32_t b, uint32_t i) { if (b == bin) mpos[p++] = i; });
+    }
+    __syncthreads();
+    for (uint32_t p = t; p < in_bin; p += kRowThreads) {             // all lanes together: one round trip
+        const u32x2 c = crow[mpos[p]];
+        mkey[p] = c.x;
+        mpos[p] = c.y;                            // from here on: the member's coordinate
+    }
+    __syncthreads();
+    MV_STAMP(3, 5);
+    if (in_bin <= (uint32_t)kRankCap) {           // uniform
+        // few members: ranked by counting under (magnitude desc, coordinate asc);
+        // the one with exactly want-1 others ahead is the last of the top K
+        if (t < 4) {                              // pad to a multiple of 4 with entries ranked last
+            mkey[in_bin + t] = 0;
+            mpos[in_bin + t] = 0xFFFFFFFFu;
+        }
+        __syncthreads();
+        if (t < in_bin) {
+            const uint32_t mk = mkey[t], mi = mpos[t];
+            const u32x4* hk = reinterpret_cast<const u32x4*>(mkey);
+            const u32x4* hi = reinterpret_cast<const u32x4*>(mpos);
+            uint32_t ahead = 0;
+#pragma unroll 4
+            for (uint32_t j = 0; j < (in_bin + 3) / 4; ++j) {
+                const u32x4 ok = hk[j], oi = hi[j];
+                ahead += (ok.x > mk) || (ok.x == mk && oi.x < mi);
+                ahead += (ok.y > mk) || (ok.y == mk && oi.y < mi);
+                ahead += (ok.z > mk) || (ok.z == mk && oi.z < mi);
+                ahead += (ok.w > mk) || (ok.w == mk && oi.w < mi);
+            }
+            if (ahead == want - 1) {
+                lds.bcast[0] = mk;
+                lds.bcast[1] = mi;
+            }
+        }
+        __syncthreads();
+        kth = lds.bcast[0];
+        tie_cut = lds.bcast[1];
+        __syncthreads();
+        MV_STAMP(3, 6);
+        return true;
+    }
+    // Values on a lattice put hundreds of EQUAL magnitudes there: if all members share one
+    // key, that key is the K-th largest and only the tie cut is left to find.
+    if (t == 0) lds.bcast[2] = 0;
+    __syncthreads();
+    {
+        bool differs = false;
+        const uint32_t k0 = mkey[0];
+        for (uint32_t p = t; p < in_bin; p += kRowThreads) {
+            differs |= mkey[p] != k0;
+            lds.ties[p] = mpos[p];                // in_bin <= kKeyBins <= kTieCap
+        }
+        if (differs) lds.bcast[2] = 1;
+    }
+    __syncthreads();
+    if (lds.bcast[2] == 0) {                      // uniform
+        kth = mkey[0];
+        __syncthreads();                          // everyone has read bcast and mkey
+        tie_cut = want < in_bin ? smallest_coordinate(lds, in_bin, want) : 0xFFFFFFFFu;
+        MV_STAMP(3, 7);
+        return true;
+    }
+    // up to 4096 members: the bin spans exactly 4096 key values, so a histogram over the
+    // members' exact keys finds the K-th largest, and its ties' coordinates are in LDS
+    uint32_t* h2 = lds.rhist + 2 * kKeyBins;
+    const uint32_t bin_lo = tau + (bin << kFineShift);
+    for (int b = t; b < kKeyBins; b += kRowThreads) h2[b] = 0;
+    __syncthreads();
+    for (uint32_t p0 = 0; p0 < in_bin; p0 += kRowThreads) {          // wave-wide grouping: many keys are equal
+        const uint32_t p = p0 + t;
+        tally_digit(h2, p < in_bin, p < in_bin ? (mkey[p] - bin_lo) & (uint32_t)(kKeyBins - 1) : 0u, lane);
+    }
+    __syncthreads();
+    uint32_t sub, take_eq, n_eq;
+    find_rank_bin<kKeyBins>(h2, lds.scan, lds.bcast, want, sub, take_eq, n_eq);
+    kth = bin_lo + sub;
+    tie_cut = 0xFFFFFFFFu;
+    if (take_eq < n_eq) {                         // uniform: only the take_eq lowest coordinates of the ties
+        if (t == 0) lds.n_list = 0;
+        __syncthreads();
+        for (uint32_t p0 = 0; p0 < in_bin; p0 += kRowThreads) {
+            const uint32_t p = p0 + t;
+            const bool mine = p < in_bin && mkey[p] == kth;
+            const uint32_t s = wave_slots(mine, &lds.n_list, lane);
+            if (mine) lds.ties[s] = mpos[p];
+        }
+        __syncthreads();
+        tie_cut = smallest_coordinate(lds, n_eq, take_eq);
+    }
+    MV_STAMP(3, 7);
+    return true;
+}
+
+// parts workgroups per row; the grid is one-dimensional and workgroup ids are laid
+// out so that the workgroups of one row have equal id % 8: consecutive ids go to
+// different XCDs (each with an L2 of its own), so a row's list is then read from
+// memory once and served to the row's other workgroups from that L2.
+// Usual case: EVERY workgroup of a row runs the same exact select over the row's
+// candidate list (the work is repeated rather than shared so that no workgroup
+// waits for another): the K-th largest magnitude kth[row] and tie_cut[row], the
+// largest coordinate taken among the candidates tied with it (0xFFFFFFFF: all ties
+// taken).  Each workgroup then casts the votes of its share of the list.  With
+// thresholds_only (add-drop voting) no vote is cast; with slow_rows_only the
+// candidate lists are selected by the mv_sel_* kernels and their votes cast by
+// mv_row_votes.
+// If the candidate count is < K or overflowed the list (for instance a row of
+// equal magnitudes), the row's first workgroup selects it exactly from memory (e
+// already holds a = g + e), emits and casts its vote; slow_flag[row] = 1 tells the
+// later kernels to skip the row.
+// n_spec (<= kSpec): how many of a thread's list entries are fetched before the
+// row's count is known (the list's storage holds cap entries; what lies at or
+// beyond the count is ignored), so that the two loads do not queue up.
+template <int KEEP>
+__global__ __launch_bounds__(kRowThreads) void mv_row_select(
+    const float* __restrict__ e, int64_t ld_e, int64_t d, uint32_t N, uint32_t K,
+    const u32x2* __restrict__ cand, uint32_t cap, const uint32_t* __restrict__ row_count_sets,
+    uint32_t row_count_set_words, const uint32_t* __restrict__ step_no,
+    const unsigned long long* __restrict__ tau_pub, const uint32_t* __restrict__ row_poison,
+    uint32_t* __restrict__ cand_count, uint32_t* __restrict__ tau_bits, uint32_t* __restrict__ kth_out, uint32_t* __restrict__ tie_cut_out,
+    uint32_t* __restrict__ worker_idx, uint32_t* __restrict__ votes32,
+    uint32_t* __restrict__ seg_sel, uint32_t nseg, uint32_t* __restrict__ lvl_sets,
+    uint32_t* __restrict__ slow_flag, uint32_t parts, uint32_t n_spec, int thresholds_only, int slow_rows_only)
+{
+    MV_SPAN(3);
+    __shared__ SelectLds lds;
+    const uint32_t t = threadIdx.x;
+    const uint32_t within = blockIdx.x % (8u * parts);
+    const uint32_t row = (blockIdx.x / (8u * parts)) * 8u + within % 8u, part = within / 8u;
+    if (row >= N) return;                         // whole workgroup
+    const u32x2* crow = cand + (size_t)row * cap;
+    MV_STAMP(3, 0);
+    uint32_t raw[kSpec];
+#pragma unroll
+    for (int q = 0; q < kSpec; ++q) {
+        raw[q] = 0;
+        if ((uint32_t)q < n_spec) raw[q] = crow[min((uint32_t)q * kRowThreads + t, cap - 1)].x;
         if ((q & 7) == 7) __builtin_amdgcn_sched_barrier(0);   // keep address arithmetic from piling up
     }
-    const uint32_t C = row_count[row * kCounterStride];
-    const uint32_t tau = tau_bits[row];           // with the count, not after it
+    // (the streaming kernel counted into the counter set of this step's parity)
+    const uint32_t epoch = step_no[0] + 1u;
+    uint32_t C = row_count_sets[(epoch & 1u) * row_count_set_words + row * kCounterStride];
+    const uint32_t tau = (uint32_t)tau_pub[row * (kCounterStride / 2)];   // with the count, not after it
+    // a row whose streaming wavefronts did not all see tau in time: its list is incomplete
+    const bool poisoned = row_poison[row] == epoch;
+    // the fine histogram is cleared while those loads are under way
+    {
+        const u32x4 z = {0u, 0u, 0u, 0u};
+        u32x4* rz = reinterpret_cast<u32x4*>(lds.rhist);
+        for (int b = t; b < kFineBins * kRep / 4; b += kRowThreads) rz[b] = z;
+        if (t == 0) lds.n_list = 0;
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    __syncthreads();
+    MV_STAMP(3, 1);
+    if (poisoned) C = kRowPoison | C;             // reads as overflowed, here and for every later reader
+    if (part == 0 && t == 0) {                    // for the kernels that follow, and the row statistics
+        cand_count[row] = C;
+        tau_bits[row] = tau;
+        slow_flag[row] = 0;
+    }
+    const bool from_list = C >= K && C <= cap;
+    if (slow_rows_only && from_list) return;      // whole workgroup
+    if (!from_list && part != 0) return;          // whole workgroup
 
-    if (C >= K && C <= cap) {
-        uint32_t kth, tie_cut, path;
-        if (C <= (uint32_t)kKeep * kRowThreads) {
-            const KeysInRegs src{k, C};
-            select_among_candidates(src, crow, C, K, tau, lds, kth, tie_cut, path);
-        } else {
+    if (from_list) {
+        uint32_t kth = 0, tie_cut = 0, path = 0;
+        bool done = false;
+        if (tau != 0 && C <= (uint32_t)KEEP * kRowThreads) {
+            PackedBins<KEEP> bins;
+            bins.clear();
+            auto pack = [&](auto qc, uint32_t key) {
+                constexpr int Q = decltype(qc)::value;
+                const uint32_t i = (uint32_t)Q * kRowThreads + t;
+                bins.template set<Q>(i < C ? fine_bin(key, tau) : 0xFFFFu);
+            };
+            // what was fetched ahead, then the rest of the list
+            static_for<0, (KEEP < kSpec ? KEEP : kSpec)>([&](auto qc) {
+                constexpr int Q = decltype(qc)::value;
+                if ((uint32_t)Q < n_spec && (uint32_t)Q * kRowThreads < C) pack(qc, raw[Q]);
+            });
+            static_for<0, KEEP>([&](auto qc) {
+                constexpr int Q = decltype(qc)::value;
+                if ((uint32_t)Q >= n_spec && (uint32_t)Q * kRowThreads < C)
+                    pack(qc, crow[min((uint32_t)Q * kRowThreads + t, cap - 1)].x);
+            });
+            done = select_from_bins<KEEP>(bins, crow, C, K, tau, lds, kth, tie_cut);
+        }
+        if (!done) {                              // uniform
+            __syncthreads();
+            path = 2;
             auto at = [crow](uint64_t i) { return crow[i].x; };
             const KeysInMemory<decltype(at)> src{at, C};
-            select_among_candidates(src, crow, C, K, tau, lds, kth, tie_cut, path);
+            uint32_t p2;
+            select_among_candidates(src, crow, C, K, tau, lds, kth, tie_cut, p2);
         }
-        if (t == 0) {
+        if (part == 0 && t == 0) {
             kth_out[row] = kth;
             tie_cut_out[row] = tie_cut;
             if (path) slow_flag[row] = path;      // diagnostic only
         }
+        MV_STAMP(3, 8);
+        if (!thresholds_only) {
+            for (int i = t; i < 257; i += kRowThreads) lds.lvl[i] = 0;
+            __syncthreads();
+            cast_votes_of_share<kRowThreads>(crow, C, kth, tie_cut, part, parts, votes32, lds.lvl,
+                                             seg_sel ? seg_sel + (size_t)row * nseg : nullptr);
+            __syncthreads();
+            merge_levels(lds.lvl, lvl_sets, blockIdx.x);
+        }
+        MV_STAMP(3, 9);
         return;
     }
 
@@ -488,14 +827,14 @@ __global__ __launch_bounds__(kRowThreads) void mv_row_select(
     uint32_t gt_before = 0, eq_before = 0;
     for (int64_t j0 = 0; j0 < d; j0 += (int64_t)kRowThreads * 4) {
         const int64_t j = j0 + (int64_t)t * 4;
-        uint32_t k[4];
+        uint32_t kk[4];
         uint32_t gt = 0, eq = 0;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             const bool valid = (j + c < d);
-            k[c] = valid ? (__float_as_uint(arow[j + c]) & kAbsMask) : 0u;
-            gt += (valid && k[c] > kth);
-            eq += (valid && k[c] == kth);
+            kk[c] = valid ? (__float_as_uint(arow[j + c]) & kAbsMask) : 0u;
+            gt += (valid && kk[c] > kth);
+            eq += (valid && kk[c] == kth);
         }
         uint64_t total;
         const uint64_t ex = block_excl_scan64<kRowThreads>(pack2(gt, eq), lds.scan, total);
@@ -503,7 +842,7 @@ __global__ __launch_bounds__(kRowThreads) void mv_row_select(
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             if (j + c < d) {
-                const bool is_gt = k[c] > kth, is_eq = k[c] == kth;
+                const bool is_gt = kk[c] > kth, is_eq = kk[c] == kth;
                 if (is_gt || (is_eq && e0 < take_eq)) {
                     const uint32_t pos = g0 + min(e0, take_eq);
                     if (out && pos < K) out[pos] = (uint32_t)(j + c);
@@ -517,11 +856,7 @@ __global__ __launch_bounds__(kRowThreads) void mv_row_select(
         eq_before += (uint32_t)total;
         __syncthreads();   // lds.scan is reused by the next round
     }
-    __syncthreads();
-    for (int i = t; i < 256; i += kRowThreads) {
-        const uint32_t c = lds.lvl[i];
-        if (c) atomicAdd(&cnt_ge[(size_t)row * 256 + i], c);
-    }
+    merge_levels(lds.lvl, lvl_sets, blockIdx.x);
 }
 
 // ---- exact select over a long list with many workgroups ----------------------
@@ -669,7 +1004,8 @@ __device__ __forceinline__ bool list_rank_body(const ListSelect& a, uint32_t row
         const uint32_t last = C - 1;
 #pragma unroll
         for (int q = 0; q < kKeep; ++q) {
-            k[q] = list2[min((uint32_t)q * kRowThreads + t, last)].x;
+            k[q] = 0;
+            if ((uint32_t)q * kRowThreads < C) k[q] = list2[min((uint32_t)q * kRowThreads + t, last)].x;
             if ((q & 7) == 7) __builtin_amdgcn_sched_barrier(0);
         }
         const KeysInRegs src{k, C};
@@ -685,11 +1021,13 @@ __device__ __forceinline__ bool list_rank_body(const ListSelect& a, uint32_t row
 // ---- the rows' top-K when K is large (grid: blocks of the candidate list x rows)
 __global__ __launch_bounds__(kRowThreads) void mv_sel_hist(ListSelect a)
 {
+    MV_SPAN(8);
     __shared__ uint32_t hist[kSelBins];
     list_hist_body(a, blockIdx.y, hist);
 }
 __global__ __launch_bounds__(kRowThreads) void mv_sel_split(ListSelect a)
 {
+    MV_SPAN(9);
     __shared__ ListSplitLds lds;
     list_split_body(a, blockIdx.y, lds, nullptr);
 }
@@ -697,6 +1035,7 @@ __global__ __launch_bounds__(kRowThreads) void mv_sel_rank(ListSelect a, uint32_
                                                            uint32_t* __restrict__ tie_cut_out,
                                                            uint32_t* __restrict__ slow_flag)
 {
+    MV_SPAN(10);
     __shared__ SelectLds lds;
     const uint32_t row = blockIdx.x;
     uint32_t kth, tie_cut, path;

@@ -95,3 +95,55 @@ def test_codec_on_the_lists_of_a_vote_step(oracle):
     gpu_codec_round_trip(oracle, lists, w.d, block_len, w.K)
     bits = B.mv_codec_stream_bits(w.K, w.d, block_len)
     assert abs(bits / w.K - oracle.bits_per_position(block_len)) < 0.01       # log2(1/phi) + 2 per position
+
+
+def test_codec_lengths_from_the_wire_are_clamped(oracle):
+    """A received stream length above max_bits, or a list count above n, is wire-side
+    data the host cannot validate: the kernels read it as the maximum, and nothing
+    outside the scratch, the streams or the lists is written (guard bands on all)."""
+    dev = torch.device("cuda:0")
+    d, L, n, rows = 50000, 100, 600, 3
+    say("codec oversized lengths d=%d block=%d n=%d rows=%d" % (d, L, n, rows))
+    rng = np.random.default_rng(11)
+    lists = [np.sort(rng.choice(d, n, replace=False)).astype(np.uint32) for _ in range(rows)]
+    max_bits = B.mv_codec_stream_bits(n, d, L)
+    max_words = (max_bits + 31) // 32
+    guard_rows = 2
+
+    # ---- encoder: counts beyond n are read as n
+    idx = torch.full((rows + guard_rows, n), 7, dtype=torch.int32, device=dev)   # guard rows: readable, valid coordinates
+    for r, l in enumerate(lists):
+        idx[r] = torch.from_numpy(l.astype(np.int64)).to(torch.int32)
+    counts = torch.tensor([n + 5, 0x7FFFFFFF, n], dtype=torch.int32, device=dev)
+    streams = torch.full((rows + guard_rows, max_words), 0x5A5A5A5A, dtype=torch.int32, device=dev)
+    n_bits = torch.zeros(rows, dtype=torch.int64, device=dev)
+    B.mv_codec_encode(idx[:rows], n, d, L, streams[:rows], n_bits, counts=counts)
+    torch.cuda.synchronize()
+    got = streams.cpu().numpy().view(np.uint32)
+    assert np.all(got[rows:] == 0x5A5A5A5A), "the encoder wrote past the last stream"
+    for r, l in enumerate(lists):
+        words, nb = oracle.codec_encode(l, d, L)
+        assert int(n_bits[r]) == nb == max_bits
+        assert np.array_equal(got[r, : (nb + 31) // 32], words[: (nb + 31) // 32]), "row %d" % r
+
+    # ---- decoder: lengths beyond max_bits are read as max_bits
+    nbytes = B.mv_codec_scratch_bytes(max_bits, rows)
+    band = 4096
+    raw = torch.full((nbytes + 2 * band + 256,), 0xA5, dtype=torch.uint8, device=dev)
+    off = band + (-(raw.data_ptr() + band)) % 256
+    scratch = raw[off: off + nbytes]
+    long_bits = torch.tensor([max_bits + 1000, 1 << 40, max_bits], dtype=torch.int64, device=dev)
+    out = torch.full((rows + guard_rows, n), -1, dtype=torch.int32, device=dev)
+    cnt = torch.full((rows + GUARD_COUNTS,), -7, dtype=torch.int32, device=dev)
+    B.mv_codec_decode(streams[:rows], long_bits, max_bits, d, L, out[:rows], n, cnt[:rows], scratch)
+    torch.cuda.synchronize()
+    r_host = raw.cpu().numpy()
+    assert np.all(r_host[:off] == 0xA5) and np.all(r_host[off + nbytes:] == 0xA5), "write outside the decoder's scratch"
+    o = out.cpu().numpy().view(np.uint32)
+    c = cnt.cpu().numpy()
+    assert np.all(o[rows:] == 0xFFFFFFFF) and np.all(c[rows:] == -7)
+    for r, l in enumerate(lists):
+        assert c[r] == n and np.array_equal(o[r], l), "row %d decoded from a clamped length" % r
+
+
+GUARD_COUNTS = 8

@@ -260,7 +260,7 @@ def test_every_route_of_the_row_select(oracle, case):
     """Rows built to drive mv_row_select down each of its routes: crowded
     histogram bins (equal magnitudes), tie groups small / large / larger than the
     LDS list, a K-th magnitude more than an octave above the estimate, and a
-    candidate list longer than the register file holds."""
+    candidate list that needs the kernel's instance with more list entries per thread."""
     rng = np.random.default_rng(sum(map(ord, case)))
     N, d, K = 3, 300007, 3000
     if case == "ties_in_lds_by_counting":
@@ -272,7 +272,7 @@ def test_every_route_of_the_row_select(oracle, case):
     elif case == "kth_far_above_threshold":
         groups = [(3500, 8.0, 16.0), (2600, 1.0, 1.1)]          # > K coordinates beyond 2 tau
     else:
-        N, d, K = 2, 400003, 20000                              # about 2K = 40000 candidates per row
+        N, d, K = 2, 600011, 40000                              # about 46000 candidates per row
         groups = []
     say("select route %s N=%d d=%d K=%d" % (case, N, d, K))
     if groups:
@@ -297,16 +297,17 @@ def test_every_route_of_the_row_select(oracle, case):
 
 @pytest.mark.parametrize("case", ["normal", "lattice_ties", "kth_far_above_threshold"])
 def test_long_candidate_lists_are_selected_by_many_workgroups(oracle, case):
-    """K above 32768: about 2K candidates per row, selected by the histogram / split /
-    rank kernels instead of one workgroup per row."""
+    """Candidate lists longer than a workgroup of mv_row_select keeps in registers
+    (about 240,000 per row here): selected by the histogram / split / rank kernels,
+    many workgroups per row, their votes cast by mv_row_votes."""
     rng = np.random.default_rng(sum(map(ord, case)))
-    N, d, K = 3, 600011, 40000
+    N, d, K = 3, 1500007, 220000
     if case == "normal":
         g = rng.standard_normal((N, d)).astype(np.float32)
     elif case == "lattice_ties":
         g = (np.round(rng.standard_normal((N, d)) * 24.0) / 64.0).astype(np.float32)   # about 200 distinct magnitudes
     else:
-        g = np.stack([_levels_row(rng, d, [(45000, 8.0, 16.0), (30000, 1.0, 1.1)]) for _ in range(N)])
+        g = np.stack([_levels_row(rng, d, [(240000, 8.0, 16.0), (150000, 1.0, 1.1)]) for _ in range(N)])
     e = np.zeros_like(g)
     say("many-workgroup select %s N=%d d=%d K=%d" % (case, N, d, K))
     with GpuStepper(N, d, K) as gs:
@@ -318,6 +319,7 @@ def test_long_candidate_lists_are_selected_by_many_workgroups(oracle, case):
     say("  candidates %s path %s" % (cand, path))
     assert_matches_oracle(got, oracle.vote_step(g, e, K), case)
     assert all(p != 1 for p in path), "these rows are meant for the candidate-list routes"
+    assert min(cand) > 160 * 1024, "these lists are meant to be longer than one workgroup keeps"
 
 
 def test_tie_cut_inside_a_run_of_neighbouring_ties(oracle):
