@@ -59,7 +59,7 @@ struct Plan {
     uint32_t m_target;          // sampled coordinates that must lie at or above the threshold bin
     uint32_t cap;               // candidate list capacity per row
     uint32_t n_vote_blocks;     // workgroups of the mask kernels: blocks of 16384 vote_q coordinates
-    uint32_t vote_q;            // 1, 2 or 4 quads of 16 vote bytes per thread of the mask kernels
+    uint32_t vote_q;            // quads of 16 vote bytes per thread of the mask kernels (1, 2, 3, 4, 6 or 8)
     uint32_t rs_blocks;         // workgroups of mv_rs_keys: blocks of kVoteBlock coordinates
     uint32_t list_blocks;       // workgroups per row that walk a candidate list, one thread per entry
     uint32_t vote_blocks;       // workgroups per row of mv_row_votes
@@ -152,10 +152,12 @@ Plan make_plan(const mv_config* c)
 
     p.rs_blocks = (uint32_t)((p.d + mvk::kVoteBlock - 1) / mvk::kVoteBlock);
     {
-        // the mask kernels: as few vote bytes per thread as keep the grid within one round of workgroups
-        // (one workgroup of 1024 threads per compute unit, some of them taken by the segment scans)
-        uint32_t q = 1;
-        while (q < 4 && (uint64_t)p.d > 440ull * mvk::kMaskThreads * 16 * q) q *= 2;
+        // the mask kernels: as few vote bytes per thread as keep the grid at a few hundred workgroups (measured:
+        // 32 bytes per thread and 342 workgroups beat 64 bytes and 171; the work per thread is what costs)
+        static const uint32_t kQs[] = {1, 2, 3, 4, 6, 8};
+        uint32_t q = 8;
+        for (uint32_t cand_q : kQs)
+            if ((uint64_t)p.d <= 440ull * mvk::kMaskThreads * 16 * cand_q) { q = cand_q; break; }
         p.vote_q = q;
         const uint64_t per = (uint64_t)mvk::kMaskThreads * 16 * q;
         p.n_vote_blocks = (uint32_t)(((uint64_t)p.d + per - 1) / per);
@@ -608,7 +610,7 @@ mv_status enqueue_step(mv_ctx* c, const StepArgs& a, void* stream_v)
     // votes and the clearing of the vote words remain)
     const bool lists = sorted && !add_drop;
     {
-        const dim3 grid_c(p.n_vote_blocks + (lists ? p.N * p.scan_parts : 0)), grid_e(p.n_vote_blocks);
+        const dim3 grid_c(p.n_vote_blocks + (lists ? p.N : 0)), grid_e(p.n_vote_blocks);
         const dim3 block(mvk::kMaskThreads);
         uint8_t* votes_out = add_drop ? nullptr : a.votes;
         uint32_t* mask_out = random_sel ? (uint32_t*)nullptr : a.mask_idx;
@@ -623,18 +625,30 @@ mv_status enqueue_step(mv_ctx* c, const StepArgs& a, void* stream_v)
         hipLaunchKernelGGL(mvk::mv_mask_emit<Q>, grid_e, block, 0, st, mask_votes32, p.d, p.K, votethr, blockcnt, \
                            mask_out, clear);                                                                     \
         after(KID_MASK_EMIT);
-        if (p.vote_q == 1) { MV_LAUNCH_MASK(1) } else if (p.vote_q == 2) { MV_LAUNCH_MASK(2) } else { MV_LAUNCH_MASK(4) }
+        switch (p.vote_q) {
+            case 1: { MV_LAUNCH_MASK(1) } break;
+            case 2: { MV_LAUNCH_MASK(2) } break;
+            case 3: { MV_LAUNCH_MASK(3) } break;
+            case 4: { MV_LAUNCH_MASK(4) } break;
+            case 6: { MV_LAUNCH_MASK(6) } break;
+            default: { MV_LAUNCH_MASK(8) } break;
+        }
 #undef MV_LAUNCH_MASK
     }
     // 6. gather + mean + error update; extra workgroups write the sorted vote lists beside it
     {
         const float inv_n = 1.0f / (float)p.N;
         const uint32_t kb = mvk::kMaskThreads / p.N;
-        const uint32_t n_gather = (p.K + kb - 1) / kb;
+        // up to four rounds of kb coordinates per workgroup, as few as keep the grid at about a thousand workgroups
+        // (more work per thread measured no faster below that)
+        uint32_t rounds = (uint32_t)(((uint64_t)p.K + 1024ull * kb - 1) / (1024ull * kb));
+        if (rounds > 4) rounds = 4;
+        if (rounds < 1) rounds = 1;
+        const uint32_t n_gather = (p.K + kb * rounds - 1) / (kb * rounds);
         before(KID_GATHER);
         hipLaunchKernelGGL(mvk::mv_gather_update, dim3(n_gather + (lists ? p.N * p.emit_blocks : 0)),
                            dim3(mvk::kMaskThreads), 0, st, a.err, a.ld_e, p.d, p.N, p.K, a.mask_idx, inv_n,
-                           c->cfg.reduce == MV_REDUCE_MEAN ? 1 : 0, a.agg_vals, n_gather, p.emit_blocks, cand, p.cap,
+                           c->cfg.reduce == MV_REDUCE_MEAN ? 1 : 0, a.agg_vals, rounds, n_gather, p.emit_blocks, cand, p.cap,
                            rowcnt, seg, p.nseg, segpre, blktotal, p.scan_blocks, kth, tiecut, slow, a.worker_idx,
                            stepno);
         after(KID_GATHER);

@@ -46,7 +46,7 @@ __global__ __launch_bounds__(kRowThreads) void mv_row_votes(
 // vote sum).  The threshold v* is the level at which K coordinates are covered walking
 // down from N: all coordinates above v* are taken, and the first K - (#above)
 // coordinates, in coordinate order, with exactly v* votes.  A block is the 16384 Q
-// coordinates of one workgroup (Q = 1, 2 or 4 quads of 16 vote bytes per thread, chosen
+// coordinates of one workgroup (Q = 1 to 8 quads of 16 vote bytes per thread, chosen
 // so that the grid stays at a few hundred workgroups).  mv_mask_count counts, per
 // block, the coordinates above and at v*; mv_mask_emit turns the counts of the earlier
 // blocks into positions and writes the mask in ascending order.
@@ -110,12 +110,12 @@ __device__ __forceinline__ void count_above_and_at(const uint32_t (&ww)[4 * Q], 
 }
 
 // Exclusive scan of a row's segment tallies for the sorted vote lists, 4096 segments
-// per workgroup: seg_pre[s] = taken candidates in the earlier segments of s's block of
+// at a time: seg_pre[s] = taken candidates in the earlier segments of s's block of
 // 1024 segments, and blk_total[blk] = taken candidates in the whole block.
-__device__ __forceinline__ void seg_scan_block(const uint32_t* __restrict__ ssel, uint32_t nseg,
-                                               uint32_t part, uint32_t* __restrict__ spre,
-                                               uint32_t* __restrict__ blk_total, uint64_t* scan_lds,
-                                               uint32_t* bound /*LDS, 5*/)
+__device__ __forceinline__ void seg_scan_part(const uint32_t* __restrict__ ssel, uint32_t nseg,
+                                              uint32_t part, uint32_t* __restrict__ spre,
+                                              uint32_t* __restrict__ blk_total, uint64_t* scan_lds,
+                                              uint32_t* bound /*LDS, 5*/)
 {
     const uint32_t t = threadIdx.x;
     const uint32_t s0 = part * 4096u + t * 4u;
@@ -139,6 +139,7 @@ __device__ __forceinline__ void seg_scan_block(const uint32_t* __restrict__ ssel
         ex += v[q];
     }
     if ((t & 255u) == 0u && part * 4u + k < (nseg + 1023u) / 1024u) blk_total[part * 4u + k] = bound[k + 1] - bound[k];
+    __syncthreads();                              // the LDS scratch is free for the next part
 }
 
 // Workgroups [0, n_vote_blocks): count the block's coordinates above and at the vote
@@ -166,11 +167,11 @@ __global__ __launch_bounds__(kMaskThreads) void mv_mask_count(const uint32_t* __
     __shared__ uint64_t scan_lds[kMaskThreads / kWave + 1];
     __shared__ uint32_t bound[5];
     if (blockIdx.x >= n_vote_blocks) {
-        const uint32_t b = blockIdx.x - n_vote_blocks;
-        const uint32_t row = b / scan_parts;
+        const uint32_t row = blockIdx.x - n_vote_blocks;       // one workgroup per row
         if (slow_flag[row] == 1u) return;
-        seg_scan_block(seg_sel + (size_t)row * nseg, nseg, b % scan_parts, seg_pre + (size_t)row * nseg,
-                       blk_total + (size_t)row * scan_blocks, scan_lds, bound);
+        for (uint32_t part = 0; part < scan_parts; ++part)
+            seg_scan_part(seg_sel + (size_t)row * nseg, nseg, part, seg_pre + (size_t)row * nseg,
+                          blk_total + (size_t)row * scan_blocks, scan_lds, bound);
         return;
     }
     // the block's vote words first: their latency overlaps the level counters' loads.
@@ -383,7 +384,7 @@ __global__ __launch_bounds__(kMaskThreads) void mv_gather_update(float* __restri
                                                                  int64_t d, uint32_t N, uint32_t K,
                                                                  const uint32_t* __restrict__ mask_idx,
                                                                  float scale, int apply_scale,
-                                                                 float* __restrict__ agg,
+                                                                 float* __restrict__ agg, uint32_t rounds,
                                                                  uint32_t n_gather_blocks, uint32_t emit_blocks,
                                                                  const u32x2* __restrict__ cand, uint32_t cap,
                                                                  const uint32_t* __restrict__ row_count,
@@ -417,26 +418,40 @@ __global__ __launch_bounds__(kMaskThreads) void mv_gather_update(float* __restri
     // gets the next number (kept on the device, so that a captured step can be replayed).
     if (blockIdx.x == 0 && t == 0) step_no[0] = step_no[0] + 1u;
     const uint32_t kl = t / N, n = t % N;
-    const uint32_t k = blockIdx.x * kb + kl;
     const uint32_t pitch = N + 1;                     // kb * (N + 1) <= 1024 + kb <= 1536
-    if (kl < kb && k < K) {
-        const uint32_t j = mask_idx[k];
-        float v = 0.0f;
-        if ((int64_t)j < d) {                         // always true for a mask built by mv_mask_emit
-            float* p = e + (int64_t)n * ld_e + j;
-            v = *p;
+    // rounds coordinates of kb each per workgroup; a thread's loads of all rounds are in flight together
+    constexpr int kMaxRounds = 4;
+    const uint32_t k0 = blockIdx.x * kb * rounds;
+    uint32_t j[kMaxRounds];
+    float v[kMaxRounds];
+#pragma unroll
+    for (int r = 0; r < kMaxRounds; ++r) {
+        const uint32_t k = k0 + (uint32_t)r * kb + kl;
+        j[r] = ((uint32_t)r < rounds && kl < kb && k < K) ? mask_idx[k] : 0xFFFFFFFFu;
+    }
+#pragma unroll
+    for (int r = 0; r < kMaxRounds; ++r) {
+        v[r] = 0.0f;
+        if ((int64_t)j[r] < d) {                      // always true for a mask built by mv_mask_emit
+            float* p = e + (int64_t)n * ld_e + j[r];
+            v[r] = *p;
             *p = 0.0f;
         }
-        tile[kl * pitch + n] = v;
     }
-    __syncthreads();
-    if (t < kb) {
-        const uint32_t kk = blockIdx.x * kb + t;
-        if (kk < K) {
-            float s = tile[t * pitch];                // worker 0
-            for (uint32_t m = 1; m < N; ++m) s = s + tile[t * pitch + m];
-            agg[kk] = apply_scale ? s * scale : s;
+#pragma unroll
+    for (int r = 0; r < kMaxRounds; ++r) {
+        if ((uint32_t)r >= rounds) break;             // uniform over the workgroup
+        if (kl < kb) tile[kl * pitch + n] = v[r];
+        __syncthreads();
+        if (t < kb) {
+            const uint32_t kk = k0 + (uint32_t)r * kb + t;
+            if (kk < K) {
+                float s = tile[t * pitch];            // worker 0
+                for (uint32_t m = 1; m < N; ++m) s = s + tile[t * pitch + m];
+                agg[kk] = apply_scale ? s * scale : s;
+            }
         }
+        __syncthreads();
     }
 }
 

@@ -478,9 +478,11 @@ __device__ __forceinline__ void cast_votes_of_share(const u32x2* __restrict__ cr
                                                     uint32_t* __restrict__ votes32, uint32_t* lvl,
                                                     uint32_t* __restrict__ ssel)
 {
-    constexpr int kU = 4;                         // list entries per thread whose loads are in flight together
+    constexpr int kU = 8;                         // list entries per thread in flight together
     const uint32_t t = threadIdx.x, lane = lane_id();
     for (uint64_t q0 = part; q0 * NT < C; q0 += (uint64_t)parts * kU) {
+        // all the loads, then all the vote atomics, then what depends on their results: a thread's
+        // entries wait for memory together, not one after the other
         u32x2 c[kU];
 #pragma unroll
         for (int u = 0; u < kU; ++u) {
@@ -488,11 +490,21 @@ __device__ __forceinline__ void cast_votes_of_share(const u32x2* __restrict__ cr
             const u32x2 none = {0u, 0xFFFFFFFFu};
             c[u] = (i < C) ? crow[i] : none;
         }
+        uint32_t old[kU];
+        uint32_t taken_mask = 0;
+#pragma unroll
+        for (int u = 0; u < kU; ++u) {
+            old[u] = 0;
+            if (c[u].y != 0xFFFFFFFFu && is_taken(c[u], kth, tie_cut)) {
+                taken_mask |= 1u << u;
+                old[u] = atomicAdd(&votes32[c[u].y >> 2], 1u << ((c[u].y & 3u) * 8u));
+            }
+        }
 #pragma unroll
         for (int u = 0; u < kU; ++u) {
             if ((q0 + (uint64_t)u * parts) * NT >= C) break;        // uniform over the workgroup
-            const bool taken = c[u].y != 0xFFFFFFFFu && is_taken(c[u], kth, tie_cut);
-            if (taken) cast_vote(votes32, c[u].y, lvl);
+            const bool taken = (taken_mask >> u) & 1u;
+            if (taken) atomicAdd(&lvl[((old[u] >> ((c[u].y & 3u) * 8u)) & 255u) + 1u], 1u);
             if (ssel) {
                 const uint32_t sg = c[u].y / kSeg;
                 const uint32_t prev = __shfl_up(sg, 1, kWave);

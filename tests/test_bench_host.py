@@ -21,10 +21,11 @@ def test_comm_load_context_reproduces_the_paper_s_first_row():
 
 
 def test_traffic_summary_is_read_and_sane():
-    t = bench.measured_traffic("C4")
+    t, source = bench.measured_traffic("C4")
     algorithmic = 12 * 16 * 11_173_962
     assert t is not None and algorithmic <= t <= 1.2 * algorithmic
-    assert bench.measured_traffic("no such workload") is None
+    assert source == os.path.join("profiles", "vote_step_C4_hbm_counters.txt")
+    assert bench.measured_traffic("no such workload") == (None, None)
 
 
 def test_more_than_one_gpu_is_refused():
