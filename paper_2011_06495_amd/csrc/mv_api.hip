@@ -18,7 +18,6 @@ enum KernelId {
     KID_ROW_SELECT,
     KID_ROW_VOTES,
     KID_MASK_COUNT,
-    KID_MASK_EMIT,
     KID_GATHER,
     // add-drop voting only
     KID_AD_COLLECT,
@@ -39,7 +38,7 @@ enum KernelId {
 };
 const char* const kKernelNames[KID_COUNT] = {
     "mv_stream_collect",   "mv_row_select",      "mv_row_votes",
-    "mv_mask_count",     "mv_mask_emit",       "mv_gather_update",    "mv_ad_collect",      "mv_ad_select",
+    "mv_mask_count",     "mv_gather_update",    "mv_ad_collect",      "mv_ad_select",
     "mv_ad_apply",       "mv_ad_compact_count", "mv_ad_compact_emit",
     "mv_sel_hist",       "mv_sel_split",       "mv_sel_rank",
     "mv_rs_keys",        "mv_rs_hist",         "mv_rs_split",         "mv_rs_rank"};
@@ -85,7 +84,9 @@ struct Plan {
     size_t off_sampledone, off_readsdone, off_taupub, off_poison, off_stepno, off_candcount;
     size_t off_hist, off_tau, off_rowcnt, off_slow, off_kth, off_tiecut, off_lvlsets, off_seg, off_segsel,
         off_segpre,
-        off_blktotal, off_alist, off_dlist, off_adcount, off_adthr, off_adbits, off_adblk, off_cand, off_votes, off_blockcnt, off_votethr;
+        off_blktotal, off_alist, off_dlist, off_adcount, off_adthr, off_adbits, off_adblk, off_cand, off_votes, off_blockcnt, off_subcnt, off_votethr, off_emitfail,
+        off_lookback;
+    uint32_t n_zero_words;      // words from off_lvlsets on that a step's first kernel zeroes
     size_t total_bytes;
 };
 
@@ -152,12 +153,15 @@ Plan make_plan(const mv_config* c)
 
     p.rs_blocks = (uint32_t)((p.d + mvk::kVoteBlock - 1) / mvk::kVoteBlock);
     {
-        // the mask kernels: as few vote bytes per thread as keep the grid at a few hundred workgroups (measured:
-        // 32 bytes per thread and 342 workgroups beat 64 bytes and 171; the work per thread is what costs)
+        // the mask kernels: as few vote bytes per thread as keep the grid, with one more workgroup per row for
+        // the segment scans, within one round of the chip (one workgroup of 1024 threads per compute unit)
         static const uint32_t kQs[] = {1, 2, 3, 4, 6, 8};
         uint32_t q = 8;
         for (uint32_t cand_q : kQs)
-            if ((uint64_t)p.d <= 440ull * mvk::kMaskThreads * 16 * cand_q) { q = cand_q; break; }
+            if ((uint64_t)p.d <= (uint64_t)(250 - (p.N < 128 ? p.N : 128)) * mvk::kMaskThreads * 16 * cand_q) {
+                q = cand_q;
+                break;
+            }
         p.vote_q = q;
         const uint64_t per = (uint64_t)mvk::kMaskThreads * 16 * q;
         p.n_vote_blocks = (uint32_t)(((uint64_t)p.d + per - 1) / per);
@@ -213,7 +217,12 @@ Plan make_plan(const mv_config* c)
     p.off_slow = off;     off += align_up((size_t)p.N * 4);
     p.off_kth = off;      off += align_up((size_t)p.N * 4);
     p.off_tiecut = off;   off += align_up((size_t)p.N * 4);
-    p.off_lvlsets = off;  off += align_up((size_t)mvk::kLvlSets * 256 * 4);
+    // the vote-level counters and, behind them, what mv_mask_count's blocks publish to each other (a flag word
+    // and two 64-bit words per block): one stretch of words that every step's first kernel leaves at zero
+    p.off_lvlsets = off;  off += (size_t)mvk::kLvlSets * 256 * 4;
+    p.off_emitfail = off; off += 8;
+    p.off_lookback = off; off += align_up((size_t)p.n_vote_blocks * 16);
+    p.n_zero_words = (uint32_t)((off - p.off_lvlsets) / 4);
     p.off_seg = off;      off += align_up((size_t)p.N * p.nseg * 8);
     p.off_segsel = off;   off += align_up((size_t)p.N * p.nseg * 4);
     p.off_segpre = off;   off += align_up((size_t)p.N * p.nseg * 4);
@@ -221,6 +230,7 @@ Plan make_plan(const mv_config* c)
     p.off_cand = off;     off += align_up((size_t)p.N * p.cap * 8);
     p.off_votes = off;    off += align_up(((size_t)p.d + 15) / 16 * 16);
     p.off_blockcnt = off; off += align_up((size_t)p.n_vote_blocks * 8);
+    p.off_subcnt = off;   off += align_up((size_t)p.n_vote_blocks * (mvk::kMaskThreads / mvk::kWave) * 8);
     p.off_votethr = off;  off += align_up(2 * 4);
     p.add_drop = (c->flags & MV_FLAG_ADD_DROP) != 0;
     p.nwords = (uint32_t)((p.d + 31) / 32);
@@ -435,6 +445,9 @@ mv_status enqueue_step(mv_ctx* c, const StepArgs& a, void* stream_v)
     mvk::u32x2* cand = ws_ptr<mvk::u32x2>(c, p.off_cand);
     uint32_t* votes32 = ws_ptr<uint32_t>(c, p.off_votes);
     mvk::u32x2* blockcnt = ws_ptr<mvk::u32x2>(c, p.off_blockcnt);
+    mvk::u32x2* subcnt = ws_ptr<mvk::u32x2>(c, p.off_subcnt);
+    uint32_t* emitfail = ws_ptr<uint32_t>(c, p.off_emitfail);
+    unsigned long long* lookback = ws_ptr<unsigned long long>(c, p.off_lookback);
     uint32_t* votethr = ws_ptr<uint32_t>(c, p.off_votethr);
     mvk::u32x2* alist = p.add_drop ? ws_ptr<mvk::u32x2>(c, p.off_alist) : nullptr;
     mvk::u32x2* dlist = p.add_drop ? ws_ptr<mvk::u32x2>(c, p.off_dlist) : nullptr;
@@ -473,14 +486,16 @@ mv_status enqueue_step(mv_ctx* c, const StepArgs& a, void* stream_v)
             hipLaunchKernelGGL(mvk::mv_stream_collect<uint16_t>, grid, dim3(mvk::kStreamThreads), 0, st,
                                static_cast<const uint16_t*>(a.grads), a.ld_g, a.err, a.ld_e, p.d, p.N, p.sample_wgs,
                                p.stride, p.n_sampled_chunks, p.m_target, hist, sampledone, readsdone, taupub, stepno,
-                               c->spin_limit, poison, lvlsets, (uint32_t)(mvk::kLvlSets * 256), adcount, cand, p.cap,
-                               rowcnt_sets, rowcnt_set_words, seg, segsel, p.nseg, wpr, c->head_wgs);
+                               c->spin_limit, poison, lvlsets, p.n_zero_words, adcount, cand, p.cap,
+                               rowcnt_sets, rowcnt_set_words, seg, segsel, p.nseg, wpr, c->head_wgs,
+                               add_drop ? (uint32_t*)nullptr : votes32, (int64_t)(((size_t)p.d + 15) / 16 * 16));
         else
             hipLaunchKernelGGL(mvk::mv_stream_collect<float>, grid, dim3(mvk::kStreamThreads), 0, st,
                                static_cast<const float*>(a.grads), a.ld_g, a.err, a.ld_e, p.d, p.N, p.sample_wgs,
                                p.stride, p.n_sampled_chunks, p.m_target, hist, sampledone, readsdone, taupub, stepno,
-                               c->spin_limit, poison, lvlsets, (uint32_t)(mvk::kLvlSets * 256), adcount, cand, p.cap,
-                               rowcnt_sets, rowcnt_set_words, seg, segsel, p.nseg, wpr, c->head_wgs);
+                               c->spin_limit, poison, lvlsets, p.n_zero_words, adcount, cand, p.cap,
+                               rowcnt_sets, rowcnt_set_words, seg, segsel, p.nseg, wpr, c->head_wgs,
+                               add_drop ? (uint32_t*)nullptr : votes32, (int64_t)(((size_t)p.d + 15) / 16 * 16));
         after(KID_STREAM);
     }
     // 3. exact per-row select
@@ -605,26 +620,45 @@ mv_status enqueue_step(mv_ctx* c, const StepArgs& a, void* stream_v)
                            (uint32_t*)nullptr, (int64_t)0);
         after(KID_AD_COMPACT_EMIT);
     }
-    // 5. global mask; in plain voting extra workgroups of the first kernel scan the segment tallies for
-    // the sorted vote lists (with random selection the mask is already written: only the copy of the
-    // votes and the clearing of the vote words remain)
+    // 5. global mask: the vote threshold and the counts per stretch of the vote bytes (in plain voting extra
+    // workgroups scan the segment tallies for the sorted vote lists); then 6. every workgroup of the last
+    // kernel emits its part of the mask, gathers it, takes the mean and updates the error buffers; extra
+    // workgroups write the sorted vote lists beside it.  With random selection the mask is already written.
     const bool lists = sorted && !add_drop;
     {
-        const dim3 grid_c(p.n_vote_blocks + (lists ? p.N : 0)), grid_e(p.n_vote_blocks);
+        const dim3 grid_c(p.n_vote_blocks + (lists ? p.N : 0));
         const dim3 block(mvk::kMaskThreads);
         uint8_t* votes_out = add_drop ? nullptr : a.votes;
-        uint32_t* mask_out = random_sel ? (uint32_t*)nullptr : a.mask_idx;
-        const int clear = add_drop ? 0 : 1;
+        const float inv_n = 1.0f / (float)p.N;
+        const uint32_t kb = mvk::kMaskThreads / p.N;
+        // up to four rounds of kb mask positions per workgroup, as few as keep the grid, with the sorted lists'
+        // workgroups, within one round of the chip (one workgroup of 1024 threads per compute unit)
+        const uint32_t eb = p.emit_blocks;
+        const uint32_t n_list = lists ? p.N * eb : 0;
+        const uint32_t room = n_list + 64 <= 250 ? 250 - n_list : 64;
+        uint32_t rounds = (uint32_t)(((uint64_t)p.K + (uint64_t)room * kb - 1) / ((uint64_t)room * kb));
+        if (rounds > (uint32_t)mvk::kGatherRounds) rounds = mvk::kGatherRounds;
+        if (rounds < 1) rounds = 1;
+        const uint32_t n_gather = (p.K + kb * rounds - 1) / (kb * rounds);
+        const dim3 grid_g(n_gather + n_list);
 #define MV_LAUNCH_MASK(Q)                                                                                        \
         before(KID_MASK_COUNT);                                                                                  \
         hipLaunchKernelGGL(mvk::mv_mask_count<Q>, grid_c, block, 0, st, mask_votes32, p.d, p.N, p.K, lvlsets,     \
-                           blockcnt, votethr, votes_out, p.n_vote_blocks, p.scan_parts, p.scan_blocks, p.nseg,   \
-                           slow, segsel, segpre, blktotal, add_drop ? 1 : 0);                                    \
+                           subcnt, blockcnt, votethr, votes_out, p.n_vote_blocks, p.scan_parts, p.scan_blocks,   \
+                           p.nseg,                                                                               \
+                           slow, segsel, segpre, blktotal, add_drop ? 1 : 0, lookback, emitfail, c->spin_limit,  \
+                           random_sel ? nullptr : a.mask_idx);                                                  \
         after(KID_MASK_COUNT);                                                                                   \
-        before(KID_MASK_EMIT);                                                                                   \
-        hipLaunchKernelGGL(mvk::mv_mask_emit<Q>, grid_e, block, 0, st, mask_votes32, p.d, p.K, votethr, blockcnt, \
-                           mask_out, clear);                                                                     \
-        after(KID_MASK_EMIT);
+        before(KID_GATHER);                                                                                      \
+        hipLaunchKernelGGL(mvk::mv_gather_update<Q>, grid_g, block, 0, st, a.err, a.ld_e, p.d, p.N, p.K,          \
+                           (const uint32_t*)mask_votes32, (const mvk::u32x2*)subcnt,                             \
+                           (const mvk::u32x2*)blockcnt, p.n_vote_blocks,                                         \
+                           (const uint32_t*)votethr, a.mask_idx, random_sel ? 1 : 0,                             \
+                           (const uint32_t*)emitfail, inv_n,                                                     \
+                           c->cfg.reduce == MV_REDUCE_MEAN ? 1 : 0, a.agg_vals, rounds, n_gather, eb,            \
+                           cand, p.cap, rowcnt, seg, p.nseg, segpre, blktotal, p.scan_blocks, kth, tiecut, slow, \
+                           a.worker_idx, stepno);                                                                \
+        after(KID_GATHER);
         switch (p.vote_q) {
             case 1: { MV_LAUNCH_MASK(1) } break;
             case 2: { MV_LAUNCH_MASK(2) } break;
@@ -634,24 +668,6 @@ mv_status enqueue_step(mv_ctx* c, const StepArgs& a, void* stream_v)
             default: { MV_LAUNCH_MASK(8) } break;
         }
 #undef MV_LAUNCH_MASK
-    }
-    // 6. gather + mean + error update; extra workgroups write the sorted vote lists beside it
-    {
-        const float inv_n = 1.0f / (float)p.N;
-        const uint32_t kb = mvk::kMaskThreads / p.N;
-        // up to four rounds of kb coordinates per workgroup, as few as keep the grid at about a thousand workgroups
-        // (more work per thread measured no faster below that)
-        uint32_t rounds = (uint32_t)(((uint64_t)p.K + 1024ull * kb - 1) / (1024ull * kb));
-        if (rounds > 4) rounds = 4;
-        if (rounds < 1) rounds = 1;
-        const uint32_t n_gather = (p.K + kb * rounds - 1) / (kb * rounds);
-        before(KID_GATHER);
-        hipLaunchKernelGGL(mvk::mv_gather_update, dim3(n_gather + (lists ? p.N * p.emit_blocks : 0)),
-                           dim3(mvk::kMaskThreads), 0, st, a.err, a.ld_e, p.d, p.N, p.K, a.mask_idx, inv_n,
-                           c->cfg.reduce == MV_REDUCE_MEAN ? 1 : 0, a.agg_vals, rounds, n_gather, p.emit_blocks, cand, p.cap,
-                           rowcnt, seg, p.nseg, segpre, blktotal, p.scan_blocks, kth, tiecut, slow, a.worker_idx,
-                           stepno);
-        after(KID_GATHER);
     }
     c->last_stream = st;
     c->steps_done += 1;

@@ -11,7 +11,8 @@
 
 namespace mvk {
 
-constexpr int kMaskThreads = 1024;   // mv_mask_count / mv_mask_emit / mv_gather_update
+constexpr int kMaskThreads = 1024;   // mv_mask_count / mv_gather_update
+constexpr int kLookBack = 256;       // earlier blocks whose totals a block of mv_mask_count adds up itself
 
 // ----------------------------------------------------------------------------
 // 4. vote casting for long candidate lists (the rows' select ran in the mv_sel_*
@@ -48,8 +49,9 @@ __global__ __launch_bounds__(kRowThreads) void mv_row_votes(
 // coordinates, in coordinate order, with exactly v* votes.  A block is the 16384 Q
 // coordinates of one workgroup (Q = 1 to 8 quads of 16 vote bytes per thread, chosen
 // so that the grid stays at a few hundred workgroups).  mv_mask_count counts, per
-// block, the coordinates above and at v*; mv_mask_emit turns the counts of the earlier
-// blocks into positions and writes the mask in ascending order.
+// wavefront's stretch of the vote bytes, the coordinates above and at v*;
+// mv_gather_update turns the counts of the earlier stretches into positions: each of
+// its workgroups emits the part of the mask it gathers.
 
 // All threads of the workgroup: vstar / take_eq from the level counters.
 __device__ __forceinline__ void vote_threshold(const uint32_t* __restrict__ lvl_sets, uint32_t N, uint32_t K,
@@ -91,18 +93,23 @@ __device__ __forceinline__ void vote_threshold(const uint32_t* __restrict__ lvl_
     take_eq = thr[1];
 }
 
-// the thread's coordinates with more than / exactly vstar votes among its 16 Q bytes from j0 on
+// The thread's coordinates with more than / exactly vstar votes among its 16 Q bytes from j0
+// on.  Must be called by all lanes of a wavefront together: a word that holds no vote in
+// any lane is passed over by the whole wavefront (most words, where votes are sparse);
+// with vstar == 0 the coordinates without a vote count too and nothing is passed over.
 template <int Q>
-__device__ __forceinline__ void count_above_and_at(const uint32_t (&ww)[4 * Q], uint32_t any, int64_t j0, int64_t d,
+__device__ __forceinline__ void count_above_and_at(const uint32_t (&ww)[4 * Q], int64_t j0, int64_t d,
                                                    uint32_t vstar, uint32_t& gt, uint32_t& eq)
 {
     gt = 0;
     eq = 0;
-    if (any || vstar == 0u) {                     // nearly all threads hold no vote at all
 #pragma unroll
-        for (int q = 0; q < 16 * Q; ++q) {
-            const uint32_t v = (ww[q >> 2] >> (8 * (q & 3))) & 255u;
-            const bool inside = j0 + q < d;                            // matters when v* is 0
+    for (int q = 0; q < 4 * Q; ++q) {
+        if (vstar != 0u && __ballot(ww[q] != 0u) == 0ull) continue;   // wave-uniform
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const uint32_t v = (ww[q] >> (8 * b)) & 255u;
+            const bool inside = j0 + 4 * q + b < d;                   // matters when v* is 0
             gt += (inside && v > vstar);
             eq += (inside && v == vstar);
         }
@@ -142,14 +149,15 @@ __device__ __forceinline__ void seg_scan_part(const uint32_t* __restrict__ ssel,
     __syncthreads();                              // the LDS scratch is free for the next part
 }
 
-// Workgroups [0, n_vote_blocks): count the block's coordinates above and at the vote
-// threshold; optionally copy the vote bytes to the caller.  Workgroups beyond (only
-// launched when the sorted vote lists are wanted): scan the segment tallies of row
-// (b / scan_parts), part (b % scan_parts).
+// Workgroups [0, n_vote_blocks): count, per wavefront's stretch of 1024 Q coordinates, the
+// coordinates above and at the vote threshold; optionally copy the vote bytes to the
+// caller.  Workgroups beyond (only launched when the sorted vote lists are wanted): one
+// per row, scanning the row's segment tallies.
 template <int Q>
 __global__ __launch_bounds__(kMaskThreads) void mv_mask_count(const uint32_t* __restrict__ votes32,
                                                               int64_t d, uint32_t N, uint32_t K,
                                                               const uint32_t* __restrict__ lvl_sets,
+                                                              u32x2* __restrict__ sub_cnt,
                                                               u32x2* __restrict__ block_cnt,
                                                               uint32_t* __restrict__ vote_thr,
                                                               uint8_t* __restrict__ votes_out,
@@ -159,13 +167,17 @@ __global__ __launch_bounds__(kMaskThreads) void mv_mask_count(const uint32_t* __
                                                               const uint32_t* __restrict__ seg_sel,
                                                               uint32_t* __restrict__ seg_pre,
                                                               uint32_t* __restrict__ blk_total,
-                                                              int exact_levels)
+                                                              int exact_levels,
+                                                              unsigned long long* __restrict__ lookback,
+                                                              uint32_t* __restrict__ emit_fail, uint32_t spin_limit,
+                                                              uint32_t* __restrict__ mask_idx)
 {
     MV_SPAN(5);
     __shared__ uint32_t lvl[256];
     __shared__ uint32_t thr[2];
     __shared__ uint64_t scan_lds[kMaskThreads / kWave + 1];
     __shared__ uint32_t bound[5];
+    __shared__ uint64_t before_sh;
     if (blockIdx.x >= n_vote_blocks) {
         const uint32_t row = blockIdx.x - n_vote_blocks;       // one workgroup per row
         if (slow_flag[row] == 1u) return;
@@ -187,11 +199,9 @@ __global__ __launch_bounds__(kMaskThreads) void mv_mask_count(const uint32_t* __
     uint32_t vstar, take_eq;
     vote_threshold(lvl_sets, N, K, lvl, thr, vstar, take_eq, exact_levels);
     uint32_t ww[4 * Q];
-    uint32_t any = 0;
 #pragma unroll
     for (int q = 0; q < Q; ++q) {
         ww[4 * q + 0] = w[q].x; ww[4 * q + 1] = w[q].y; ww[4 * q + 2] = w[q].z; ww[4 * q + 3] = w[q].w;
-        any |= w[q].x | w[q].y | w[q].z | w[q].w;
         if (votes_out) {
             const int64_t j = j0 + q * 16;
             if (j + 16 <= d && ((reinterpret_cast<uintptr_t>(votes_out) & 15) == 0)) {
@@ -203,75 +213,112 @@ __global__ __launch_bounds__(kMaskThreads) void mv_mask_count(const uint32_t* __
         }
     }
     uint32_t gt, eq;
-    count_above_and_at<Q>(ww, any, j0, d, vstar, gt, eq);
-    uint64_t total;
-    (void)block_excl_scan64<kMaskThreads>(pack2(gt, eq), scan_lds, total);
-    if (threadIdx.x == 0) {
-        u32x2 r;
-        r.x = (uint32_t)(total >> 32);
-        r.y = (uint32_t)total;
-        block_cnt[blockIdx.x] = r;
-        if (blockIdx.x == 0) {                   // the threshold, for mv_mask_emit
-            vote_thr[0] = vstar;
-            vote_thr[1] = take_eq;
+    count_above_and_at<Q>(ww, j0, d, vstar, gt, eq);
+    const uint32_t lane = lane_id(), wave = threadIdx.x / kWave;
+    const uint64_t both = pack2(gt, eq);
+    uint64_t block_total;
+    const uint64_t ex = block_excl_scan64<kMaskThreads>(both, scan_lds, block_total);   // before this thread, in the block
+    {
+        // the counts per wavefront stretch and per block: what mv_gather_update scans when the
+        // mask could not be written here
+        const uint64_t stretch = (uint64_t)__shfl((unsigned long long)(ex + both), kWave - 1, kWave) -
+                                 (uint64_t)__shfl((unsigned long long)ex, 0, kWave);
+        if (lane == 0) {
+            u32x2 r;
+            r.x = (uint32_t)(stretch >> 32);
+            r.y = (uint32_t)stretch;
+            sub_cnt[(size_t)blockIdx.x * (kMaskThreads / kWave) + wave] = r;
+        }
+        if (threadIdx.x == 0) {
+            u32x2 r;
+            r.x = (uint32_t)(block_total >> 32);
+            r.y = (uint32_t)block_total;
+            block_cnt[blockIdx.x] = r;
         }
     }
-}
+    if (blockIdx.x == 0 && threadIdx.x == 0) {    // the threshold, for the kernel that follows
+        vote_thr[0] = vstar;
+        vote_thr[1] = take_eq;
+    }
+    if (!mask_idx) return;                        // random selection writes the mask elsewhere
 
-// Emits the mask in ascending order and clears the vote words for the next step
-// (mask_idx == nullptr: only clears; the mask was written elsewhere).
-template <int Q>
-__global__ __launch_bounds__(kMaskThreads) void mv_mask_emit(uint32_t* __restrict__ votes32,
-                                                             int64_t d, uint32_t K,
-                                                             const uint32_t* __restrict__ vote_thr,
-                                                             const u32x2* __restrict__ block_cnt,
-                                                             uint32_t* __restrict__ mask_idx, int clear_votes)
-{
-    MV_SPAN(6);
-    __shared__ uint64_t scan_lds[kMaskThreads / kWave + 1];
-    // the block's vote words first (cleared behind for the next step): their latency
-    // overlaps the loads of the prefix below.  Thread t owns bytes [16 Q t, 16 Q t + 16 Q).
-    const int64_t j0 = ((int64_t)blockIdx.x * kMaskThreads + threadIdx.x) * (16 * Q);
-    uint32_t ww[4 * Q];
-    uint32_t any = 0;
+    // The counts of the earlier blocks, without another kernel: every block publishes its own
+    // totals at once (word 0 of its pair); its first wavefront then reads the totals of the
+    // kLookBack blocks before it, all loads in flight together, and the sum over everything
+    // up to the block before those (word 1 of that block's pair, published by that block once
+    // it has summed up itself), polling until every word is there.  A word holds a "present"
+    // bit and both counts (each below 2^31), so one 64-bit store publishes it whole.  Blocks
+    // are dispatched in the order of their numbers and publish their totals before they wait,
+    // so the wait ends; were a word still missing after spin_limit polls, the block gives up,
+    // says so in emit_fail, and mv_gather_update finds the mask from the counts instead.
+    constexpr unsigned long long kPresent = 1ull << 63, kCountMask = 0x7FFFFFFFull;
+    constexpr int kPer = kLookBack / kWave;
+    auto word_of = [&](uint64_t counts) { return kPresent | ((counts >> 32) << 31) | (counts & kCountMask); };
+    auto counts_of = [&](unsigned long long w) {
+        return pack2((uint32_t)((w >> 31) & kCountMask), (uint32_t)(w & kCountMask));
+    };
+    if (wave == 0) {
+        const int64_t me = blockIdx.x;
+        if (lane == 0)
+            __hip_atomic_store(&lookback[2 * me], word_of(block_total), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        // lane l: the totals of blocks me - 1 - l - 64 r; lane 0 also the sum up to block me - kLookBack - 1
+        const unsigned long long* src[kPer + 1];
+        unsigned long long w[kPer + 1];
 #pragma unroll
-    for (int q = 0; q < Q; ++q) {
-        const int64_t j = j0 + q * 16;
-        u32x4 w = {0u, 0u, 0u, 0u};
-        if (j < d) {
-            u32x4* p = reinterpret_cast<u32x4*>(votes32 + (j >> 2));
-            w = *p;
-            const u32x4 z = {0u, 0u, 0u, 0u};
-            if (clear_votes && (w.x | w.y | w.z | w.w) != 0u) *p = z;
+        for (int r = 0; r < kPer; ++r) {
+            const int64_t b = me - 1 - (int64_t)lane - (int64_t)kWave * r;
+            src[r] = b >= 0 ? &lookback[2 * b] : nullptr;
         }
-        ww[4 * q + 0] = w.x; ww[4 * q + 1] = w.y; ww[4 * q + 2] = w.z; ww[4 * q + 3] = w.w;
-        any |= w.x | w.y | w.z | w.w;
+        src[kPer] = (lane == 0 && me - kLookBack - 1 >= 0) ? &lookback[2 * (me - kLookBack - 1) + 1] : nullptr;
+#pragma unroll
+        for (int r = 0; r <= kPer; ++r) w[r] = src[r] ? 0ull : kPresent;
+        bool found = true;
+        for (uint32_t polls = 0;; ++polls) {
+            bool all = true;
+#pragma unroll
+            for (int r = 0; r <= kPer; ++r)
+                if (!(w[r] & kPresent)) w[r] = __hip_atomic_load(src[r], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+            for (int r = 0; r <= kPer; ++r) all = all && (w[r] & kPresent);
+            if (__ballot(!all) == 0ull) break;
+            if (polls >= spin_limit) {                                // uniform
+                found = false;
+                break;
+            }
+            __builtin_amdgcn_s_sleep(2);
+        }
+        uint64_t before = 0;
+#pragma unroll
+        for (int r = 0; r <= kPer; ++r) before += counts_of(w[r]);
+#pragma unroll
+        for (int o = 1; o < kWave; o <<= 1) before += (uint64_t)__shfl_xor((unsigned long long)before, o, kWave);
+        if (lane == 0) {
+            if (found)
+                __hip_atomic_store(&lookback[2 * me + 1], word_of(before + block_total), __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+            else
+                __hip_atomic_store(emit_fail, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            before_sh = before;
+            bound[0] = found ? 1u : 0u;
+        }
     }
-    if (!mask_idx) return;                        // whole workgroup
-    const uint32_t vstar = vote_thr[0], take_eq = vote_thr[1];   // found by mv_mask_count
-
-    // coordinates selected / tied before this block
-    uint64_t mine = 0;
-    for (uint32_t b = threadIdx.x; b < blockIdx.x; b += kMaskThreads) {
-        const u32x2 r = block_cnt[b];
-        mine += pack2(r.x, r.y);
-    }
-    uint32_t gt, eq;
-    count_above_and_at<Q>(ww, any, j0, d, vstar, gt, eq);
-    uint64_t before, total;
-    (void)block_excl_scan64<kMaskThreads>(mine, scan_lds, before);
     __syncthreads();
-    const uint64_t ex = block_excl_scan64<kMaskThreads>(pack2(gt, eq), scan_lds, total);
-    if (gt | eq) {
-        uint32_t g0 = (uint32_t)(before >> 32) + (uint32_t)(ex >> 32), e0 = (uint32_t)before + (uint32_t)ex;
+    if (bound[0] == 0u) return;                   // whole workgroup
+    const uint64_t before = before_sh;
+    if ((uint32_t)(before >> 32) + min((uint32_t)before, take_eq) >= K) return;   // the mask is full before this block
+    uint32_t g0 = (uint32_t)((before + ex) >> 32), e0 = (uint32_t)(before + ex);
 #pragma unroll
-        for (int q = 0; q < 16 * Q; ++q) {
-            const uint32_t v = (ww[q >> 2] >> (8 * (q & 3))) & 255u;
-            const bool inside = j0 + q < d;
+    for (int q = 0; q < 4 * Q; ++q) {
+        if (vstar != 0u && __ballot(ww[q] != 0u) == 0ull) continue;   // wave-uniform: no vote in this word
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const uint32_t v = (ww[q] >> (8 * b)) & 255u;
+            const int64_t j = j0 + 4 * q + b;
+            const bool inside = j < d;
             const bool is_gt = inside && v > vstar, is_eq = inside && v == vstar;
             if (is_gt || (is_eq && e0 < take_eq)) {
                 const uint32_t pos = g0 + min(e0, take_eq);
-                if (pos < K) mask_idx[pos] = (uint32_t)(j0 + q);
+                if (pos < K) mask_idx[pos] = (uint32_t)j;
             }
             g0 += is_gt;
             e0 += is_eq;
@@ -372,17 +419,43 @@ __device__ __forceinline__ void row_emit_block(const u32x2* __restrict__ crow, u
     }
 }
 
-// Workgroups [0, n_gather_blocks): each handles kb = 1024 / N mask coordinates.
-// Thread (kl, n) reads a[n][mask[k]] (held in e), stores +0.0 there (the error
-// update: the residual of a transmitted coordinate is zero), and parks the value in
-// LDS; one thread per coordinate then adds the N values in worker order 0..N-1 in
-// fp32 and applies the 1/N of the mean once.
+// Workgroups [0, n_gather_blocks): each owns `rounds` times kb = 1024 / N consecutive
+// positions of the mask.
+// (a) Unless the mask is given (random selection writes it elsewhere), the workgroup
+//     first finds its own positions' coordinates: the counts per block of the vote bytes
+//     and, inside the few blocks that matter, per wavefront stretch (from mv_mask_count)
+//     are scanned, which says where in the mask each stretch's coordinates go; the few
+//     stretches that reach into the workgroup's positions are read again, one wavefront each, and their coordinates above the
+//     vote threshold, and the first take_eq at it, go to their positions -- in LDS for
+//     the gather, and in mask_idx for the caller.  No kernel of its own emits the mask.
+// (b) Thread (kl, n) reads a[n][mask[k]] (held in e), stores +0.0 there (the error
+//     update: the residual of a transmitted coordinate is zero), and parks the value in
+//     LDS; one thread per coordinate then adds the N values in worker order 0..N-1 in
+//     fp32 and applies the 1/N of the mean once.
 // Workgroups beyond (only launched when the sorted vote lists are wanted): write
 // row (b / emit_blocks)'s vote list; they start after the gather's workgroups and
 // run beside them.
+constexpr int kGatherRounds = 4;                  // at most this many rounds of kb positions per workgroup
+
+struct GatherLds {
+    float    tile[kMaskThreads + kMaskThreads / 2 + 8];
+    uint32_t slice[kGatherRounds * kMaskThreads];              // the workgroup's positions' coordinates
+    uint32_t need[3 * (kGatherRounds * kMaskThreads + 2)];     // stretches to read: (stretch, above before, at before)
+    uint32_t blocks[3 * (kGatherRounds * kMaskThreads + 2)];   // blocks whose stretches are looked at
+    uint32_t n_need, n_blocks;
+    uint32_t blk_pre[kMaxScanBlocks];
+    uint64_t scan[kMaskThreads / kWave + 1];
+};
+
+template <int Q>
 __global__ __launch_bounds__(kMaskThreads) void mv_gather_update(float* __restrict__ e, int64_t ld_e,
                                                                  int64_t d, uint32_t N, uint32_t K,
-                                                                 const uint32_t* __restrict__ mask_idx,
+                                                                 const uint32_t* __restrict__ votes32,
+                                                                 const u32x2* __restrict__ sub_cnt,
+                                                                 const u32x2* __restrict__ block_cnt, uint32_t n_blocks,
+                                                                 const uint32_t* __restrict__ vote_thr,
+                                                                 uint32_t* __restrict__ mask_idx, int mask_given,
+                                                                 const uint32_t* __restrict__ emit_fail,
                                                                  float scale, int apply_scale,
                                                                  float* __restrict__ agg, uint32_t rounds,
                                                                  uint32_t n_gather_blocks, uint32_t emit_blocks,
@@ -399,9 +472,7 @@ __global__ __launch_bounds__(kMaskThreads) void mv_gather_update(float* __restri
                                                                  uint32_t* __restrict__ step_no)
 {
     MV_SPAN(7);
-    __shared__ float tile[kMaskThreads + kMaskThreads / 2 + 8];
-    __shared__ uint32_t blk_pre[kMaxScanBlocks];
-    __shared__ uint64_t scan_lds[kMaskThreads / kWave + 1];
+    __shared__ GatherLds lds;
     if (blockIdx.x >= n_gather_blocks) {
         const uint32_t b = blockIdx.x - n_gather_blocks;
         const uint32_t row = b / emit_blocks;
@@ -409,45 +480,138 @@ __global__ __launch_bounds__(kMaskThreads) void mv_gather_update(float* __restri
         row_emit_block(cand + (size_t)row * cap, row_count[row], seg + (size_t)row * nseg,
                        seg_pre + (size_t)row * nseg, blk_total + (size_t)row * scan_blocks, scan_blocks, K,
                        kth_in[row], tie_cut_in[row], b % emit_blocks, emit_blocks,
-                       worker_idx + (size_t)row * K, blk_pre, scan_lds);
+                       worker_idx + (size_t)row * K, lds.blk_pre, lds.scan);
         return;
     }
     const uint32_t kb = kMaskThreads / N;             // N <= 255, so kb >= 4
-    const uint32_t t = threadIdx.x;
+    const uint32_t t = threadIdx.x, lane = lane_id(), wave = t / kWave;
     // This is the step's last kernel and nothing in it reads the step's number: the next step
     // gets the next number (kept on the device, so that a captured step can be replayed).
     if (blockIdx.x == 0 && t == 0) step_no[0] = step_no[0] + 1u;
+    const uint32_t k0 = blockIdx.x * kb * rounds;     // the workgroup's positions: [k0, k1)
+    const uint32_t k1 = min(K, k0 + kb * rounds);
+
+    if (!mask_given && emit_fail[0] != 0u) {          // uniform over the grid; not expected
+        const uint32_t vstar = vote_thr[0], take_eq = vote_thr[1];
+        if (t == 0) {
+            lds.n_need = 0;
+            lds.n_blocks = 0;
+        }
+        // position of a stretch's (a block's) first mask coordinate = (coordinates above the threshold
+        // before it) + min(coordinates at the threshold before it, take_eq)
+        auto reaches_in = [&](uint32_t g, uint32_t q, u32x2 c) {
+            const uint32_t q_taken = min(q, take_eq);                  // of the earlier ones at the threshold
+            const uint32_t first = g + q_taken;
+            const uint32_t n_in = c.x + min(c.y, take_eq - q_taken);
+            return n_in != 0u && first < k1 && first + n_in > k0;
+        };
+        // first level: the blocks' totals
+        uint32_t gt_before = 0, eq_before = 0;        // over the blocks of the earlier passes
+        for (uint32_t b0 = 0; b0 < n_blocks; b0 += kMaskThreads) {
+            const u32x2 none = {0u, 0u};
+            const u32x2 c = b0 + t < n_blocks ? block_cnt[b0 + t] : none;
+            uint64_t total;
+            const uint64_t ex = block_excl_scan64<kMaskThreads>(pack2(c.x, c.y), lds.scan, total);
+            const uint32_t g = gt_before + (uint32_t)(ex >> 32), q = eq_before + (uint32_t)ex;
+            if (reaches_in(g, q, c)) {
+                const uint32_t at = atomicAdd(&lds.n_blocks, 1u);
+                lds.blocks[3 * at + 0] = b0 + t;
+                lds.blocks[3 * at + 1] = g;
+                lds.blocks[3 * at + 2] = q;
+            }
+            gt_before += (uint32_t)(total >> 32);
+            eq_before += (uint32_t)total;
+            __syncthreads();                          // lds.scan is reused by the next pass
+            if (gt_before + min(eq_before, take_eq) >= k1) break;   // uniform: the rest lies behind this workgroup's positions
+        }
+        __syncthreads();
+        // second level: the stretches of those blocks (16 each), one wavefront per block
+        constexpr uint32_t kSubs = kMaskThreads / kWave;
+        const uint32_t n_blk = lds.n_blocks;
+        for (uint32_t i = wave; i < n_blk; i += kSubs) {
+            const uint32_t b = lds.blocks[3 * i];
+            const u32x2 none = {0u, 0u};
+            const u32x2 c = lane < kSubs ? sub_cnt[(size_t)b * kSubs + lane] : none;
+            const uint64_t both = pack2(c.x, c.y);
+            const uint64_t ex = wave_incl_scan64(both) - both;
+            const uint32_t g = lds.blocks[3 * i + 1] + (uint32_t)(ex >> 32), q = lds.blocks[3 * i + 2] + (uint32_t)ex;
+            if (lane < kSubs && reaches_in(g, q, c)) {
+                const uint32_t at = atomicAdd(&lds.n_need, 1u);
+                lds.need[3 * at + 0] = b * kSubs + lane;
+                lds.need[3 * at + 1] = g;
+                lds.need[3 * at + 2] = q;
+            }
+        }
+        __syncthreads();
+        // one wavefront per needed stretch: its 1024 Q vote bytes, lane l owning bytes [16 Q l, 16 Q l + 16 Q)
+        const uint32_t n_need = lds.n_need;
+        for (uint32_t i = wave; i < n_need; i += kSubs) {
+            const uint32_t sidx = lds.need[3 * i];
+            const int64_t j0 = ((int64_t)sidx * kWave + lane) * (16 * Q);
+            uint32_t ww[4 * Q];
+#pragma unroll
+            for (int q = 0; q < Q; ++q) {
+                const int64_t j = j0 + q * 16;
+                const u32x4 z = {0u, 0u, 0u, 0u};
+                const u32x4 w = (j < d) ? *reinterpret_cast<const u32x4*>(votes32 + (j >> 2)) : z;
+                ww[4 * q + 0] = w.x; ww[4 * q + 1] = w.y; ww[4 * q + 2] = w.z; ww[4 * q + 3] = w.w;
+            }
+            uint32_t gt, eq;
+            count_above_and_at<Q>(ww, j0, d, vstar, gt, eq);
+            const uint64_t both = pack2(gt, eq);
+            const uint64_t ex = wave_incl_scan64(both) - both;
+            uint32_t g0 = lds.need[3 * i + 1] + (uint32_t)(ex >> 32), e0 = lds.need[3 * i + 2] + (uint32_t)ex;
+#pragma unroll
+            for (int q = 0; q < 4 * Q; ++q) {
+                if (vstar != 0u && __ballot(ww[q] != 0u) == 0ull) continue;   // wave-uniform: no vote in this word
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    const uint32_t v = (ww[q] >> (8 * b)) & 255u;
+                    const int64_t j = j0 + 4 * q + b;
+                    const bool inside = j < d;
+                    const bool is_gt = inside && v > vstar, is_eq = inside && v == vstar;
+                    if (is_gt || (is_eq && e0 < take_eq)) {
+                        const uint32_t pos = g0 + min(e0, take_eq);
+                        if (pos >= k0 && pos < k1) {
+                            lds.slice[pos - k0] = (uint32_t)j;
+                            mask_idx[pos] = (uint32_t)j;
+                        }
+                    }
+                    g0 += is_gt;
+                    e0 += is_eq;
+                }
+            }
+        }
+    } else {
+        for (uint32_t k = k0 + t; k < k1; k += kMaskThreads) lds.slice[k - k0] = mask_idx[k];
+    }
+    __syncthreads();
+
     const uint32_t kl = t / N, n = t % N;
     const uint32_t pitch = N + 1;                     // kb * (N + 1) <= 1024 + kb <= 1536
-    // rounds coordinates of kb each per workgroup; a thread's loads of all rounds are in flight together
-    constexpr int kMaxRounds = 4;
-    const uint32_t k0 = blockIdx.x * kb * rounds;
-    uint32_t j[kMaxRounds];
-    float v[kMaxRounds];
+    // a thread's loads of all rounds are in flight together
+    float v[kGatherRounds];
 #pragma unroll
-    for (int r = 0; r < kMaxRounds; ++r) {
+    for (int r = 0; r < kGatherRounds; ++r) {
         const uint32_t k = k0 + (uint32_t)r * kb + kl;
-        j[r] = ((uint32_t)r < rounds && kl < kb && k < K) ? mask_idx[k] : 0xFFFFFFFFu;
-    }
-#pragma unroll
-    for (int r = 0; r < kMaxRounds; ++r) {
+        const uint32_t j = ((uint32_t)r < rounds && kl < kb && k < k1) ? lds.slice[k - k0] : 0xFFFFFFFFu;
         v[r] = 0.0f;
-        if ((int64_t)j[r] < d) {                      // always true for a mask built by mv_mask_emit
-            float* p = e + (int64_t)n * ld_e + j[r];
+        if ((int64_t)j < d) {                         // always true for a mask built above
+            float* p = e + (int64_t)n * ld_e + j;
             v[r] = *p;
             *p = 0.0f;
         }
     }
 #pragma unroll
-    for (int r = 0; r < kMaxRounds; ++r) {
+    for (int r = 0; r < kGatherRounds; ++r) {
         if ((uint32_t)r >= rounds) break;             // uniform over the workgroup
-        if (kl < kb) tile[kl * pitch + n] = v[r];
+        if (kl < kb) lds.tile[kl * pitch + n] = v[r];
         __syncthreads();
         if (t < kb) {
             const uint32_t kk = k0 + (uint32_t)r * kb + t;
-            if (kk < K) {
-                float s = tile[t * pitch];            // worker 0
-                for (uint32_t m = 1; m < N; ++m) s = s + tile[t * pitch + m];
+            if (kk < k1) {
+                float s = lds.tile[t * pitch];        // worker 0
+                for (uint32_t m = 1; m < N; ++m) s = s + lds.tile[t * pitch + m];
                 agg[kk] = apply_scale ? s * scale : s;
             }
         }

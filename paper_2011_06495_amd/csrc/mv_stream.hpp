@@ -189,7 +189,8 @@ __global__ __launch_bounds__(kStreamThreads) void mv_stream_collect(
     uint32_t n_lvl_words, uint32_t* __restrict__ ad_count,
     u32x2* __restrict__ cand, uint32_t cap, uint32_t* __restrict__ row_count_sets, uint32_t row_count_set_words,
     u32x2* __restrict__ seg,
-    uint32_t* __restrict__ seg_sel, uint32_t nseg, uint32_t wgs_per_row, uint32_t head_wgs)
+    uint32_t* __restrict__ seg_sel, uint32_t nseg, uint32_t wgs_per_row, uint32_t head_wgs,
+    uint32_t* __restrict__ zero_votes32, int64_t votes_bytes)
 {
     MV_SPAN(2);
     __shared__ StreamLds lds;
@@ -349,6 +350,13 @@ __global__ __launch_bounds__(kStreamThreads) void mv_stream_collect(
                         crow[pos] = rec;
                     }
                 }
+    }
+    // Row 0's wavefronts pass over every coordinate once: they also clear the packed vote bytes
+    // (one per coordinate, 16 per lane), which the kernels that follow fill and read.
+    if (zero_votes32 && row == 0 && live) {
+        const int64_t j = base + (int64_t)lane * 16;
+        const u32x4 z = {0u, 0u, 0u, 0u};
+        if (j < votes_bytes) *reinterpret_cast<u32x4*>(zero_votes32 + (j >> 2)) = z;
     }
     if (live && lane == 0) {
         u32x2 rec;
