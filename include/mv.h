@@ -16,7 +16,14 @@
  * say how ties are broken.  Here ties go to the LOWEST index, both for the
  * magnitudes of a row and for the vote counts.  "Highest absolute value" is the
  * order of the fp32 bit pattern with the sign bit cleared (so -0 == +0,
- * denormals are ordered and never flushed, +Inf is above all finite values).
+ * denormals are ordered and never flushed, and an infinity of either sign is
+ * above all finite values; equal infinities tie like any equal magnitudes).
+ * Infinite values are handled exactly as long as no NaN arises from them
+ * (Inf - Inf in g + e or in the sum over workers).  NaN, given or arising, is
+ * outside the contract: the values written are then unspecified (a NaN's
+ * payload after an addition is the processor's choice); the call still ends,
+ * every index written is a coordinate below d, index lists stay ascending and
+ * nothing outside the output arrays is touched.
  *
  * All tensor pointers are DEVICE pointers owned by the caller.  The library
  * keeps none of them after a call returns, except cfg.workspace, which must
@@ -176,7 +183,9 @@ mv_status mv_ad_vote_step(mv_ctx* ctx,
                           void* stream);
 
 /*
- * Ends the context: waits for the device, frees scratch the context allocated
+ * Ends the context: waits for the stream of the context's last step (steps are
+ * serialized by the caller, so that is the only one with work of this context
+ * still in flight), frees scratch the context allocated
  * (never cfg.workspace).  The handle stays a valid pointer so that a later
  * mv_vote_step / mv_end on it reports MV_ERR_STATE; mv_release frees it.
  */

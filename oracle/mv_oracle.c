@@ -622,11 +622,15 @@ int64_t mvo_codec_encode(const uint32_t* idx, int64_t n, int64_t d, int64_t bloc
     return (int64_t)total;
 }
 
-/* Decoder, as the receiver of Sec. 4.3.1 reads the stream: a 1 bit -> read the
- * next B bits as the position inside the current block; a 0 bit -> next block;
- * until the cursor reaches the end of the stream.  Returns the number of
- * positions written to idx_out, or -1 (more than max_n positions, a position
- * outside its block or the vector, or a truncated code). */
+/* Decoder (the receiving side of the code of Sec. 4.3.1).  It keeps a cursor into
+ * the stream and the number of the block it is in, starting at block 0.  A set
+ * bit under the cursor announces a position: the B bits behind it are that
+ * position's offset inside the current block, so the coordinate is
+ * block * block_len + offset.  A clear bit ends the current block and the next
+ * one begins.  Decoding stops when the cursor has passed n_bits.  Returns the
+ * number of positions written to idx_out, or -1 (more than max_n positions, a
+ * position outside its block or the vector, or an offset cut short by the end
+ * of the stream). */
 int64_t mvo_codec_decode(const uint32_t* words, int64_t n_bits, int64_t d, int64_t block_len,
                          uint32_t* idx_out, int64_t max_n)
 {

@@ -745,7 +745,8 @@ mv_status mv_end(mv_ctx* c)
     DeviceGuard guard(c->cfg.device);
     if (!guard.ok) return MV_ERR_DEVICE;
     mv_status rc = MV_OK;
-    if (hipDeviceSynchronize() != hipSuccess) rc = MV_ERR_DEVICE;
+    // steps run in the order of their calls, so the last call's stream is the one that still holds work
+    if (c->steps_done != 0 && hipStreamSynchronize(c->last_stream) != hipSuccess) rc = MV_ERR_DEVICE;
     for (int r = 0; r < kEventRing; ++r)
         for (int i = 0; i < KID_COUNT; ++i)
             for (int j = 0; j < 2; ++j)
@@ -831,29 +832,6 @@ mv_status mv_last_step_row_stats(mv_ctx* c, uint32_t* cand_count, uint32_t* thre
         return MV_ERR_DEVICE;
     return MV_OK;
 }
-
-#ifdef MV_PHASE_STAMPS
-int mv_debug_spans(unsigned long long* host)
-{
-    if (hipDeviceSynchronize() != hipSuccess) return -1;
-    if (hipMemcpyFromSymbol(host, HIP_SYMBOL(mvk::g_span), sizeof(unsigned long long) * 16 * 4096 * 2) != hipSuccess)
-        return -1;
-    void* dev = nullptr;
-    if (hipGetSymbolAddress(&dev, HIP_SYMBOL(mvk::g_span)) != hipSuccess) return -1;
-    if (hipMemset(dev, 0, sizeof(unsigned long long) * 16 * 4096 * 2) != hipSuccess) return -1;
-    return 0;
-}
-int mv_debug_stamps(unsigned long long* host, int n)
-{
-    if (n > 2 * 16 * 32) n = 2 * 16 * 32;
-    if (hipDeviceSynchronize() != hipSuccess) return -1;
-    if (hipMemcpyFromSymbol(host, HIP_SYMBOL(mvk::g_stamps), (size_t)n * 8) != hipSuccess) return -1;
-    void* dev = nullptr;
-    if (hipGetSymbolAddress(&dev, HIP_SYMBOL(mvk::g_stamps)) != hipSuccess) return -1;
-    if (hipMemset(dev, 0, sizeof(unsigned long long) * 2 * 16 * 32) != hipSuccess) return -1;
-    return n;
-}
-#endif
 
 mv_status mv_probe_copy(void* dst, const void* src, size_t bytes, void* stream)
 {

@@ -357,19 +357,12 @@ mv_status mv_codec_encode(const uint32_t* idx, int64_t ld_idx, const uint32_t* c
     return hipGetLastError() == hipSuccess ? MV_OK : MV_ERR_DEVICE;
 }
 
-mv_status mv_codec_decode(const uint32_t* streams, int64_t ld_words, const uint64_t* n_bits, uint64_t max_bits,
-                          int32_t rows, int64_t d, int64_t block_len, uint32_t* idx_out, int64_t ld_idx,
-                          int64_t max_n, uint32_t* counts_out, void* scratch, size_t scratch_bytes, void* stream)
+static mv_status decode_with_scratch(const uint32_t* streams, int64_t ld_words, const uint64_t* n_bits,
+                                     uint64_t max_bits, int32_t rows, int64_t d, int64_t block_len,
+                                     uint32_t* idx_out, int64_t ld_idx, int64_t max_n, uint32_t* counts_out,
+                                     void* scratch, void* stream)
 {
-    if (!streams || !n_bits || !idx_out || !counts_out || !scratch || rows < 1 || rows > 65535)
-        return MV_ERR_INVALID_ARG;
-    if (d < 1 || d > 0x7FFFFFFFll || block_len < 1 || block_len > d || max_n < 0 || ld_idx < max_n ||
-        max_n > 0xFFFFFFFFll)
-        return MV_ERR_INVALID_ARG;
-    if ((uint64_t)ld_words * 32 < max_bits) return MV_ERR_INVALID_ARG;
-    if (scratch_bytes < mv_codec_scratch_bytes(max_bits, rows)) return MV_ERR_INVALID_ARG;
     const uint64_t max_chunks = (max_bits + mvc::kChunkBits - 1) / mvc::kChunkBits;
-    if (max_chunks == 0) return MV_ERR_INVALID_ARG;
     uintptr_t base = (reinterpret_cast<uintptr_t>(scratch) + 255) & ~(uintptr_t)255;
     uint8_t* maps = reinterpret_cast<uint8_t*>(base);
     const size_t maps_bytes = ((size_t)rows * max_chunks * 3 * (mvc::kMaxB + 1) + 255) & ~(size_t)255;
@@ -389,6 +382,30 @@ mv_status mv_codec_decode(const uint32_t* streams, int64_t ld_words, const uint6
                        streams, ld_words, nb, max_bits, d, (uint32_t)block_len, B, entries, max_chunks, idx_out,
                        ld_idx, (uint32_t)max_n);
     return hipGetLastError() == hipSuccess ? MV_OK : MV_ERR_DEVICE;
+}
+
+static bool decode_args_valid(const uint32_t* streams, int64_t ld_words, const uint64_t* n_bits, uint64_t max_bits,
+                              int32_t rows, int64_t d, int64_t block_len, const uint32_t* idx_out, int64_t ld_idx,
+                              int64_t max_n, const uint32_t* counts_out)
+{
+    if (!streams || !n_bits || !idx_out || !counts_out || rows < 1 || rows > 65535) return false;
+    if (d < 1 || d > 0x7FFFFFFFll || block_len < 1 || block_len > d || max_n < 0 || ld_idx < max_n ||
+        max_n > 0xFFFFFFFFll)
+        return false;
+    if (ld_words < 0 || (uint64_t)ld_words * 32 < max_bits) return false;
+    return max_bits != 0;
+}
+
+mv_status mv_codec_decode(const uint32_t* streams, int64_t ld_words, const uint64_t* n_bits, uint64_t max_bits,
+                          int32_t rows, int64_t d, int64_t block_len, uint32_t* idx_out, int64_t ld_idx,
+                          int64_t max_n, uint32_t* counts_out, void* scratch, size_t scratch_bytes, void* stream)
+{
+    if (!scratch || !decode_args_valid(streams, ld_words, n_bits, max_bits, rows, d, block_len, idx_out, ld_idx,
+                                       max_n, counts_out))
+        return MV_ERR_INVALID_ARG;
+    if (scratch_bytes < mv_codec_scratch_bytes(max_bits, rows)) return MV_ERR_INVALID_ARG;
+    return decode_with_scratch(streams, ld_words, n_bits, max_bits, rows, d, block_len, idx_out, ld_idx, max_n,
+                               counts_out, scratch, stream);
 }
 
 }  // extern "C"

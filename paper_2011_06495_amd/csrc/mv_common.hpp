@@ -30,47 +30,6 @@ constexpr uint32_t kAbsMask        = 0x7FFFFFFFu;
 constexpr int      kFineBins       = 2048;   // mv_row_select: histogram of the candidates' magnitudes above tau
 constexpr int      kFineShift      = 12;     // 2048 bins of 4096 bit patterns = one octave above tau
 
-#ifdef MV_PHASE_STAMPS
-// development aid: wall-clock stamps (100 MHz) of the first and the last workgroup of a kernel
-__device__ unsigned long long g_stamps[2 * 16 * 32];
-#define MV_STAMP(k, i)                                                                              \
-    do {                                                                                            \
-        __builtin_amdgcn_s_waitcnt(0);                                                              \
-        if (threadIdx.x == 0) {                                                                     \
-            if (blockIdx.x == 0 && blockIdx.y == 0) g_stamps[(k) * 32 + (i)] = wall_clock64();      \
-            if (blockIdx.x == gridDim.x - 1 && blockIdx.y == gridDim.y - 1)                         \
-                g_stamps[16 * 32 + (k) * 32 + (i)] = wall_clock64();                                \
-        }                                                                                           \
-    } while (0)
-// stamp by thread 0 of the calling workgroup into bank 0 (no block test)
-#define MV_STAMP_HERE(k, i)                                                                         \
-    do {                                                                                            \
-        __builtin_amdgcn_s_waitcnt(0);                                                              \
-        if (threadIdx.x == 0) g_stamps[(k) * 32 + (i)] = wall_clock64();                            \
-    } while (0)
-// begin and end of every workgroup of kernel k (plain stores; slot = linear block id % 4096)
-__device__ unsigned long long g_span[16 * 4096 * 2];
-struct StampSpan {
-    int k;
-    unsigned long long t0;
-    __device__ __forceinline__ explicit StampSpan(int kk) : k(kk), t0(wall_clock64()) {}
-    __device__ __forceinline__ ~StampSpan()
-    {
-        __builtin_amdgcn_s_waitcnt(0);
-        if (threadIdx.x == 0) {
-            const uint32_t id = (blockIdx.y * gridDim.x + blockIdx.x) % 4096u;
-            g_span[((size_t)k * 4096 + id) * 2] = t0;
-            g_span[((size_t)k * 4096 + id) * 2 + 1] = wall_clock64();
-        }
-    }
-};
-#define MV_SPAN(k) StampSpan stamp_span_(k)
-#else
-#define MV_STAMP(k, i) do {} while (0)
-#define MV_STAMP_HERE(k, i) do {} while (0)
-#define MV_SPAN(k) do {} while (0)
-#endif
-
 // ----------------------------------------------------------------------------
 // small helpers
 // ----------------------------------------------------------------------------

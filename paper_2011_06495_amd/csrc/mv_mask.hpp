@@ -24,7 +24,6 @@ __global__ __launch_bounds__(kRowThreads) void mv_row_votes(
     const uint32_t* __restrict__ slow_flag, uint32_t* __restrict__ seg_sel,
     uint32_t* __restrict__ votes32, uint32_t* __restrict__ lvl_sets)
 {
-    MV_SPAN(4);
     __shared__ uint32_t lvl[257];
     const uint32_t row = blockIdx.y;
     const uint32_t kth = kth_in[row], tie_cut = tie_cut_in[row];
@@ -172,7 +171,6 @@ __global__ __launch_bounds__(kMaskThreads) void mv_mask_count(const uint32_t* __
                                                               uint32_t* __restrict__ emit_fail, uint32_t spin_limit,
                                                               uint32_t* __restrict__ mask_idx)
 {
-    MV_SPAN(5);
     __shared__ uint32_t lvl[256];
     __shared__ uint32_t thr[2];
     __shared__ uint64_t scan_lds[kMaskThreads / kWave + 1];
@@ -471,7 +469,6 @@ __global__ __launch_bounds__(kMaskThreads) void mv_gather_update(float* __restri
                                                                  uint32_t* __restrict__ worker_idx,
                                                                  uint32_t* __restrict__ step_no)
 {
-    MV_SPAN(7);
     __shared__ GatherLds lds;
     if (blockIdx.x >= n_gather_blocks) {
         const uint32_t b = blockIdx.x - n_gather_blocks;

@@ -349,15 +349,12 @@ __device__ __forceinline__ void select_among_candidates(const Keys& keys, const 
             for (int b = t; b < kFineBins * kRep / 4; b += kRowThreads) rz[b] = z;
         }
         __syncthreads();
-        MV_STAMP(3, 2);
         keys.each([&](uint32_t k, uint64_t, bool valid) {
             if (valid) atomicAdd(&lds.rhist[fine_bin(k, tau) * kRep + (lane & (kRep - 1))], 1u);
         });
         __syncthreads();
-        MV_STAMP(3, 3);
         uint32_t bin, want, in_bin;
         find_rank_bin<kFineBins, kRep>(lds.rhist, lds.scan, lds.bcast, K, bin, want, in_bin);
-        MV_STAMP(3, 4);
         if (in_bin <= (uint32_t)kRankCap) {       // uniform
             // few candidates in that bin: rank them by brute force under (magnitude desc,
             // coordinate asc); the one with exactly want-1 others ahead is the last of the top K
@@ -388,7 +385,6 @@ __device__ __forceinline__ void select_among_candidates(const Keys& keys, const 
             __syncthreads();
             kth = lds.bcast[0];
             tie_cut = lds.bcast[1];
-            MV_STAMP(3, 5);
             return;
         }
         if (Keys::kCheapPasses && in_bin <= (uint32_t)kKeyBins) {   // uniform; an extra pass only where passes are cheap
@@ -408,11 +404,9 @@ __device__ __forceinline__ void select_among_candidates(const Keys& keys, const 
             const bool one_key = lds.bcast[0] == 0u && lds.bcast[1] == 0xFFFFFFFFu;   // nobody differed from hist[0]
             const uint32_t the_key = lds.hist[0];
             __syncthreads();
-            MV_STAMP(3, 6);
             if (one_key) {                                           // uniform
                 kth = the_key;
                 tie_cut = want < in_bin ? smallest_coordinate(lds, in_bin, want) : 0xFFFFFFFFu;
-                MV_STAMP(3, 7);
                 return;
             }
             if (t == 0) lds.n_list = 0;                              // distinct keys: go on below
@@ -570,7 +564,6 @@ __device__ __forceinline__ bool select_from_bins(const PackedBins<KEEP>& bins, c
     static_assert(kFineBins * kRep >= 3 * kKeyBins, "the members' lists reuse the histogram's storage");
     const uint32_t lane = lane_id(), t = threadIdx.x;
     // (the caller has zeroed lds.rhist and lds.n_list, and a barrier has passed since)
-    MV_STAMP(3, 2);
     // Values on a lattice put thousands of candidates on a few dozen keys, and LDS
     // atomics of one instruction that meet on one address are served one after the
     // other: lane l adds to copy l % kRep of the histogram, which divides those queues.
@@ -578,10 +571,8 @@ __device__ __forceinline__ bool select_from_bins(const PackedBins<KEEP>& bins, c
         if (bin != 0xFFFFu) atomicAdd(&lds.rhist[bin * kRep + (lane & (kRep - 1))], 1u);
     });
     __syncthreads();
-    MV_STAMP(3, 3);
     uint32_t bin, want, in_bin;
     find_rank_bin<kFineBins, kRep>(lds.rhist, lds.scan, lds.bcast, K, bin, want, in_bin);
-    MV_STAMP(3, 4);
     if (in_bin > (uint32_t)kKeyBins) return false;                  // uniform
     // the last bin is open-ended: its members' keys do not fit the exact-key histogram
     if (in_bin > (uint32_t)kRankCap && bin == (uint32_t)(kFineBins - 1)) return false;
@@ -603,7 +594,6 @@ __device__ __forceinline__ bool select_from_bins(const PackedBins<KEEP>& bins, c
         mpos[p] = c.y;                            // from here on: the member's coordinate
     }
     __syncthreads();
-    MV_STAMP(3, 5);
     if (in_bin <= (uint32_t)kRankCap) {           // uniform
         // few members: ranked by counting under (magnitude desc, coordinate asc);
         // the one with exactly want-1 others ahead is the last of the top K
@@ -634,7 +624,6 @@ __device__ __forceinline__ bool select_from_bins(const PackedBins<KEEP>& bins, c
         kth = lds.bcast[0];
         tie_cut = lds.bcast[1];
         __syncthreads();
-        MV_STAMP(3, 6);
         return true;
     }
     // Values on a lattice put hundreds of EQUAL magnitudes there: if all members share one
@@ -655,7 +644,6 @@ __device__ __forceinline__ bool select_from_bins(const PackedBins<KEEP>& bins, c
         kth = mkey[0];
         __syncthreads();                          // everyone has read bcast and mkey
         tie_cut = want < in_bin ? smallest_coordinate(lds, in_bin, want) : 0xFFFFFFFFu;
-        MV_STAMP(3, 7);
         return true;
     }
     // up to 4096 members: the bin spans exactly 4096 key values, so a histogram over the
@@ -685,7 +673,6 @@ __device__ __forceinline__ bool select_from_bins(const PackedBins<KEEP>& bins, c
         __syncthreads();
         tie_cut = smallest_coordinate(lds, n_eq, take_eq);
     }
-    MV_STAMP(3, 7);
     return true;
 }
 
@@ -719,14 +706,12 @@ __global__ __launch_bounds__(kRowThreads) void mv_row_select(
     uint32_t* __restrict__ seg_sel, uint32_t nseg, uint32_t* __restrict__ lvl_sets,
     uint32_t* __restrict__ slow_flag, uint32_t parts, uint32_t n_spec, int thresholds_only, int slow_rows_only)
 {
-    MV_SPAN(3);
     __shared__ SelectLds lds;
     const uint32_t t = threadIdx.x;
     const uint32_t within = blockIdx.x % (8u * parts);
     const uint32_t row = (blockIdx.x / (8u * parts)) * 8u + within % 8u, part = within / 8u;
     if (row >= N) return;                         // whole workgroup
     const u32x2* crow = cand + (size_t)row * cap;
-    MV_STAMP(3, 0);
     uint32_t raw[kSpec];
 #pragma unroll
     for (int q = 0; q < kSpec; ++q) {
@@ -749,7 +734,6 @@ __global__ __launch_bounds__(kRowThreads) void mv_row_select(
     }
     __builtin_amdgcn_sched_barrier(0);
     __syncthreads();
-    MV_STAMP(3, 1);
     if (poisoned) C = kRowPoison | C;             // reads as overflowed, here and for every later reader
     if (part == 0 && t == 0) {                    // for the kernels that follow, and the row statistics
         cand_count[row] = C;
@@ -796,7 +780,6 @@ __global__ __launch_bounds__(kRowThreads) void mv_row_select(
             tie_cut_out[row] = tie_cut;
             if (path) slow_flag[row] = path;      // diagnostic only
         }
-        MV_STAMP(3, 8);
         if (!thresholds_only) {
             for (int i = t; i < 257; i += kRowThreads) lds.lvl[i] = 0;
             __syncthreads();
@@ -805,7 +788,6 @@ __global__ __launch_bounds__(kRowThreads) void mv_row_select(
             __syncthreads();
             merge_levels(lds.lvl, lvl_sets, blockIdx.x);
         }
-        MV_STAMP(3, 9);
         return;
     }
 
@@ -1033,13 +1015,11 @@ __device__ __forceinline__ bool list_rank_body(const ListSelect& a, uint32_t row
 // ---- the rows' top-K when K is large (grid: blocks of the candidate list x rows)
 __global__ __launch_bounds__(kRowThreads) void mv_sel_hist(ListSelect a)
 {
-    MV_SPAN(8);
     __shared__ uint32_t hist[kSelBins];
     list_hist_body(a, blockIdx.y, hist);
 }
 __global__ __launch_bounds__(kRowThreads) void mv_sel_split(ListSelect a)
 {
-    MV_SPAN(9);
     __shared__ ListSplitLds lds;
     list_split_body(a, blockIdx.y, lds, nullptr);
 }
@@ -1047,7 +1027,6 @@ __global__ __launch_bounds__(kRowThreads) void mv_sel_rank(ListSelect a, uint32_
                                                            uint32_t* __restrict__ tie_cut_out,
                                                            uint32_t* __restrict__ slow_flag)
 {
-    MV_SPAN(10);
     __shared__ SelectLds lds;
     const uint32_t row = blockIdx.x;
     uint32_t kth, tie_cut, path;

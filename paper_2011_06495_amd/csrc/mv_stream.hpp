@@ -75,7 +75,6 @@ __device__ __forceinline__ void sample_and_pick(StreamLds& lds, const GT* __rest
                                                 uint32_t* __restrict__ ad_count)
 {
     const uint32_t t = threadIdx.x;
-    if (row == 0 && part == 0) MV_STAMP_HERE(0, 0);
     for (int b = t; b < kHistBins; b += kStreamThreads) lds.h[b] = 0;
     __syncthreads();
     const GT*    grow = g + (int64_t)row * ld_g;
@@ -119,7 +118,6 @@ __device__ __forceinline__ void sample_and_pick(StreamLds& lds, const GT* __rest
     // every sample of this workgroup has been used, so it has arrived: the row's streaming
     // wavefronts may overwrite e as far as this workgroup is concerned
     if (t == 0) atomicAdd(&reads_done[row * kCounterStride], 1u);
-    if (row == 0 && part == 0) MV_STAMP_HERE(0, 1);
     uint32_t* hrow = hist + (size_t)row * kHistBins;
     for (int b = t; b < kHistBins; b += kStreamThreads) {
         const uint32_t c = lds.h[b];
@@ -131,9 +129,7 @@ __device__ __forceinline__ void sample_and_pick(StreamLds& lds, const GT* __rest
     __syncthreads();
     if (t == 0) lds.is_last = atomicAdd(&sample_done[row * kCounterStride], 1u) == spr - 1u;
     __syncthreads();
-    if (row == 0 && part == 0) MV_STAMP_HERE(0, 2);
     if (!lds.is_last) return;                     // whole workgroup
-    if (row == 0) MV_STAMP_HERE(1, 0);
 
     // ---- the row's last sampling workgroup: histogram -> tau
     constexpr int per = kHistBins / kStreamThreads;   // bins per thread, descending bin order
@@ -147,7 +143,6 @@ __device__ __forceinline__ void sample_and_pick(StreamLds& lds, const GT* __rest
 #pragma unroll
     for (int q = 0; q < per; ++q) sum += c[q];
     if (t == 0) lds.found = 0;
-    if (row == 0) MV_STAMP_HERE(1, 1);
     uint64_t total;
     const uint64_t excl = block_excl_scan64<kStreamThreads>(sum, lds.scan, total);
     if (excl < m_target && (uint64_t)m_target <= excl + sum) {
@@ -165,7 +160,6 @@ __device__ __forceinline__ void sample_and_pick(StreamLds& lds, const GT* __rest
         __hip_atomic_store(&tau_pub[row * (kCounterStride / 2)], ((unsigned long long)epoch << 32) | tau,
                            __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    if (row == 0) MV_STAMP_HERE(1, 2);
     // Behind the publication, what the NEXT step's kernel must find at zero (ordinary stores: they
     // are in memory when this kernel has ended): the histogram, the sampling counter, the row's
     // candidate counter of the other parity (this step's streaming workgroups bump row_count; the
@@ -192,7 +186,6 @@ __global__ __launch_bounds__(kStreamThreads) void mv_stream_collect(
     uint32_t* __restrict__ seg_sel, uint32_t nseg, uint32_t wgs_per_row, uint32_t head_wgs,
     uint32_t* __restrict__ zero_votes32, int64_t votes_bytes)
 {
-    MV_SPAN(2);
     __shared__ StreamLds lds;
     // The step's number lives on the device (the step's last kernel counts it up), so that a
     // captured step can be replayed; the rows' candidate counters exist twice, and this step
@@ -217,18 +210,10 @@ __global__ __launch_bounds__(kStreamThreads) void mv_stream_collect(
     const unsigned long long* tau_at = tau_pub + row * (kCounterStride / 2);
     // a first look at the row's tau together with the data loads: after the kernel's first
     // microseconds it is there, and the wavefront never waits
-#ifdef EXP_NOPOLL
-    unsigned long long tw = *tau_at;
-#else
     unsigned long long tw = __hip_atomic_load(tau_at, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-#endif
     const uint32_t* rd_at = reads_done + row * kCounterStride;
     const uint32_t rd_target = spr * epoch;       // the counter grows by spr per step and wraps with this product
-#ifdef EXP_NOPOLL
-    uint32_t rd = rd_target;
-#else
     uint32_t rd = __hip_atomic_load(rd_at, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-#endif
     uint32_t spins = 0;
     // (all lanes of a wavefront load the same words, so the waits below are wave-uniform)
     auto samples_are_in = [&]() {
@@ -241,10 +226,7 @@ __global__ __launch_bounds__(kStreamThreads) void mv_stream_collect(
 
     // The kernel's first streaming workgroups would compete with the sampling for the memory
     // system and delay the estimate for everybody: they hold back even their loads.
-    const int sk = sb == 0 ? 4 : sb == 1500 ? 5 : sb == 4000 ? 6 : sb == 1365 * 15 ? 8 : -1;
-    if (sk >= 0) MV_STAMP_HERE(sk, 0);
     if (sb < head_wgs) samples_are_in();
-    if (sk >= 0) MV_STAMP_HERE(sk, 1);
 
     uint32_t key[16];
     uint32_t inside = 0;                          // bit i: key[i] is a coordinate of the row
@@ -289,14 +271,12 @@ __global__ __launch_bounds__(kStreamThreads) void mv_stream_collect(
             }
     }
 
-    if (sk >= 0) MV_STAMP_HERE(sk, 2);
     // tau: wait for it if need be (bounded), then the candidates' flags
     while ((uint32_t)(tw >> 32) != epoch && spins < spin_limit) {
         __builtin_amdgcn_s_sleep(16);
         tw = __hip_atomic_load(tau_at, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         ++spins;
     }
-    if (sk >= 0) MV_STAMP_HERE(sk, 3);
     uint32_t tau = (uint32_t)tw;
     if ((uint32_t)(tw >> 32) != epoch) {                               // not seen in time: the row goes the exact way
         tau = 0xFFFFFFFFu;                                             // above every key
@@ -365,7 +345,6 @@ __global__ __launch_bounds__(kStreamThreads) void mv_stream_collect(
         seg[(size_t)row * nseg + s] = rec;
         seg_sel[(size_t)row * nseg + s] = 0;     // tallied when the votes are cast
     }
-    if (sk >= 0) MV_STAMP_HERE(sk, 4);
 }
 
 }  // namespace mvk

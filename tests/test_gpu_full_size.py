@@ -116,6 +116,12 @@ def test_add_drop_paper_regime_full(oracle):
     run_full_ad(oracle, w, [w.K, 11174, 11174])
 
 
+@pytest.mark.timeout(1200)
+def test_add_drop_c5_full_bf16(oracle):
+    # the largest workload (102 M coordinates, bf16 gradients): a full first vote, then phi_ad = phi / 10
+    run_full_ad(oracle, W.C5, [W.C5.K, W.C5.K // 10])
+
+
 # ---- majority voting with random selection (Algorithm 1, S_rand-weighted) at full size
 
 def run_full_rs(oracle, w, steps):

@@ -119,17 +119,94 @@ def test_row_stride_larger_than_d_and_padding_untouched(oracle):
     run_sequence(oracle, w, 2, extra_ld=5)
 
 
-def test_sum_reduction(oracle):
-    w = W.C2.with_size(40001, N=7)
-    say("sum reduction")
-    g = W.gradients(w, 0)
+@pytest.mark.parametrize("w", [W.C2.with_size(40001, N=7), W.C2.with_size(20011, N=255), W.C5.with_size(60005, N=5)],
+                         ids=["f32_N7", "f32_N255", "bf16_N5"])
+def test_sum_reduction(oracle, w):
+    say("sum reduction N=%d d=%d K=%d %s" % (w.N, w.d, w.K, w.grad_dtype))
     e = W.zero_error(w)
-    with GpuStepper(w.N, w.d, w.K, reduce=B.MV_REDUCE_SUM) as gs:
+    with GpuStepper(w.N, w.d, w.K, bf16=(w.grad_dtype == "bf16"), reduce=B.MV_REDUCE_SUM) as gs:
+        gs.set_error(e)
+        for t in range(2):                                                 # the second step with a carried error
+            g = W.gradients(w, t)
+            gs.set_grads(g)
+            gs.step()
+            got = gs.fetch()
+            ref = oracle.vote_step(g, e, w.K, reduce_mean=False)
+            assert_matches_oracle(got, ref, "sum, step %d" % t)
+            e = ref.err
+
+
+def test_infinite_magnitudes_are_ordered_above_finite(oracle):
+    """+-Inf is a magnitude like any other, above every finite one; equal infinities go to the
+    lowest coordinate.  (Coordinates where Inf - Inf would arise are outside the contract and
+    not produced here: at a coordinate the infinities of all workers have one sign.)"""
+    N, d, K = 3, 70001, 500
+    say("infinities N=%d d=%d K=%d" % (N, d, K))
+    rng = np.random.default_rng(11)
+    g0 = rng.standard_normal((N, d)).astype(np.float32)
+    sign = np.where(rng.integers(0, 2, size=d) == 1, np.float32(np.inf), np.float32(-np.inf))
+    few = rng.choice(d, size=40, replace=False)
+    g0[0, few] = sign[few]
+    g0[2, few[:25]] = sign[few[:25]]
+    many = rng.choice(d, size=K + 100, replace=False)                      # more infinities than K: ties among them
+    g0[1, many] = sign[many]
+    g1 = rng.standard_normal((N, d)).astype(np.float32)                    # finite: Inf + finite stays Inf
+    e = np.zeros((N, d), np.float32)
+    with GpuStepper(N, d, K) as gs:
+        gs.set_error(e)
+        for t, g in enumerate((g0, g1)):
+            gs.set_grads(g)
+            gs.step()
+            got = gs.fetch()
+            ref = oracle.vote_step(g, e, K)
+            assert not np.isnan(ref.agg).any() and not np.isnan(ref.err).any()
+            assert np.isinf(ref.agg).any()
+            assert_matches_oracle(got, ref, "infinities, step %d" % t)
+            e = ref.err
+        assert np.isinf(e).any()                                           # infinities that lost the vote were carried
+
+
+def test_nan_inputs_end_with_valid_indices():
+    """NaN is outside the contract (its payload after an addition is the processor's choice): the
+    values are then unspecified, but the step ends and every index it writes is a coordinate."""
+    N, d, K = 4, 50003, 300
+    say("NaN N=%d d=%d K=%d" % (N, d, K))
+    rng = np.random.default_rng(12)
+    g = rng.standard_normal((N, d)).astype(np.float32)
+    g[rng.integers(0, N, size=2000), rng.integers(0, d, size=2000)] = np.float32(np.nan)
+    g[1, :400] = np.float32(np.inf)
+    e = np.zeros((N, d), np.float32)
+    e[1, :200] = np.float32(-np.inf)                                       # Inf - Inf
+    with GpuStepper(N, d, K) as gs:
         gs.set_error(e)
         gs.set_grads(g)
         gs.step()
         got = gs.fetch()
-    assert_matches_oracle(got, oracle.vote_step(g, e, w.K, reduce_mean=False), "sum")
+    assert np.all(got.mask_idx < d) and np.all(np.diff(got.mask_idx.astype(np.int64)) > 0)
+    assert np.all(got.worker_idx < d) and np.all(np.diff(got.worker_idx.astype(np.int64), axis=1) > 0)
+    assert got.votes.max() <= N and int(got.votes.sum()) == N * K
+    assert np.all(got.err[:, got.mask_idx].view(np.uint32) == 0)
+
+
+def test_mask_is_exact_when_the_blocks_do_not_wait_for_each_other(oracle):
+    """With no polls allowed, a streaming wavefront that does not find its row's threshold at the
+    first look gives the row to the exact slow path, and a block of the mask kernel that does not
+    find the earlier blocks' counts at the first look leaves the mask to the kernel behind it:
+    slower, and the same result."""
+    w = W.C4.with_size(700001, N=6)
+    say("no polls N=%d d=%d K=%d" % (w.N, w.d, w.K))
+    e = W.zero_error(w)
+    with GpuStepper(w.N, w.d, w.K) as gs:
+        B.mv_set_spin_limit(gs.ctx, 0)
+        gs.set_error(e)
+        for t in range(2):
+            g = W.gradients(w, t)
+            gs.set_grads(g)
+            gs.step()
+            got = gs.fetch()
+            ref = oracle.vote_step(g, e, w.K)
+            assert_matches_oracle(got, ref, "no polls, step %d" % t)
+            e = ref.err
 
 
 def test_optional_outputs_and_caller_workspace(oracle):
