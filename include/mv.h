@@ -292,6 +292,29 @@ mv_status mv_codec_decode(const uint32_t* streams, int64_t ld_words, const uint6
                           int32_t rows, int64_t d, int64_t block_len, uint32_t* idx_out, int64_t ld_idx,
                           int64_t max_n, uint32_t* counts_out, void* scratch, size_t scratch_bytes, void* stream);
 
+/*
+ * mv_codec_decode for callers that cannot allocate device memory and have no
+ * scratch buffer to hand over: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, results and errors as
+ * mv_codec_decode without `scratch` / `scratch_bytes`: the decoder's tables live
+ * in an array of MV_CODEC_STATIC_SCRATCH_BYTES bytes that is part of the
+ * library's device code (every GPU the library runs on holds its own copy from
+ * the first call on it until the process ends).  The call allocates and frees
+ * nothing, on the device or through any library.
+ *   - mv_codec_scratch_bytes(max_bits, rows) must not exceed
+ *     MV_CODEC_STATIC_SCRATCH_BYTES, else MV_ERR_UNSUPPORTED (nothing is enqueued);
+ *     MV_ERR_UNSUPPORTED also for a device number of 64 or more.
+ *   - The array is shared by every call on a GPU, whatever the stream: two calls
+ *     that may overlap in time on one GPU race on it and must be ordered by the
+ *     caller (same stream, or an event between them).  mv_codec_decode with
+ *     buffers of its own has no such limit.
+ *   - Runs on the CURRENT device, enqueued on `stream`.
+ */
+#define MV_CODEC_STATIC_SCRATCH_BYTES (16u << 20)
+mv_status mv_codec_decode_static(const uint32_t* streams, int64_t ld_words, const uint64_t* n_bits,
+                                 uint64_t max_bits, int32_t rows, int64_t d, int64_t block_len, uint32_t* idx_out,
+                                 int64_t ld_idx, int64_t max_n, uint32_t* counts_out, void* stream);
+
 /* ---- fractional quantisation (paper: Sec. 4.3.2) --------------------------- */
 
 /*

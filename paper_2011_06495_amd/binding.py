@@ -23,7 +23,7 @@ ABI_SYMBOLS = (
     "mv_workspace_bytes", "mv_begin", "mv_vote_step", "mv_ad_vote_step", "mv_rs_vote_step", "mv_end", "mv_release", "mv_status_string",
     "mv_kernel_count", "mv_kernel_name", "mv_set_profiling", "mv_set_spin_limit", "mv_step_kernel_ms",
     "mv_last_step_row_stats", "mv_probe_copy",
-    "mv_codec_stream_bits", "mv_codec_scratch_bytes", "mv_codec_encode", "mv_codec_decode",
+    "mv_codec_stream_bits", "mv_codec_scratch_bytes", "mv_codec_encode", "mv_codec_decode", "mv_codec_decode_static",
     "mv_quant_scratch_bytes", "mv_quant_encode", "mv_quant_decode",
 )
 
@@ -100,6 +100,8 @@ def load() -> ctypes.CDLL:
     L.mv_codec_encode.restype = i32
     L.mv_codec_decode.argtypes = [vp, i64, vp, u64, i32, i64, i64, vp, i64, i64, vp, vp, ctypes.c_size_t, vp]
     L.mv_codec_decode.restype = i32
+    L.mv_codec_decode_static.argtypes = [vp, i64, vp, u64, i32, i64, i64, vp, i64, i64, vp, vp]
+    L.mv_codec_decode_static.restype = i32
     L.mv_quant_scratch_bytes.argtypes = [i64, i32, i32]
     L.mv_quant_scratch_bytes.restype = ctypes.c_size_t
     L.mv_quant_encode.argtypes = [vp, i64, i64, i32, i32, vp, i64, vp, vp, ctypes.c_size_t, vp]
@@ -279,6 +281,22 @@ def mv_codec_decode(streams, n_bits, max_bits: int, d: int, block_len: int, idx_
                                 _dev_ptr(scratch), scratch.numel() * scratch.element_size(), stream.cuda_stream)
     if st != MV_OK:
         raise MvError(st, "mv_codec_decode")
+
+
+MV_CODEC_STATIC_SCRATCH_BYTES = 16 << 20
+
+
+def mv_codec_decode_static(streams, n_bits, max_bits: int, d: int, block_len: int, idx_out, max_n: int, counts_out,
+                           stream=None) -> None:
+    """mv_codec_decode on the library's own scratch array: allocates nothing."""
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream(streams.device)
+    st = load().mv_codec_decode_static(_dev_ptr(streams), streams.stride(0), _dev_ptr(n_bits), max_bits,
+                                       streams.shape[0], d, block_len, _dev_ptr(idx_out), idx_out.stride(0), max_n,
+                                       _dev_ptr(counts_out), stream.cuda_stream)
+    if st != MV_OK:
+        raise MvError(st, "mv_codec_decode_static")
 
 
 def mv_quant_scratch_bytes(n: int, rows: int, q: int) -> int:

@@ -22,6 +22,8 @@
 // coordinate = closed blocks * block_len + offset at its place in the list.
 #include "../../include/mv.h"
 
+#include <mutex>
+
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -357,6 +359,35 @@ mv_status mv_codec_encode(const uint32_t* idx, int64_t ld_idx, const uint32_t* c
     return hipGetLastError() == hipSuccess ? MV_OK : MV_ERR_DEVICE;
 }
 
+// ---- the decoder's scratch for callers that cannot allocate -----------------
+// One array per GPU, there from the moment the library's code is loaded on that GPU
+// until the process ends.  In host code the array's name is only a handle for
+// hipGetSymbolAddress; what kernels and copies are given is the address that call
+// returns for the device that is current, kept per device below.
+static __device__ __align__(256) unsigned char scratch[MV_CODEC_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void*      g_scratch_ptr[kMaxDevices];      // the array's address on each device, once asked for
+
+// The address of `scratch` on the current device; asked for once per device.
+mv_status static_scratch_of_current_device(void** out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0) return MV_ERR_DEVICE;
+    if (dev >= kMaxDevices) return MV_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return MV_ERR_DEVICE;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return MV_OK;
+}
+}  // namespace
+
 static mv_status decode_with_scratch(const uint32_t* streams, int64_t ld_words, const uint64_t* n_bits,
                                      uint64_t max_bits, int32_t rows, int64_t d, int64_t block_len,
                                      uint32_t* idx_out, int64_t ld_idx, int64_t max_n, uint32_t* counts_out,
@@ -406,6 +437,22 @@ mv_status mv_codec_decode(const uint32_t* streams, int64_t ld_words, const uint6
     if (scratch_bytes < mv_codec_scratch_bytes(max_bits, rows)) return MV_ERR_INVALID_ARG;
     return decode_with_scratch(streams, ld_words, n_bits, max_bits, rows, d, block_len, idx_out, ld_idx, max_n,
                                counts_out, scratch, stream);
+}
+
+mv_status mv_codec_decode_static(const uint32_t* streams, int64_t ld_words, const uint64_t* n_bits,
+                                 uint64_t max_bits, int32_t rows, int64_t d, int64_t block_len, uint32_t* idx_out,
+                                 int64_t ld_idx, int64_t max_n, uint32_t* counts_out, void* stream)
+{
+    if (!decode_args_valid(streams, ld_words, n_bits, max_bits, rows, d, block_len, idx_out, ld_idx, max_n,
+                           counts_out))
+        return MV_ERR_INVALID_ARG;
+    if (mv_codec_scratch_bytes(max_bits, rows) > (size_t)MV_CODEC_STATIC_SCRATCH_BYTES) return MV_ERR_UNSUPPORTED;
+    void* ptr = nullptr;
+    const mv_status got = static_scratch_of_current_device(&ptr);
+    if (got != MV_OK) return got;
+    // the kernels write every scratch entry they later read: nothing of the last call's contents matters
+    return decode_with_scratch(streams, ld_words, n_bits, max_bits, rows, d, block_len, idx_out, ld_idx, max_n,
+                               counts_out, ptr, stream);
 }
 
 }  // extern "C"
