@@ -367,6 +367,7 @@ def main():
     ev1.record(p.stream)
     torch.cuda.synchronize()
     copy_gbs = 2.0 * src.numel() * 4 * 10 / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
+    copy_bytes_each_way = src.numel() * 4
     del src, dst
 
     coords = float(N) * float(d)
@@ -382,6 +383,7 @@ def main():
                     "traffic": traffic, "traffic_source": traffic_src,
                     "avg_kernel_ms": round(avg_ms, 4), "kernel_launches_timed": len(dom_ms),
                     "algorithmic_bytes_per_launch": bytes_per_coord * coords,
+                    "algorithmic_bytes_rule": "%d B x %d x %s" % (bytes_per_coord, N, format(d, ",")),
                     "note": "the kernel also holds the threshold estimate (sampling workgroups at the head of its grid)"}
 
     # ---- the oracle on the host: agreement over the whole sequence, then its speed on one step
@@ -463,6 +465,7 @@ def main():
         "step_hbm_frac_algorithmic": head["step_hbm_frac_algorithmic"],
         "step_hbm_frac_algorithmic_median": head["step_hbm_frac_algorithmic_median"],
         "copy_probe_GBs": round(copy_gbs, 1),
+        "copy_probe_bytes_each_way": copy_bytes_each_way,
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
         "oracle_agrees_on_sequence": oracle_agrees,

@@ -6,42 +6,56 @@
 // contraction, so no MFMA; the design goal is ONE streaming pass over g and e.
 //
 // How the per-worker top-K is found without re-reading the row:
-//   1. mv_sample_hist     histogram of the magnitude bit patterns of a strided
-//      mv_pick_threshold  sample of each row (cache-line sized chunks), turned
-//                         into a bin edge tau that about 2K coordinates of the
-//                         row exceed (an ESTIMATE, never trusted); also resets
-//                         the row's per-step counters
-//   2. mv_stream_collect  the streaming pass: a = g + e is written over e, and
-//                         every coordinate with |a| >= tau is appended to the
-//                         row's candidate list; each wavefront's 1024-coordinate
-//                         segment records where its run of candidates went
-//   3. mv_row_select      per row: EXACT select of the K-th largest magnitude
-//                         among the candidates (their number is known exactly;
-//                         if it is < K or overflowed the list, the row is
-//                         selected exactly from memory instead), and of the
-//                         largest coordinate taken among its ties.  Long lists
-//                         (large K) go through mv_sel_hist / mv_sel_split /
-//                         mv_sel_rank, many workgroups per row
-//   4. mv_row_votes       one thread per candidate: the taken ones cast their vote
-//   5. mv_mask_count /    counting-sort selection of the K most voted
-//      mv_mask_emit       coordinates, ties to the lowest coordinate.  Extra
-//                         workgroups of the same two launches write each row's
-//                         vote in ascending coordinate order (segment tallies
-//                         scanned, then one thread per candidate), off the
-//                         critical path
-//   6. mv_gather_update   masked gather, sum over workers in order, mean, and
-//                         the error update (zero on the mask)
-//   7. mv_ad_*            majority voting with add-drop (Algorithm 2): replaces
-//                         step 4 by the update of the workers' standing votes
-//   8. mv_rs_*            majority voting with random selection (Algorithm 1,
-//                         S_rand-weighted): replaces the mask of step 5
+//   1. mv_stream_collect  ONE launch holds the threshold estimate and the
+//                         streaming pass.  The first workgroups of the grid take
+//                         a histogram of the magnitude bit patterns of a strided
+//                         sample of each row; the last of a row's samplers turns
+//                         it into a bin edge tau that somewhat more than K
+//                         coordinates of the row exceed (an ESTIMATE, never
+//                         trusted) and publishes it.  The other workgroups
+//                         stream: a = g + e is written over e, and every
+//                         coordinate with |a| >= tau is appended to the row's
+//                         candidate list; each wavefront's 1024-coordinate
+//                         segment records where its run of candidates went.  A
+//                         streaming wavefront looks for its row's tau while its
+//                         loads are in flight and polls a bounded number of
+//                         times; a row whose wavefronts did not all see tau is
+//                         selected from memory instead
+//   2. mv_row_select      per row, a few workgroups: EXACT select of the K-th
+//                         largest magnitude among the candidates (their number
+//                         is known exactly; if it is < K or overflowed the list,
+//                         the row is selected exactly from memory instead) and of
+//                         the largest coordinate taken among its ties; then every
+//                         workgroup casts the votes of its share of the list.
+//                         Long lists (large K) go through mv_sel_hist /
+//                         mv_sel_split / mv_sel_rank and mv_row_votes, many
+//                         workgroups per row
+//   3. mv_mask_count      counting-sort selection of the K most voted
+//                         coordinates, ties to the lowest coordinate: the vote
+//                         threshold from the level counters, the counts of every
+//                         block of the vote bytes, their sums across blocks
+//                         (published between the workgroups), and the mask's
+//                         coordinates written in place.  Extra workgroups scan
+//                         the segment tallies for the sorted vote lists
+//   4. mv_gather_update   masked gather, sum over workers in order, mean, and
+//                         the error update (zero on the mask); extra workgroups
+//                         write each row's vote in ascending coordinate order
+//   5. mv_ad_*            majority voting with add-drop (Algorithm 2): replaces
+//                         the vote casting by the update of the workers'
+//                         standing votes
+//   6. mv_rs_*            majority voting with random selection (Algorithm 1,
+//                         S_rand-weighted): replaces the mask of step 3
 //
-// Two things measured on this machine shape much of the code: a returning
+// Things measured on this machine that shape much of the code: a returning
 // atomic completes only after the previous one on the same cache line (so
 // list space is reserved once per workgroup and hot counters sit on lines of
-// their own), and a load issued inside a divergent per-thread loop pays its
-// full latency every time (so sparse work is first compacted into LDS and then
-// fetched by all lanes together).
+// their own); a load issued inside a divergent per-thread loop pays its full
+// latency every time (so sparse work is first compacted into LDS and then
+// fetched by all lanes together); a kernel boundary costs about 2 us and a
+// small dependent kernel at least 4 us (so short steps share a launch, with
+// words published between workgroups where one step feeds the next); a
+// workgroup of 1024 threads has a compute unit to itself (so grids of the small
+// kernels are sized to one round of the chip's 256 units).
 #pragma once
 
 #include "mv_common.hpp"
