@@ -154,6 +154,34 @@ def test_add_drop_degenerate_rows(oracle):
         gs.close()
 
 
+def test_add_drop_with_infinite_magnitudes(oracle):
+    """Infinities order above every finite magnitude in the additions (largest first) and in the
+    removals (smallest first); at a coordinate all workers' infinities have one sign, so no NaN arises."""
+    N, d, K, k_ad = 3, 60001, 400, 40
+    say("add-drop infinities N=%d d=%d K=%d K_ad=%d" % (N, d, K, k_ad))
+    rng = np.random.default_rng(31)
+    sign = np.where(rng.integers(0, 2, size=d) == 1, np.float32(np.inf), np.float32(-np.inf))
+    gs = GpuAdStepper(N, d, K, K)
+    try:
+        vote = np.zeros((N, d), np.uint8)
+        msum = np.zeros(d, np.uint8)
+        e = np.zeros((N, d), np.float32)
+        for t, ka in enumerate([K, k_ad, k_ad, k_ad]):
+            g = rng.standard_normal((N, d)).astype(np.float32)
+            if t in (0, 2):                                   # new infinities while the standing votes move
+                hot = rng.choice(d, size=60, replace=False)
+                g[t % N, hot] = sign[hot]
+                g[(t + 1) % N, hot[:20]] = sign[hot[:20]]
+            gs.step(g, ka)
+            ref = oracle.ad_vote_step(g, e, K, ka, vote, msum)
+            assert not np.isnan(ref.err).any() and not np.isnan(ref.agg).any()
+            gs.compare(ref, "infinities step %d" % t)
+            vote, msum, e = ref.vote, ref.msum, ref.err
+        assert np.isinf(e).any() or np.isinf(ref.agg).any()
+    finally:
+        gs.close()
+
+
 def test_add_drop_needs_the_flag_and_valid_arguments():
     ctx = B.mv_begin(B.make_config(2, 1000, 10))
     dev = torch.device("cuda:0")

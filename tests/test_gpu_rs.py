@@ -89,6 +89,31 @@ def test_equal_times_go_to_the_lowest_coordinate(oracle, clocks):
         assert_matches_oracle(gs.fetch(), oracle.rs_vote_step(g, e, K, r), clocks)
 
 
+def test_random_selection_with_infinite_magnitudes(oracle):
+    """Infinite gradients only change who votes: the clocks are the caller's finite numbers."""
+    N, d, K = 4, 50003, 300
+    say("random selection, infinities N=%d d=%d K=%d" % (N, d, K))
+    rng = np.random.default_rng(32)
+    sign = np.where(rng.integers(0, 2, size=d) == 1, np.float32(np.inf), np.float32(-np.inf))
+    e = np.zeros((N, d), np.float32)
+    with GpuStepper(N, d, K) as gs:
+        gs.set_error(e)
+        for t in range(2):
+            g = rng.standard_normal((N, d)).astype(np.float32)
+            if t == 0:
+                hot = rng.choice(d, size=80, replace=False)
+                g[0, hot] = sign[hot]
+                g[3, hot[:30]] = sign[hot[:30]]
+            r = rng.exponential(size=d).astype(np.float32)
+            gs.set_grads(g)
+            gs.step_rs(r)
+            got = gs.fetch()
+            ref = oracle.rs_vote_step(g, e, K, r)
+            assert not np.isnan(ref.err).any() and not np.isnan(ref.agg).any()
+            assert_matches_oracle(got, ref, "random selection, infinities, step %d" % t)
+            e = ref.err
+
+
 def test_plain_and_random_steps_share_a_context(oracle):
     """The result of either kind of step does not depend on which kind ran before."""
     w = W.C2.with_size(210007, N=8)
