@@ -214,9 +214,12 @@ mv_status mv_set_profiling(mv_ctx* ctx, int32_t level);
  * Inside the streaming kernel the wavefronts of a row wait for the row's threshold
  * estimate, which other workgroups of the same launch publish; the wait is bounded by
  * `polls` looks at memory (default 2^20, about a second), after which the wavefront
- * gives up and the row is selected exactly from memory instead.  Results never depend
- * on it.  A test hook: 0 makes every wavefront that does not find the estimate at its
- * first look give up, which forces that path without any kernel waiting.
+ * gives up and the row is selected exactly from memory instead.  The same bound holds
+ * for the one other wait between workgroups: a block of the mask kernel waits for the
+ * counts of the blocks before it, and if it gives up the kernel behind it finds the
+ * mask from the counts instead.  Results never depend on the bound.  A test hook: 0
+ * makes every waiter that does not find what it needs at its first look give up, which
+ * forces both alternative paths without any kernel waiting.
  */
 mv_status mv_set_spin_limit(mv_ctx* ctx, uint32_t polls);
 
