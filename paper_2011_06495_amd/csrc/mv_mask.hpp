@@ -148,10 +148,11 @@ __device__ __forceinline__ void seg_scan_part(const uint32_t* __restrict__ ssel,
     __syncthreads();                              // the LDS scratch is free for the next part
 }
 
-// Workgroups [0, n_vote_blocks): count, per wavefront's stretch of 1024 Q coordinates, the
-// coordinates above and at the vote threshold; optionally copy the vote bytes to the
-// caller.  Workgroups beyond (only launched when the sorted vote lists are wanted): one
-// per row, scanning the row's segment tallies.
+// Workgroups [0, n_vote_blocks): count the block's coordinates above and at the vote
+// threshold (also per wavefront's stretch of 1024 Q coordinates), exchange the counts
+// with the other blocks and write the block's part of the mask; optionally copy the vote
+// bytes to the caller.  Workgroups beyond (only launched when the sorted vote lists are
+// wanted): one per row, scanning the row's segment tallies.
 template <int Q>
 __global__ __launch_bounds__(kMaskThreads) void mv_mask_count(const uint32_t* __restrict__ votes32,
                                                               int64_t d, uint32_t N, uint32_t K,
