@@ -505,20 +505,23 @@ mv_status enqueue_step(mv_ctx* c, const StepArgs& a, void* stream_v)
     before(KID_ROW_SELECT);
     {
         const uint32_t parts = votes_in_select ? p.select_parts : 1;
+        // (with the many-workgroup select this launch only serves rows that need the exact path from memory:
+        // nothing of the lists is fetched ahead)
+        const uint32_t n_spec = p.multi_select ? 0u : p.n_spec;
         const dim3 grid((p.N + 7) / 8 * 8 * parts);
         if (p.long_lists)
             hipLaunchKernelGGL(mvk::mv_row_select<mvk::kKeepLong>, grid, dim3(mvk::kRowThreads), 0, st, a.err, a.ld_e,
                                p.d, p.N, p.K, cand, p.cap, rowcnt_sets, rowcnt_set_words, stepno, taupub, poison, rowcnt,
                                tau, kth, tiecut,
                                a.worker_idx, votes32,
-                               sorted ? segsel : nullptr, p.nseg, lvlsets, slow, parts, p.n_spec, add_drop ? 1 : 0,
+                               sorted ? segsel : nullptr, p.nseg, lvlsets, slow, parts, n_spec, add_drop ? 1 : 0,
                                p.multi_select ? 1 : 0);
         else
             hipLaunchKernelGGL(mvk::mv_row_select<mvk::kKeepShort>, grid, dim3(mvk::kRowThreads), 0, st, a.err, a.ld_e,
                                p.d, p.N, p.K, cand, p.cap, rowcnt_sets, rowcnt_set_words, stepno, taupub, poison, rowcnt,
                                tau, kth, tiecut,
                                a.worker_idx, votes32,
-                               sorted ? segsel : nullptr, p.nseg, lvlsets, slow, parts, p.n_spec, add_drop ? 1 : 0,
+                               sorted ? segsel : nullptr, p.nseg, lvlsets, slow, parts, n_spec, add_drop ? 1 : 0,
                                p.multi_select ? 1 : 0);
     }
     after(KID_ROW_SELECT);

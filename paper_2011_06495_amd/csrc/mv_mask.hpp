@@ -31,7 +31,7 @@ __global__ __launch_bounds__(kRowThreads) void mv_row_votes(
     const uint32_t C = row_count[row];
     for (int i = threadIdx.x; i < 257; i += kRowThreads) lvl[i] = 0;
     __syncthreads();
-    cast_votes_of_share<kRowThreads>(cand + (size_t)row * cap, C, kth, tie_cut, blockIdx.x, gridDim.x, votes32, lvl,
+    cast_votes_of_share<kRowThreads, true>(cand + (size_t)row * cap, C, kth, tie_cut, blockIdx.x, gridDim.x, votes32, lvl,
                                      seg_sel ? seg_sel + (size_t)row * nseg : nullptr);
     __syncthreads();
     merge_levels(lvl, lvl_sets, blockIdx.y * gridDim.x + blockIdx.x);

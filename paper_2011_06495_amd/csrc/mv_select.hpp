@@ -466,7 +466,7 @@ __device__ __forceinline__ void select_among_candidates(const Keys& keys, const 
 // consecutive list entries, which mostly share a segment (they are one run): the
 // first lane of each group of equal segments adds the group's count.  All threads of
 // the workgroup must call it.
-template <int NT>
+template <int NT, bool MERGE>
 __device__ __forceinline__ void cast_votes_of_share(const u32x2* __restrict__ crow, uint32_t C, uint32_t kth,
                                                     uint32_t tie_cut, uint32_t part, uint32_t parts,
                                                     uint32_t* __restrict__ votes32, uint32_t* lvl,
@@ -484,15 +484,48 @@ __device__ __forceinline__ void cast_votes_of_share(const u32x2* __restrict__ cr
             const u32x2 none = {0u, 0xFFFFFFFFu};
             c[u] = (i < C) ? crow[i] : none;
         }
+        // MERGE (long lists, where the atomics' rate at the memory side is what the step waits for): lanes
+        // hold consecutive list entries, ascending inside a run, and a row votes at most once per
+        // coordinate, so neighbouring taken lanes whose coordinates share a vote word (four bytes) cast
+        // their votes with ONE atomic, the sum of their byte increments, issued by the first of them;
+        // the returned word holds every byte's count before this row's vote.  Where the mask is dense
+        // that is up to four votes per atomic (measured at K = d/100: 27 -> 19 us).  Short lists are
+        // sparse and wait for latency, not rate: there every taken lane issues its own.
         uint32_t old[kU];
         uint32_t taken_mask = 0;
+        uint32_t ahead[kU];                           // lanes between this lane and the first of its group
 #pragma unroll
         for (int u = 0; u < kU; ++u) {
-            old[u] = 0;
-            if (c[u].y != 0xFFFFFFFFu && is_taken(c[u], kth, tie_cut)) {
-                taken_mask |= 1u << u;
-                old[u] = atomicAdd(&votes32[c[u].y >> 2], 1u << ((c[u].y & 3u) * 8u));
+            const bool taken = c[u].y != 0xFFFFFFFFu && is_taken(c[u], kth, tie_cut);
+            if (taken) taken_mask |= 1u << u;
+            const uint32_t inc = taken ? 1u << ((c[u].y & 3u) * 8u) : 0u;
+            uint32_t before = 0;                      // lanes of the same group just below this one
+            uint32_t sum = inc;
+            if (MERGE) {
+                const uint32_t key = taken ? (c[u].y >> 2) : (0xFFFFFF00u | lane);   // never equal to a neighbour's
+                bool run = true;
+#pragma unroll
+                for (int k = 1; k < 4; ++k) {
+                    const uint32_t below = __shfl_up(key, k, kWave);
+                    run = run && lane >= (uint32_t)k && below == key;
+                    before += run ? 1u : 0u;
+                }
+                run = true;
+#pragma unroll
+                for (int k = 1; k < 4; ++k) {
+                    const uint32_t above_key = __shfl_down(key, k, kWave);
+                    const uint32_t above_inc = __shfl_down(inc, k, kWave);
+                    run = run && lane + (uint32_t)k < (uint32_t)kWave && above_key == key;
+                    sum += run ? above_inc : 0u;
+                }
             }
+            ahead[u] = before;
+            old[u] = 0;
+            if (taken && before == 0u) old[u] = atomicAdd(&votes32[c[u].y >> 2], sum);
+        }
+        if (MERGE) {
+#pragma unroll
+            for (int u = 0; u < kU; ++u) old[u] = __shfl(old[u], lane - ahead[u], kWave);   // the group's returned word
         }
 #pragma unroll
         for (int u = 0; u < kU; ++u) {
@@ -783,7 +816,7 @@ __global__ __launch_bounds__(kRowThreads) void mv_row_select(
         if (!thresholds_only) {
             for (int i = t; i < 257; i += kRowThreads) lds.lvl[i] = 0;
             __syncthreads();
-            cast_votes_of_share<kRowThreads>(crow, C, kth, tie_cut, part, parts, votes32, lds.lvl,
+            cast_votes_of_share<kRowThreads, false>(crow, C, kth, tie_cut, part, parts, votes32, lds.lvl,
                                              seg_sel ? seg_sel + (size_t)row * nseg : nullptr);
             __syncthreads();
             merge_levels(lds.lvl, lvl_sets, blockIdx.x);
