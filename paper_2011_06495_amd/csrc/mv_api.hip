@@ -634,8 +634,9 @@ mv_status enqueue_step(mv_ctx* c, const StepArgs& a, void* stream_v)
         uint8_t* votes_out = add_drop ? nullptr : a.votes;
         const float inv_n = 1.0f / (float)p.N;
         const uint32_t kb = mvk::kMaskThreads / p.N;
-        // up to four rounds of kb mask positions per workgroup, as few as keep the grid, with the sorted lists'
-        // workgroups, within one round of the chip (one workgroup of 1024 threads per compute unit)
+        // up to kGatherRounds rounds of kb mask positions per workgroup, as few as keep the grid, with the sorted
+        // lists' workgroups, within one round of the chip (one workgroup of 1024 threads per compute unit);
+        // longer workgroups than that measured slower than a second round of them
         const uint32_t eb = p.emit_blocks;
         const uint32_t n_list = lists ? p.N * eb : 0;
         const uint32_t room = n_list + 64 <= 250 ? 250 - n_list : 64;

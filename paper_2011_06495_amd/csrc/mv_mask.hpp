@@ -439,8 +439,8 @@ constexpr int kGatherRounds = 4;                  // at most this many rounds of
 struct GatherLds {
     float    tile[kMaskThreads + kMaskThreads / 2 + 8];
     uint32_t slice[kGatherRounds * kMaskThreads];              // the workgroup's positions' coordinates
-    uint32_t need[3 * (kGatherRounds * kMaskThreads + 2)];     // stretches to read: (stretch, above before, at before)
-    uint32_t blocks[3 * (kGatherRounds * kMaskThreads + 2)];   // blocks whose stretches are looked at
+    uint32_t need[3 * (kMaskThreads + 2)];                     // stretches to read: (stretch, above before, at before)
+    uint32_t blocks[3 * (kMaskThreads + 2)];                   // blocks whose stretches are looked at
     uint32_t n_need, n_blocks;
     uint32_t blk_pre[kMaxScanBlocks];
     uint64_t scan[kMaskThreads / kWave + 1];
@@ -491,94 +491,100 @@ __global__ __launch_bounds__(kMaskThreads) void mv_gather_update(float* __restri
 
     if (!mask_given && emit_fail[0] != 0u) {          // uniform over the grid; not expected
         const uint32_t vstar = vote_thr[0], take_eq = vote_thr[1];
-        if (t == 0) {
-            lds.n_need = 0;
-            lds.n_blocks = 0;
-        }
-        // position of a stretch's (a block's) first mask coordinate = (coordinates above the threshold
-        // before it) + min(coordinates at the threshold before it, take_eq)
-        auto reaches_in = [&](uint32_t g, uint32_t q, u32x2 c) {
-            const uint32_t q_taken = min(q, take_eq);                  // of the earlier ones at the threshold
-            const uint32_t first = g + q_taken;
-            const uint32_t n_in = c.x + min(c.y, take_eq - q_taken);
-            return n_in != 0u && first < k1 && first + n_in > k0;
-        };
-        // first level: the blocks' totals
-        uint32_t gt_before = 0, eq_before = 0;        // over the blocks of the earlier passes
-        for (uint32_t b0 = 0; b0 < n_blocks; b0 += kMaskThreads) {
-            const u32x2 none = {0u, 0u};
-            const u32x2 c = b0 + t < n_blocks ? block_cnt[b0 + t] : none;
-            uint64_t total;
-            const uint64_t ex = block_excl_scan64<kMaskThreads>(pack2(c.x, c.y), lds.scan, total);
-            const uint32_t g = gt_before + (uint32_t)(ex >> 32), q = eq_before + (uint32_t)ex;
-            if (reaches_in(g, q, c)) {
-                const uint32_t at = atomicAdd(&lds.n_blocks, 1u);
-                lds.blocks[3 * at + 0] = b0 + t;
-                lds.blocks[3 * at + 1] = g;
-                lds.blocks[3 * at + 2] = q;
+        // one round of at most kb <= 1024 positions [q0, q1) at a time: that bounds the lists in LDS
+        for (uint32_t r = 0; r < rounds; ++r) {
+            const uint32_t q0 = k0 + r * kb, q1 = min(k1, q0 + kb);
+            if (q0 >= q1) break;                          // uniform
+            if (t == 0) {
+                lds.n_need = 0;
+                lds.n_blocks = 0;
             }
-            gt_before += (uint32_t)(total >> 32);
-            eq_before += (uint32_t)total;
-            __syncthreads();                          // lds.scan is reused by the next pass
-            if (gt_before + min(eq_before, take_eq) >= k1) break;   // uniform: the rest lies behind this workgroup's positions
-        }
-        __syncthreads();
-        // second level: the stretches of those blocks (16 each), one wavefront per block
-        constexpr uint32_t kSubs = kMaskThreads / kWave;
-        const uint32_t n_blk = lds.n_blocks;
-        for (uint32_t i = wave; i < n_blk; i += kSubs) {
-            const uint32_t b = lds.blocks[3 * i];
-            const u32x2 none = {0u, 0u};
-            const u32x2 c = lane < kSubs ? sub_cnt[(size_t)b * kSubs + lane] : none;
-            const uint64_t both = pack2(c.x, c.y);
-            const uint64_t ex = wave_incl_scan64(both) - both;
-            const uint32_t g = lds.blocks[3 * i + 1] + (uint32_t)(ex >> 32), q = lds.blocks[3 * i + 2] + (uint32_t)ex;
-            if (lane < kSubs && reaches_in(g, q, c)) {
-                const uint32_t at = atomicAdd(&lds.n_need, 1u);
-                lds.need[3 * at + 0] = b * kSubs + lane;
-                lds.need[3 * at + 1] = g;
-                lds.need[3 * at + 2] = q;
+            // position of a stretch's (a block's) first mask coordinate = (coordinates above the threshold
+            // before it) + min(coordinates at the threshold before it, take_eq)
+            auto reaches_in = [&](uint32_t g, uint32_t q, u32x2 c) {
+                const uint32_t q_taken = min(q, take_eq);                  // of the earlier ones at the threshold
+                const uint32_t first = g + q_taken;
+                const uint32_t n_in = c.x + min(c.y, take_eq - q_taken);
+                return n_in != 0u && first < q1 && first + n_in > q0;
+            };
+            // first level: the blocks' totals
+            uint32_t gt_before = 0, eq_before = 0;        // over the blocks of the earlier passes
+            for (uint32_t b0 = 0; b0 < n_blocks; b0 += kMaskThreads) {
+                const u32x2 none = {0u, 0u};
+                const u32x2 c = b0 + t < n_blocks ? block_cnt[b0 + t] : none;
+                uint64_t total;
+                const uint64_t ex = block_excl_scan64<kMaskThreads>(pack2(c.x, c.y), lds.scan, total);
+                const uint32_t g = gt_before + (uint32_t)(ex >> 32), q = eq_before + (uint32_t)ex;
+                if (reaches_in(g, q, c)) {
+                    const uint32_t at = atomicAdd(&lds.n_blocks, 1u);
+                    lds.blocks[3 * at + 0] = b0 + t;
+                    lds.blocks[3 * at + 1] = g;
+                    lds.blocks[3 * at + 2] = q;
+                }
+                gt_before += (uint32_t)(total >> 32);
+                eq_before += (uint32_t)total;
+                __syncthreads();                          // lds.scan is reused by the next pass
+                if (gt_before + min(eq_before, take_eq) >= q1) break;   // uniform: the rest lies behind these positions
             }
-        }
-        __syncthreads();
-        // one wavefront per needed stretch: its 1024 Q vote bytes, lane l owning bytes [16 Q l, 16 Q l + 16 Q)
-        const uint32_t n_need = lds.n_need;
-        for (uint32_t i = wave; i < n_need; i += kSubs) {
-            const uint32_t sidx = lds.need[3 * i];
-            const int64_t j0 = ((int64_t)sidx * kWave + lane) * (16 * Q);
-            uint32_t ww[4 * Q];
-#pragma unroll
-            for (int q = 0; q < Q; ++q) {
-                const int64_t j = j0 + q * 16;
-                const u32x4 z = {0u, 0u, 0u, 0u};
-                const u32x4 w = (j < d) ? *reinterpret_cast<const u32x4*>(votes32 + (j >> 2)) : z;
-                ww[4 * q + 0] = w.x; ww[4 * q + 1] = w.y; ww[4 * q + 2] = w.z; ww[4 * q + 3] = w.w;
-            }
-            uint32_t gt, eq;
-            count_above_and_at<Q>(ww, j0, d, vstar, gt, eq);
-            const uint64_t both = pack2(gt, eq);
-            const uint64_t ex = wave_incl_scan64(both) - both;
-            uint32_t g0 = lds.need[3 * i + 1] + (uint32_t)(ex >> 32), e0 = lds.need[3 * i + 2] + (uint32_t)ex;
-#pragma unroll
-            for (int q = 0; q < 4 * Q; ++q) {
-                if (vstar != 0u && __ballot(ww[q] != 0u) == 0ull) continue;   // wave-uniform: no vote in this word
-#pragma unroll
-                for (int b = 0; b < 4; ++b) {
-                    const uint32_t v = (ww[q] >> (8 * b)) & 255u;
-                    const int64_t j = j0 + 4 * q + b;
-                    const bool inside = j < d;
-                    const bool is_gt = inside && v > vstar, is_eq = inside && v == vstar;
-                    if (is_gt || (is_eq && e0 < take_eq)) {
-                        const uint32_t pos = g0 + min(e0, take_eq);
-                        if (pos >= k0 && pos < k1) {
-                            lds.slice[pos - k0] = (uint32_t)j;
-                            mask_idx[pos] = (uint32_t)j;
-                        }
-                    }
-                    g0 += is_gt;
-                    e0 += is_eq;
+            __syncthreads();
+            // second level: the stretches of those blocks (16 each), one wavefront per block
+            constexpr uint32_t kSubs = kMaskThreads / kWave;
+            const uint32_t n_blk = lds.n_blocks;
+            for (uint32_t i = wave; i < n_blk; i += kSubs) {
+                const uint32_t b = lds.blocks[3 * i];
+                const u32x2 none = {0u, 0u};
+                const u32x2 c = lane < kSubs ? sub_cnt[(size_t)b * kSubs + lane] : none;
+                const uint64_t both = pack2(c.x, c.y);
+                const uint64_t ex = wave_incl_scan64(both) - both;
+                const uint32_t g = lds.blocks[3 * i + 1] + (uint32_t)(ex >> 32), q = lds.blocks[3 * i + 2] + (uint32_t)ex;
+                if (lane < kSubs && reaches_in(g, q, c)) {
+                    const uint32_t at = atomicAdd(&lds.n_need, 1u);
+                    lds.need[3 * at + 0] = b * kSubs + lane;
+                    lds.need[3 * at + 1] = g;
+                    lds.need[3 * at + 2] = q;
                 }
             }
+            __syncthreads();
+            // one wavefront per needed stretch: its 1024 Q vote bytes, lane l owning bytes [16 Q l, 16 Q l + 16 Q)
+            const uint32_t n_need = lds.n_need;
+            for (uint32_t i = wave; i < n_need; i += kSubs) {
+                const uint32_t sidx = lds.need[3 * i];
+                const int64_t j0 = ((int64_t)sidx * kWave + lane) * (16 * Q);
+                uint32_t ww[4 * Q];
+#pragma unroll
+                for (int q = 0; q < Q; ++q) {
+                    const int64_t j = j0 + q * 16;
+                    const u32x4 z = {0u, 0u, 0u, 0u};
+                    const u32x4 w = (j < d) ? *reinterpret_cast<const u32x4*>(votes32 + (j >> 2)) : z;
+                    ww[4 * q + 0] = w.x; ww[4 * q + 1] = w.y; ww[4 * q + 2] = w.z; ww[4 * q + 3] = w.w;
+                }
+                uint32_t gt, eq;
+                count_above_and_at<Q>(ww, j0, d, vstar, gt, eq);
+                const uint64_t both = pack2(gt, eq);
+                const uint64_t ex = wave_incl_scan64(both) - both;
+                uint32_t g0 = lds.need[3 * i + 1] + (uint32_t)(ex >> 32), e0 = lds.need[3 * i + 2] + (uint32_t)ex;
+#pragma unroll
+                for (int q = 0; q < 4 * Q; ++q) {
+                    if (vstar != 0u && __ballot(ww[q] != 0u) == 0ull) continue;   // wave-uniform: no vote in this word
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) {
+                        const uint32_t v = (ww[q] >> (8 * b)) & 255u;
+                        const int64_t j = j0 + 4 * q + b;
+                        const bool inside = j < d;
+                        const bool is_gt = inside && v > vstar, is_eq = inside && v == vstar;
+                        if (is_gt || (is_eq && e0 < take_eq)) {
+                            const uint32_t pos = g0 + min(e0, take_eq);
+                            if (pos >= q0 && pos < q1) {
+                                lds.slice[pos - k0] = (uint32_t)j;
+                                mask_idx[pos] = (uint32_t)j;
+                            }
+                        }
+                        g0 += is_gt;
+                        e0 += is_eq;
+                    }
+                }
+            }
+            __syncthreads();                          // the lists are reused by the next round
         }
     } else {
         for (uint32_t k = k0 + t; k < k1; k += kMaskThreads) lds.slice[k - k0] = mask_idx[k];

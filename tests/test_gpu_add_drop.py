@@ -81,10 +81,12 @@ class GpuAdStepper:
         B.mv_release(self.ctx)
 
 
-def run_ad_sequence(oracle, w, k_ads, threads=8):
+def run_ad_sequence(oracle, w, k_ads, threads=8, spin_limit=None):
     k_ad_max = max(k_ads)
     gs = GpuAdStepper(w.N, w.d, w.K, k_ad_max, bf16=(w.grad_dtype == "bf16"))
     try:
+        if spin_limit is not None:
+            B.mv_set_spin_limit(gs.ctx, spin_limit)
         vote = np.zeros((w.N, w.d), np.uint8)
         msum = np.zeros(w.d, np.uint8)
         e = W.zero_error(w)
@@ -107,6 +109,15 @@ def test_add_drop_reduced_workloads(oracle, name, d, N):
     # from the empty state: small steps first (the mask reaches into unvoted coordinates),
     # then a full vote, then the paper's regime phi_ad = phi / 10
     run_ad_sequence(oracle, w, [k_ad, k_ad, w.K, k_ad, k_ad, 1, k_ad])
+
+
+def test_add_drop_when_nothing_waits_for_anything(oracle):
+    """No polls allowed: rows whose threshold is not seen at the first look are selected from memory,
+    and the mask is found from the blocks' counts by the last kernel (with few votes standing, the
+    mask's vote level is 0 and reaches over many blocks).  Same results."""
+    w = W.C2.with_size(150007, N=6, K=300)
+    say("add-drop without polls N=%d d=%d K=%d" % (w.N, w.d, w.K))
+    run_ad_sequence(oracle, w, [30, 30, w.K, 30, 1], spin_limit=0)
 
 
 @pytest.mark.parametrize("d,K,N", [(1, 1, 1), (33, 5, 2), (1025, 40, 3), (4099, 4099, 2), (70001, 700, 4)])
