@@ -489,8 +489,8 @@ __device__ __forceinline__ void cast_votes_of_share(const u32x2* __restrict__ cr
         // coordinate, so neighbouring taken lanes whose coordinates share a vote word (four bytes) cast
         // their votes with ONE atomic, the sum of their byte increments, issued by the first of them;
         // the returned word holds every byte's count before this row's vote.  Where the mask is dense
-        // that is up to four votes per atomic (measured at K = d/100: 27 -> 19 us).  Short lists are
-        // sparse and wait for latency, not rate: there every taken lane issues its own.
+        // that is up to four votes per atomic (measured at K = d/100: 27 -> 19 us).  Short lists
+        // wait for latency, not rate: there every taken lane issues its own.
         uint32_t old[kU];
         uint32_t taken_mask = 0;
         uint32_t ahead[kU];                           // lanes between this lane and the first of its group
@@ -793,10 +793,21 @@ __global__ __launch_bounds__(kRowThreads) void mv_row_select(
                 constexpr int Q = decltype(qc)::value;
                 if ((uint32_t)Q < n_spec && (uint32_t)Q * kRowThreads < C) pack(qc, raw[Q]);
             });
-            static_for<0, KEEP>([&](auto qc) {
-                constexpr int Q = decltype(qc)::value;
-                if ((uint32_t)Q >= n_spec && (uint32_t)Q * kRowThreads < C)
-                    pack(qc, crow[min((uint32_t)Q * kRowThreads + t, cap - 1)].x);
+            // (sixteen loads at a time under one uniform test: a test per load would make each wait for
+            // the one before)
+            static_for<0, KEEP / 16>([&](auto gc) {
+                constexpr int G = decltype(gc)::value;
+                if ((uint32_t)(G * 16 + 15) >= n_spec && (uint32_t)(G * 16) * kRowThreads < C) {   // uniform
+                    uint32_t more[16];
+#pragma unroll
+                    for (int q = 0; q < 16; ++q)
+                        more[q] = crow[min((uint32_t)(G * 16 + q) * kRowThreads + t, cap - 1)].x;
+                    static_for<0, 16>([&](auto qc) {
+                        constexpr int Q = G * 16 + decltype(qc)::value;
+                        if ((uint32_t)Q >= n_spec && (uint32_t)Q * kRowThreads < C)
+                            pack(std::integral_constant<int, Q>{}, more[decltype(qc)::value]);
+                    });
+                }
             });
             done = select_from_bins<KEEP>(bins, crow, C, K, tau, lds, kth, tie_cut);
         }
@@ -816,7 +827,7 @@ __global__ __launch_bounds__(kRowThreads) void mv_row_select(
         if (!thresholds_only) {
             for (int i = t; i < 257; i += kRowThreads) lds.lvl[i] = 0;
             __syncthreads();
-            cast_votes_of_share<kRowThreads, false>(crow, C, kth, tie_cut, part, parts, votes32, lds.lvl,
+            cast_votes_of_share<kRowThreads, (KEEP > kKeepShort)>(crow, C, kth, tie_cut, part, parts, votes32, lds.lvl,
                                              seg_sel ? seg_sel + (size_t)row * nseg : nullptr);
             __syncthreads();
             merge_levels(lds.lvl, lvl_sets, blockIdx.x);
