@@ -793,15 +793,18 @@ __global__ __launch_bounds__(kRowThreads) void mv_row_select(
                 constexpr int Q = decltype(qc)::value;
                 if ((uint32_t)Q < n_spec && (uint32_t)Q * kRowThreads < C) pack(qc, raw[Q]);
             });
-            // (sixteen loads at a time under one uniform test: a test per load would make each wait for
-            // the one before)
+            // (sixteen loads at a time, all issued before the first is used: used one by one, each load
+            // would wait for the one before)
             static_for<0, KEEP / 16>([&](auto gc) {
                 constexpr int G = decltype(gc)::value;
                 if ((uint32_t)(G * 16 + 15) >= n_spec && (uint32_t)(G * 16) * kRowThreads < C) {   // uniform
                     uint32_t more[16];
 #pragma unroll
-                    for (int q = 0; q < 16; ++q)
-                        more[q] = crow[min((uint32_t)(G * 16 + q) * kRowThreads + t, cap - 1)].x;
+                    for (int q = 0; q < 16; ++q) {
+                        more[q] = 0;
+                        if ((uint32_t)(G * 16 + q) >= n_spec && (uint32_t)(G * 16 + q) * kRowThreads < C)   // uniform
+                            more[q] = crow[min((uint32_t)(G * 16 + q) * kRowThreads + t, cap - 1)].x;
+                    }
                     static_for<0, 16>([&](auto qc) {
                         constexpr int Q = G * 16 + decltype(qc)::value;
                         if ((uint32_t)Q >= n_spec && (uint32_t)Q * kRowThreads < C)
