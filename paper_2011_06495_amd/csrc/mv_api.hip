@@ -154,7 +154,7 @@ Plan make_plan(const mv_config* c)
     p.rs_blocks = (uint32_t)((p.d + mvk::kVoteBlock - 1) / mvk::kVoteBlock);
     {
         // the mask kernels: as few vote bytes per thread as keep the grid, with one more workgroup per row for
-        // the segment scans, within one round of the chip (one workgroup of 1024 threads per compute unit)
+        // the segment scans, at about one workgroup per compute unit
         static const uint32_t kQs[] = {1, 2, 3, 4, 6, 8};
         uint32_t q = 8;
         for (uint32_t cand_q : kQs)
@@ -190,7 +190,7 @@ Plan make_plan(const mv_config* c)
         p.n_spec = (uint32_t)(slots < (uint64_t)mvk::kSpec ? slots : (uint64_t)mvk::kSpec);
         uint64_t parts = (slots + 3) / 4;
         if (parts > 16) parts = 16;
-        if (parts * p.N > 240) parts = 240 / p.N;      // all of a step's workgroups at once: one per compute unit
+        if (parts * p.N > 240) parts = 240 / p.N;      // all at once: with its registers a workgroup has a unit to itself
         if (parts < 1) parts = 1;
         p.select_parts = (uint32_t)parts;
         // beyond what one workgroup keeps in registers the lists go through the many-workgroup select
@@ -635,7 +635,7 @@ mv_status enqueue_step(mv_ctx* c, const StepArgs& a, void* stream_v)
         const float inv_n = 1.0f / (float)p.N;
         const uint32_t kb = mvk::kMaskThreads / p.N;
         // up to kGatherRounds rounds of kb mask positions per workgroup, as few as keep the grid, with the sorted
-        // lists' workgroups, within one round of the chip (one workgroup of 1024 threads per compute unit);
+        // lists' workgroups, at about one workgroup per compute unit (two of these fit a unit);
         // longer workgroups than that measured slower than a second round of them
         const uint32_t eb = p.emit_blocks;
         const uint32_t n_list = lists ? p.N * eb : 0;

@@ -54,8 +54,9 @@
 // fetched by all lanes together); a kernel boundary costs about 2 us and a
 // small dependent kernel at least 4 us (so short steps share a launch, with
 // words published between workgroups where one step feeds the next); a
-// workgroup of 1024 threads has a compute unit to itself (so grids of the small
-// kernels are sized to one round of the chip's 256 units).
+// workgroup of 1024 threads with more than 64 VGPRs or more than 80 KB of LDS has
+// a compute unit to itself, two fit otherwise (so the grids of the small kernels
+// are sized to about one workgroup per each of the chip's 256 units).
 #pragma once
 
 #include "mv_common.hpp"
