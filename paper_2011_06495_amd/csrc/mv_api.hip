@@ -154,11 +154,13 @@ Plan make_plan(const mv_config* c)
     p.rs_blocks = (uint32_t)((p.d + mvk::kVoteBlock - 1) / mvk::kVoteBlock);
     {
         // the mask kernels: as few vote bytes per thread as keep the grid, with one more workgroup per row for
-        // the segment scans, at about one workgroup per compute unit
+        // the segment scans, at two workgroups per compute unit: all resident at once, which the exchange of
+        // counts between the blocks likes (measured: a limit of 500 beats 250 by 3 us on C4 and 13 us on C5;
+        // 750 and more lose again on d = 11 M)
         static const uint32_t kQs[] = {1, 2, 3, 4, 6, 8};
         uint32_t q = 8;
         for (uint32_t cand_q : kQs)
-            if ((uint64_t)p.d <= (uint64_t)(250 - (p.N < 128 ? p.N : 128)) * mvk::kMaskThreads * 16 * cand_q) {
+            if ((uint64_t)p.d <= (uint64_t)(500 - (p.N < 128 ? p.N : 128)) * mvk::kMaskThreads * 16 * cand_q) {
                 q = cand_q;
                 break;
             }
@@ -634,15 +636,20 @@ mv_status enqueue_step(mv_ctx* c, const StepArgs& a, void* stream_v)
         uint8_t* votes_out = add_drop ? nullptr : a.votes;
         const float inv_n = 1.0f / (float)p.N;
         const uint32_t kb = mvk::kMaskThreads / p.N;
-        // up to kGatherRounds rounds of kb mask positions per workgroup, as few as keep the grid, with the sorted
-        // lists' workgroups, at about one workgroup per compute unit (two of these fit a unit);
-        // longer workgroups than that measured slower than a second round of them
+        // Up to kGatherRounds rounds of kb mask positions per gathering workgroup.  When one or two rounds keep
+        // the grid, with the sorted lists' workgroups, at about one workgroup per compute unit, that is best
+        // (C4: 216 workgroups); when they do not (large K, many rows), many short workgroups beat few long
+        // ones: two rounds and a grid of up to a thousand measured 4 us faster at K = d/100 than four rounds.
         const uint32_t eb = p.emit_blocks;
         const uint32_t n_list = lists ? p.N * eb : 0;
-        const uint32_t room = n_list + 64 <= 250 ? 250 - n_list : 64;
-        uint32_t rounds = (uint32_t)(((uint64_t)p.K + (uint64_t)room * kb - 1) / ((uint64_t)room * kb));
-        if (rounds > (uint32_t)mvk::kGatherRounds) rounds = mvk::kGatherRounds;
-        if (rounds < 1) rounds = 1;
+        auto rounds_for = [&](uint32_t limit) {
+            const uint32_t room = n_list + 64 <= limit ? limit - n_list : 64;
+            uint32_t r = (uint32_t)(((uint64_t)p.K + (uint64_t)room * kb - 1) / ((uint64_t)room * kb));
+            if (r > (uint32_t)mvk::kGatherRounds) r = mvk::kGatherRounds;
+            return r < 1 ? 1u : r;
+        };
+        uint32_t rounds = rounds_for(250);
+        if (rounds > 2) rounds = rounds_for(1000);
         const uint32_t n_gather = (p.K + kb * rounds - 1) / (kb * rounds);
         const dim3 grid_g(n_gather + n_list);
 #define MV_LAUNCH_MASK(Q)                                                                                        \
