@@ -156,6 +156,11 @@ def test_random_selection_c4_full(oracle):
 
 
 @pytest.mark.timeout(1200)
+def test_random_selection_c5_full_bf16(oracle):
+    run_full_rs(oracle, W.C5, 2)
+
+
+@pytest.mark.timeout(1200)
 def test_random_selection_paper_regime_full(oracle):
     # ResNet-18 size, N = 10 workers, phi = 1e-2 (Sec. 4.1, 4.2)
     w = W.C2.with_size(W.C2.d, K=111740)
